@@ -1,0 +1,256 @@
+"""Plain CPU definitions of the five overlapped operators (test infrastructure only).
+
+Overlap changes *when* tiles are computed, never *what* is computed, so each
+operator below is the plain definition of its result written out with numpy in
+float64: an explicit gather (concatenate), one matrix product, an explicit
+sum over ranks, explicit top-k routing, explicit softmax attention.  The only
+roundings are the ones the data types of the layer force: every tensor that
+exists in memory in the real layer is bfloat16 (round to nearest even).
+
+bf16 tensors are numpy uint16 bit patterns.  Functions return both the rounded
+bf16 result and the unrounded float64 one.
+
+Operator definitions follow the paper's "Communication and Intra-Layer
+Parallelism" section (tensor-parallel FFN = AllGather+GEMM then
+GEMM+ReduceScatter; sequence-parallel attention = AllGather of K/V then local
+attention), its "Kernel Design" section (GEMM+RS, AG+MoE, AG-KV+attention) and
+the MoE paragraph of its evaluation (AG+Gather+GroupGEMM and
+GroupGEMM+Scatter+TopkReduce+RS).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .bf16 import round_to_bf16, widen
+
+
+# ---------------------------------------------------------------------------
+# AllGather + GEMM   (tensor-parallel FFN, first half)
+# ---------------------------------------------------------------------------
+
+def all_gather_rows(shards):
+    """Explicit AllGather along the first axis: rank order concatenation."""
+    return np.concatenate([np.asarray(s) for s in shards], axis=0)
+
+
+def ag_gemm(a_shards, b):
+    """C = AllGather_M(A_shards) . B with B given as [K, N].
+
+    Returns (gathered A bits [M,K], C float64 [M,N], C bf16 bits [M,N])."""
+    a = all_gather_rows(a_shards)
+    c = widen(a) @ widen(b)
+    return a, c, round_to_bf16(c)
+
+
+# ---------------------------------------------------------------------------
+# GEMM + ReduceScatter   (tensor-parallel FFN, second half)
+# ---------------------------------------------------------------------------
+
+def reduce_scatter_segment(own_segment_bits, peer_segments, rank):
+    """Sum over ranks q = 0..R-1 of the rows of partial q that belong to `rank`.
+    `peer_segments[q]` is [M/R, N] bf16 (entry `rank` is ignored, the local
+    partial's own rows are `own_segment_bits`)."""
+    total = np.zeros(own_segment_bits.shape, dtype=np.float64)
+    for q in range(len(peer_segments)):
+        total += widen(own_segment_bits if q == rank else peer_segments[q])
+    return total
+
+
+def gemm_rs(a, b, peer_segments, rank):
+    """P = bf16(A . B) (the local partial, stored as a tensor of the layer's
+    dtype); out = bf16( sum_q P_q[rows of segment `rank`] ).
+
+    Returns (P bits [M,N], out float64 [M/R,N], out bf16 bits)."""
+    R = len(peer_segments)
+    p = round_to_bf16(widen(a) @ widen(b))
+    seg = p.shape[0] // R
+    own = p[rank * seg:(rank + 1) * seg]
+    out = reduce_scatter_segment(own, peer_segments, rank)
+    return p, out, round_to_bf16(out)
+
+
+# ---------------------------------------------------------------------------
+# MoE routing -> dynamic mapping tables
+# ---------------------------------------------------------------------------
+
+def moe_route(logits, topk, renormalize=True):
+    """Top-k routing of every token.
+
+    The k experts of a token are those with the k largest gate logits (softmax
+    is monotonic, so this equals the k largest probabilities); equal logits go
+    to the lower expert index; experts are listed by descending logit.  The
+    routing weight is the softmax probability over all E experts, divided by
+    the sum over the selected k when `renormalize`.
+
+    Returns (topk_ids [T,k] int32, topk_w [T,k] float64)."""
+    logits = np.asarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    ids = np.zeros((T, topk), dtype=np.int32)
+    for t in range(T):
+        row = logits[t]
+        # sort by (-logit, index): python's sort is stable and exact on float32 values
+        order = sorted(range(E), key=lambda e: (-float(row[e]), e))
+        ids[t] = order[:topk]
+    x = logits.astype(np.float64)
+    x = x - x.max(axis=1, keepdims=True)
+    p = np.exp(x)
+    p /= p.sum(axis=1, keepdims=True)
+    w = np.take_along_axis(p, ids.astype(np.int64), axis=1)
+    if renormalize:
+        w = w / w.sum(axis=1, keepdims=True)
+    return ids, w
+
+
+def moe_sort_rows(topk_ids, E):
+    """Routed row (t, j) has id t*k + j and expert topk_ids[t, j].  Rows are put
+    in expert order, ascending row id inside an expert (a stable counting sort).
+
+    Returns (expert_count [E], expert_offset [E+1], sorted_row [T*k]) int32."""
+    T, k = topk_ids.shape
+    flat = topk_ids.reshape(-1)
+    count = np.zeros(E, dtype=np.int32)
+    for e in flat:
+        count[e] += 1
+    offset = np.zeros(E + 1, dtype=np.int32)
+    for e in range(E):
+        offset[e + 1] = offset[e] + count[e]
+    cursor = offset[:-1].copy()
+    sorted_row = np.zeros(T * k, dtype=np.int32)
+    for row in range(T * k):
+        e = flat[row]
+        sorted_row[cursor[e]] = row
+        cursor[e] += 1
+    return count, offset, sorted_row
+
+
+def moe_tile_tables(expert_offset, sorted_row, T, topk, R, C, Tm):
+    """Dynamic mapping tables, one row of 8 int32 per grouped-GEMM row tile:
+    (f_S_low, f_S_high, expert, chan_mask_lo, chan_mask_hi, f_R_lo, f_R_hi, 0).
+
+    Expert e owns ceil(count[e]/Tm) tiles over its run of sorted rows; the last
+    one is short.  chan_mask has bit (rank*C + local channel) set for every
+    AllGather channel that holds a token of the tile (bits 0..31 in _lo, 32..63
+    in _hi); f_R_lo..f_R_hi is the span of source ranks."""
+    E = len(expert_offset) - 1
+    tokens_per_rank = T // R
+    tokens_per_channel = tokens_per_rank // C
+    rows = []
+    for e in range(E):
+        lo = int(expert_offset[e])
+        end = int(expert_offset[e + 1])
+        while lo < end:
+            hi = min(lo + Tm, end)
+            mask = 0
+            ranks = []
+            for s in range(lo, hi):
+                token = int(sorted_row[s]) // topk
+                mask |= 1 << (token // tokens_per_channel)
+                ranks.append(token // tokens_per_rank)
+            lo32 = mask & 0xFFFFFFFF
+            hi32 = (mask >> 32) & 0xFFFFFFFF
+            to_i32 = lambda v: v - (1 << 32) if v >= (1 << 31) else v
+            rows.append((lo, hi, e, to_i32(lo32), to_i32(hi32), min(ranks), max(ranks), 0))
+            lo = hi
+    return np.array(rows, dtype=np.int32).reshape(-1, 8)
+
+
+# ---------------------------------------------------------------------------
+# MoE part 1: AllGather + Gather + GroupGEMM
+# ---------------------------------------------------------------------------
+
+def moe_ag_gather_gemm(x_shards, w1, sorted_row, expert_offset, topk):
+    """Y1[s, :] = bf16( X[token(s), :] . W1[expert(s)] ) for every sorted row s,
+    X = AllGather of the token shards, token(s) = sorted_row[s] // topk.
+
+    Returns (gathered X bits, Y1 float64 [T*k, I], Y1 bf16 bits)."""
+    x = all_gather_rows(x_shards)
+    xf = widen(x)
+    E, H, I = w1.shape
+    y = np.zeros((len(sorted_row), I), dtype=np.float64)
+    for e in range(E):
+        lo, hi = int(expert_offset[e]), int(expert_offset[e + 1])
+        if hi > lo:
+            tokens = np.asarray(sorted_row[lo:hi], dtype=np.int64) // topk
+            y[lo:hi] = xf[tokens] @ widen(w1[e])
+    return x, y, round_to_bf16(y)
+
+
+# ---------------------------------------------------------------------------
+# MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter
+# ---------------------------------------------------------------------------
+
+def moe_gemm_scatter_rs(x2, w2, sorted_row, expert_offset, topk_w, peer_segments, rank):
+    """Z[s,:] = bf16( w[row(s)] * (X2[s,:] . W2[expert(s)]) ), stored at
+    scatter_buf[sorted_row[s], :] (row id = token*k + slot);
+    partial[t,:] = bf16( sum_j scatter_buf[t*k + j, :] );
+    out = bf16( sum over ranks of the partial rows of segment `rank` ).
+
+    Returns (scatter_buf bits [T*k,H], partial bits [T,H], out float64, out bits)."""
+    E, I, H = w2.shape
+    n_rows = len(sorted_row)
+    T, k = topk_w.shape
+    w_flat = np.asarray(topk_w, dtype=np.float64).reshape(-1)
+    x2f = widen(x2)
+    scatter = np.zeros((n_rows, H), dtype=np.uint16)
+    for e in range(E):
+        lo, hi = int(expert_offset[e]), int(expert_offset[e + 1])
+        if hi > lo:
+            rows = np.asarray(sorted_row[lo:hi], dtype=np.int64)
+            z = (x2f[lo:hi] @ widen(w2[e])) * w_flat[rows][:, None]
+            scatter[rows] = round_to_bf16(z)
+    partial_f = widen(scatter).reshape(T, k, H).sum(axis=1)
+    partial = round_to_bf16(partial_f)
+    R = len(peer_segments)
+    seg = T // R
+    out = reduce_scatter_segment(partial[rank * seg:(rank + 1) * seg], peer_segments, rank)
+    return scatter, partial, out, round_to_bf16(out)
+
+
+# ---------------------------------------------------------------------------
+# Sequence-parallel attention: AllGather K/V + softmax attention
+# ---------------------------------------------------------------------------
+
+def sp_ag_attention(q, k_shards, v_shards, rank, causal=True, scale=None, heads=None, rows=None):
+    """O[i,h,:] = sum_j softmax_j(scale * <Q[i,h,:], K[j,h,:]>) V[j,h,:], with K, V
+    the row-concatenation of all ranks' shards and, when causal, j restricted to
+    j <= g where g = rank * S/R + i is the query's global position.
+
+    `heads` / `rows` restrict the computation to some heads / local query rows
+    (for sampled checks at full size).  Returns (K bits, V bits, O float64
+    [len(rows), len(heads), D], O bf16 bits)."""
+    k = all_gather_rows(k_shards)
+    v = all_gather_rows(v_shards)
+    S_loc, Hd, D = q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    heads = list(range(Hd)) if heads is None else list(heads)
+    rows = np.arange(S_loc) if rows is None else np.asarray(rows, dtype=np.int64)
+    out = np.zeros((len(rows), len(heads), D), dtype=np.float64)
+    g = rank * S_loc + rows                                    # global positions
+    for hi, h in enumerate(heads):
+        qh = widen(q[rows, h, :])
+        kh = widen(k[:, h, :])
+        vh = widen(v[:, h, :])
+        for blk in range(0, len(rows), 256):
+            sl = slice(blk, min(blk + 256, len(rows)))
+            s = (qh[sl] @ kh.T) * scale
+            if causal:
+                s = np.where(np.arange(k.shape[0])[None, :] <= g[sl][:, None], s, -np.inf)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            out[sl, hi, :] = (p @ vh) / p.sum(axis=1, keepdims=True)
+    return k, v, out, round_to_bf16(out)
+
+
+# ---------------------------------------------------------------------------
+# Error measures used by the parity tests
+# ---------------------------------------------------------------------------
+
+def rel_frobenius(got_bits, ref_bits):
+    g, r = widen(got_bits), widen(ref_bits)
+    return float(np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-300))
+
+
+def max_abs_over_max_ref(got_bits, ref_bits):
+    g, r = widen(got_bits), widen(ref_bits)
+    return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-300))
