@@ -1,0 +1,167 @@
+/*
+ * tilelink_mi355 — tile-centric overlapped tensor-parallel operators for one MI355X (gfx950).
+ *
+ * C ABI.  Every operator is one GPU's share of a tensor-parallel layer over `world_size`
+ * ranks: the other ranks' shards and partial results are ordinary device buffers the caller
+ * has filled (there is no second GPU and no collective library involved).
+ *
+ * Conventions that hold for every entry point
+ *   - Return value: TL_OK (0) or a negative tl_status.  tl_last_error() returns a
+ *     thread-local, human-readable description of the most recent failure.
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees caller memory and allocates no device
+ *     memory in an operator call.
+ *   - bf16 tensors are row-major arrays of 16-bit bfloat16; all leading dimensions are
+ *     dense (no padding between rows).
+ *   - Calls are asynchronous: work is enqueued on the caller's streams (hipStream_t passed
+ *     as void*; NULL = the default stream) and the caller synchronises.  Arguments are
+ *     validated before anything is enqueued.
+ *   - Barrier flags are `unsigned` counters in device memory that only ever grow.  The
+ *     caller zeroes them once; call number `epoch` (1, 2, 3, ...) waits for
+ *     `epoch * expected`, so no reset is needed between calls.  Reusing a flag array for
+ *     a call with a different geometry requires zeroing it again.
+ *   - A bounded wait that expires (tl_config.spin_timeout_us) writes a non-zero code into
+ *     the first word of the workspace and lets the kernel finish with undefined output;
+ *     tl_check_status() reports it as TL_ERR_TIMEOUT.
+ *
+ * Notation follows the paper: R = world size, r = rank, C = channels (barriers) per rank,
+ * producer tile Tm_p x Tn_p, consumer (compute) tile Tm_c x Tn_c.
+ */
+#ifndef TILELINK_MI355_H
+#define TILELINK_MI355_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tl_status {
+  TL_OK = 0,
+  TL_ERR_INVALID_ARG = -1,       /* null pointer, non-positive size, rank outside [0,R) ... */
+  TL_ERR_UNSUPPORTED_SHAPE = -2, /* a divisibility rule of the mapping or of the kernel is violated */
+  TL_ERR_WORKSPACE_TOO_SMALL = -3,
+  TL_ERR_HIP = -4,               /* a HIP runtime call failed; message holds hipGetErrorString */
+  TL_ERR_TIMEOUT = -5            /* a bounded flag wait expired (reported by tl_check_status) */
+} tl_status;
+
+/* Resource binding of the communication side (paper: "Decoupled Design Space"). */
+enum { TL_COMM_NONE = 0,   /* data already in place: no producer runs, consumers do not wait */
+       TL_COMM_WAVES = 1,  /* device-side: dedicated copy/reduce workgroups inside the fused kernel
+                              (tile_pull_data / tile_push_data + *_tile_notify) */
+       TL_COMM_STREAM = 2, /* host-side: copies and notifications enqueued on comm_stream through the runtime's
+                              copy path (rank_copy_data + rank_notify); reduce work runs as a second kernel there */
+       TL_COMM_SIDE_KERNEL = 3, /* device-side copy/reduce workgroups launched as a small-footprint kernel of their
+                              own on comm_stream, so that they can share compute units with resident GEMM workgroups */
+       TL_COMM_ONLY = 4,   /* communication side alone (no GEMM tiles, producer-consumer waits skipped): for timing */
+       TL_COMM_EXTERNAL = 5 /* consumers wait on the flags but the library runs no producer: the caller (a peer,
+                              another library) moves the data and raises the flags itself */ };
+
+/* Tile order of the compute side. */
+enum { TL_ORDER_NATURAL = 0, /* row-major over (row block, column block) */
+       TL_ORDER_RING = 1     /* row blocks rotated by owner rank: AG+GEMM starts with the local
+                                shard's rows, GEMM+RS starts with rank r+1's segment and ends with its own */ };
+
+/* Operators, for tl_query_workspace / tl_dump_schedule. */
+enum { TL_OP_AG_GEMM = 0, TL_OP_GEMM_RS = 1, TL_OP_MOE_AG_GATHER_GEMM = 2, TL_OP_MOE_GEMM_SCATTER_RS = 3,
+       TL_OP_SP_AG_ATTENTION = 4 };
+
+/* The mapping context (the paper's BlockChannel: rank, world size, barrier configuration,
+ * producer/consumer tile relationship) plus the free choices of the decoupled design space.
+ * A field set to 0 selects the library default for the shape at hand. */
+typedef struct tl_config {
+  int world_size;          /* R >= 1 */
+  int rank;                /* r in [0, R) */
+  int channels_per_rank;   /* C >= 1; barriers per source rank */
+  int tile_m, tile_n;      /* consumer tile Tm_c x Tn_c; supported pairs: 256x256, 256x224, 128x128 (0 = auto) */
+  int comm_tile_m;         /* producer row-tile Tm_p (AllGather) / reduce row-tile (ReduceScatter); 0 = auto */
+  int comm_tile_n;         /* producer column-tile Tn_p; 0 = whole row */
+  int comm_mode;           /* TL_COMM_* */
+  int comm_workgroups;     /* workgroups given to communication in TL_COMM_WAVES (paper's examples: 20 SMs); 0 = auto */
+  int compute_workgroups;  /* persistent compute workgroups G; 0 = number of compute units */
+  int tile_order;          /* TL_ORDER_* */
+  int xcd_swizzle;         /* 1: workgroups on one die take neighbouring tiles (see tl_dump_schedule) */
+  unsigned spin_timeout_us;/* bound on every flag wait; 0 = unbounded */
+} tl_config;
+
+typedef struct tl_ctx tl_ctx;
+
+/* Creates a context for the current HIP device from *cfg (copied).  Host call. */
+int tl_ctx_create(const tl_config* cfg /*host*/, tl_ctx** out /*host*/);
+int tl_ctx_destroy(tl_ctx* ctx);
+const char* tl_last_error(void);
+/* Library version string and the offload architecture it was built for. */
+const char* tl_version(void);
+
+/* Bytes of workspace and number of flag words operator `op` needs for `dims`
+ * (AG_GEMM, GEMM_RS: {M,N,K}; MoE: {T,H,I,E,topk}; attention: {S,heads,head_dim}).  Host call, no GPU work. */
+int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims /*host*/, size_t* ws_bytes /*host*/,
+                       size_t* n_flags /*host*/);
+
+/* Synchronous: copies the status word out of `workspace` (after the caller synchronised the
+ * streams) and returns TL_OK or TL_ERR_TIMEOUT; clears the word. */
+int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
+
+/*
+ * AllGather + GEMM (paper: "Tile-Centric Mapping", AllGather pull mode + GEMM; tensor-parallel
+ * FFN first half).  C[M,N] = concat_rows(a_shards[0..R-1])[M,K] . B[K,N], fp32 accumulation,
+ * bf16 output rounded to nearest even.
+ *   a_shards   host array of R dev pointers, shard q = rows [q*M/R, (q+1)*M/R) of A, each [M/R, K] bf16.
+ *              If a_shards[r] == a_gathered + r*(M/R)*K the local shard is taken in place.
+ *   a_gathered dev [M,K] bf16: written by the producer, read by the GEMM tiles.
+ *   b          dev [K,N] bf16.           c  dev [M,N] bf16 (written).
+ *   flags      dev unsigned[R*C]; channel index = src_rank*C + local channel (the global index of the
+ *              paper's channel formula).  After call `epoch` every entry equals epoch * expected where
+ *              expected = (M/(R*C)/Tm_p) * ceil(K/Tn_p) in WAVES mode and 1 in STREAM mode; untouched in NONE.
+ *   Requirements: R | M, C | M/R, Tm_p | M/(R*C), K % 64 == 0, N % 8 == 0, Tn_p | K.
+ *   compute_stream receives the fused kernel; comm_stream the copies in TL_COMM_STREAM.
+ */
+int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards /*host array of dev*/, void* a_gathered, const void* b,
+               void* c, int M, int N, int K, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/,
+               size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/*
+ * GEMM + ReduceScatter (paper: "Kernel Design", GEMM + ReduceScatter; evaluation: scatter by
+ * copy, reduction on compute cores).  partial[M,N] = bf16(A[M,K] . B[K,N]) is stored locally and each
+ * GEMM tile notifies the reduce tiles it covers.  A reduce tile whose rows lie in this rank's segment
+ * [r*M/R, (r+1)*M/R) waits for every peer, sums the R bf16 inputs in fp32 (rank order) and stores bf16
+ * to `out`; a reduce tile of segment q != r is pushed into peer_push[q] and peer q is notified.
+ *   peer_recv  host array of R dev pointers; entry q != r is what peer q pushed to this rank, [M/R, N] bf16
+ *              (seeded by the caller); entry r ignored.
+ *   peer_push  host array of R dev pointers; entry q != r is the landing zone of this rank's partial rows of
+ *              segment q, [M/R, N] bf16 (written); entry r ignored.
+ *   out        dev [M/R, N] bf16 (written).
+ *   flags      dev unsigned[n_flags] from tl_query_workspace: first the reduce-tile ready counters
+ *              (row-major over reduce tiles; +1 per covering GEMM tile), then R*(reduce tiles per segment)
+ *              peer-arrival counters (peer-major; entry for peer q counts q's pushes into this rank, raised by
+ *              the library's simulated peers), then the same number of pushed counters (this rank's pushes
+ *              into peer q).  Each grows by its expected count per call.
+ *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 64 == 0, N % 8 == 0.
+ */
+int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv /*host array of dev*/,
+               void* const* peer_push /*host array of dev*/, void* out, int M, int N, int K, unsigned* flags /*dev*/,
+               unsigned epoch, void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/*
+ * Schedule dump for bit-exact checks (host call, no GPU work).  Writes int records in schedule order
+ * (position p is taken by persistent workgroup p % G in its round p / G):
+ *   TL_OP_AG_GEMM : 8 ints per consumer tile: tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0
+ *   TL_OP_GEMM_RS : 9 ints per GEMM tile: tile_id, bm, bn, row_lo, row_hi, cm_lo, cm_hi, cn_lo, cn_hi
+ *                   (inclusive ranges of reduce tiles notified), followed by 9 ints per reduce tile in the
+ *                   order the reduce workgroups visit them: rs_tile_id, cm, cn, row_lo, row_hi, col_lo, col_hi,
+ *                   dest_rank, expected.
+ * `cap` = capacity of `out` in ints; *n = ints needed (written even when cap is too small, then
+ * TL_ERR_WORKSPACE_TOO_SMALL is returned).
+ */
+int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* out /*host*/, size_t cap,
+                     size_t* n /*host*/);
+
+/* The tile shape, grid sizes and flag geometry the library resolved for `dims` (host call).
+ * info[0..11] = tile_m, tile_n, tile_k, compute_workgroups, comm_workgroups, comm_tile_m, comm_tile_n,
+ *               n_consumer_tiles, n_comm_tiles, expected_per_channel, threads_per_workgroup, lds_bytes. */
+int tl_resolve(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* info /*host, 12 ints*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TILELINK_MI355_H */

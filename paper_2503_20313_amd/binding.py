@@ -1,0 +1,139 @@
+"""ctypes binding of libtilelink_mi355.so: same names as the C ABI, argument marshalling only.
+
+Device buffers are passed as torch tensors (their data_ptr() is used) or as integer
+addresses.  Every function raises TileLinkError when the library returns a negative status.
+There is no fallback: if the library has not been built, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
+
+TL_OK, TL_ERR_INVALID_ARG, TL_ERR_UNSUPPORTED_SHAPE, TL_ERR_WORKSPACE_TOO_SMALL, TL_ERR_HIP, TL_ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
+TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_ONLY, TL_COMM_EXTERNAL = 0, 1, 2, 3, 4, 5
+TL_ORDER_NATURAL, TL_ORDER_RING = 0, 1
+TL_OP_AG_GEMM, TL_OP_GEMM_RS, TL_OP_MOE_AG_GATHER_GEMM, TL_OP_MOE_GEMM_SCATTER_RS, TL_OP_SP_AG_ATTENTION = 0, 1, 2, 3, 4
+
+
+class TileLinkError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"tilelink_mi355 status {status}: {message}")
+        self.status = status
+
+
+class tl_config(ctypes.Structure):
+    _fields_ = [("world_size", ctypes.c_int), ("rank", ctypes.c_int), ("channels_per_rank", ctypes.c_int),
+                ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("comm_tile_m", ctypes.c_int),
+                ("comm_tile_n", ctypes.c_int), ("comm_mode", ctypes.c_int), ("comm_workgroups", ctypes.c_int),
+                ("compute_workgroups", ctypes.c_int), ("tile_order", ctypes.c_int), ("xcd_swizzle", ctypes.c_int),
+                ("spin_timeout_us", ctypes.c_uint)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+                      "or python paper_2503_20313_amd/build.py). There is no CPU fallback.")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _u, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
+_lib.tl_last_error.restype = ctypes.c_char_p
+_lib.tl_version.restype = ctypes.c_char_p
+_lib.tl_ctx_create.argtypes = [ctypes.POINTER(tl_config), ctypes.POINTER(_vp)]
+_lib.tl_ctx_destroy.argtypes = [_vp]
+_lib.tl_query_workspace.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
+_lib.tl_check_status.argtypes = [_vp, _vp]
+_lib.tl_resolve.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i)]
+_lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i), _sz, ctypes.POINTER(_sz)]
+_lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_gemm_rs.argtypes = [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()          # torch tensor
+
+
+def _ptr_array(items):
+    arr = (_vp * len(items))()
+    for i, it in enumerate(items):
+        arr[i] = _ptr(it)
+    return arr
+
+
+def _stream(s):
+    if s is None or isinstance(s, int):
+        return s
+    return s.cuda_stream         # torch.cuda.Stream
+
+
+def _check(status):
+    if status < 0:
+        raise TileLinkError(status, _lib.tl_last_error().decode())
+    return status
+
+
+def _dims(dims):
+    return (ctypes.c_longlong * len(dims))(*dims)
+
+
+def tl_version():
+    return _lib.tl_version().decode()
+
+
+def tl_last_error():
+    return _lib.tl_last_error().decode()
+
+
+def tl_ctx_create(**fields):
+    cfg = tl_config(**fields)
+    ctx = _vp()
+    _check(_lib.tl_ctx_create(ctypes.byref(cfg), ctypes.byref(ctx)))
+    return ctx
+
+
+def tl_ctx_destroy(ctx):
+    _check(_lib.tl_ctx_destroy(ctx))
+
+
+def tl_query_workspace(ctx, op, dims):
+    ws, nf = _sz(), _sz()
+    _check(_lib.tl_query_workspace(ctx, op, _dims(dims), ctypes.byref(ws), ctypes.byref(nf)))
+    return ws.value, nf.value
+
+
+def tl_check_status(ctx, workspace):
+    _check(_lib.tl_check_status(ctx, _ptr(workspace)))
+
+
+def tl_resolve(ctx, op, dims):
+    info = (_i * 12)()
+    _check(_lib.tl_resolve(ctx, op, _dims(dims), info))
+    keys = ["tile_m", "tile_n", "tile_k", "compute_workgroups", "comm_workgroups", "comm_tile_m", "comm_tile_n",
+            "n_consumer_tiles", "n_comm_tiles", "expected_per_channel", "threads_per_workgroup", "lds_bytes"]
+    return dict(zip(keys, list(info)))
+
+
+def tl_dump_schedule(ctx, op, dims):
+    n = _sz()
+    d = _dims(dims)
+    st = _lib.tl_dump_schedule(ctx, op, d, None, 0, ctypes.byref(n))
+    if st not in (TL_OK, TL_ERR_WORKSPACE_TOO_SMALL):
+        _check(st)
+    buf = (_i * n.value)()
+    _check(_lib.tl_dump_schedule(ctx, op, d, buf, n.value, ctypes.byref(n)))
+    return list(buf)
+
+
+def tl_ag_gemm(ctx, a_shards, a_gathered, b, c, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_ag_gemm(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr(b), _ptr(c), M, N, K, _ptr(flags), epoch,
+                           _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_gemm_rs(ctx, a, b, partial, peer_recv, peer_push, out, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_gemm_rs(ctx, _ptr(a), _ptr(b), _ptr(partial), _ptr_array(peer_recv), _ptr_array(peer_push), _ptr(out), M, N, K,
+                           _ptr(flags), epoch, _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))

@@ -1,0 +1,637 @@
+// AllGather+GEMM and GEMM+ReduceScatter: fused persistent kernels, their producers/consumers,
+// host-side validation, mapping tables and launches.  gfx950 only.
+#include "tl_gemm_tile.h"
+#include "tl_host.h"
+
+namespace tl {
+
+// ======================================================================================
+// Kernel parameters
+// ======================================================================================
+struct AgGemmParams {
+  const bf16_t* a_shards[kMaxWorld];
+  bf16_t* a_gathered;
+  const bf16_t* b;
+  bf16_t* c;
+  int M, N, K;
+  int R, rank, C;
+  Sched sched;
+  int n_comm;           // producer workgroups at the front of the grid (0: none in this launch)
+  int do_compute;       // 0: producers only
+  int do_wait;          // consumers wait on channel flags
+  int Tm_p, Tn_p, n_ptm, n_ptn;
+  int rows_per_rank, rows_per_channel;
+  int local_in_place;
+  unsigned wait_target;  // epoch * expected
+  unsigned* flags;
+  WaitCtl ctl;
+};
+
+struct GemmRsParams {
+  const bf16_t* a;
+  const bf16_t* b;
+  bf16_t* partial;
+  const bf16_t* peer_recv[kMaxWorld];
+  bf16_t* peer_push[kMaxWorld];
+  bf16_t* out;
+  int M, N, K;
+  int R, rank;
+  Sched sched;
+  int n_comm, do_compute, do_notify, do_wait;
+  int tile_m, tile_n;        // GEMM tile
+  int Tm_r, Tn_r, ncm, ncn;  // reduce tiles
+  int seg_rows, tiles_per_seg;
+  int rs_first_block;        // rotation of reduce row-blocks
+  unsigned epoch;
+  unsigned* ready;           // [ncm*ncn]
+  unsigned* arrived;         // [R*tiles_per_seg]
+  unsigned* pushed;          // [R*tiles_per_seg]
+  WaitCtl ctl;
+};
+
+// ======================================================================================
+// AllGather producer (pull mode): copy producer tile (tm, tn) of the gathered matrix from its
+// owner's shard, then notify the tile's channel.  Tiles are visited ring-wise starting with the
+// rank after this one (the local shard, which needs no transfer, is handled last).
+// ======================================================================================
+__device__ void ag_producer(const AgGemmParams& p, int wg, int n_wg, int tid, int nthreads) {
+  const int n_pt = p.n_ptm * p.n_ptn;
+  const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
+  for (int i = wg; i < n_pt; i += n_wg) {
+    int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
+    // ring order over source ranks: rank+1, rank+2, ..., rank
+    int tm = tmi + (p.rank + 1) * ptm_per_rank;
+    if (tm >= p.n_ptm) tm -= p.n_ptm;
+    int row_lo = tm * p.Tm_p;
+    int src = tm / ptm_per_rank;                                  // f_R
+    int channel = tm / (p.rows_per_channel / p.Tm_p);             // f_C
+    if (!(src == p.rank && p.local_in_place)) {
+      const bf16_t* s = p.a_shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.K + (long)tn * p.Tn_p;
+      bf16_t* d = p.a_gathered + (long)row_lo * p.K + (long)tn * p.Tn_p;
+      copy_tile(s, p.K, d, p.K, p.Tm_p, p.Tn_p, tid, nthreads);
+    }
+    __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
+    if (tid == 0) tile_notify(p.flags + channel);
+  }
+}
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x < p.n_comm) {
+    ag_producer(p, blockIdx.x, p.n_comm, tid, Cfg::NTHREADS);
+    return;
+  }
+  if (!p.do_compute) return;
+  const int w = blockIdx.x - p.n_comm;
+  const int M_per_channel = p.rows_per_channel;
+  for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
+    int tile = sched_tile(p.sched, pos);
+    int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
+    int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
+    int rows = min(Cfg::BM, p.M - row_lo), cols = min(Cfg::BN, p.N - col_lo);
+    if (p.do_wait) {
+      // consumer_tile_wait: every channel whose rows the tile touches
+      if (tid == 0) {
+        int clo = row_lo / M_per_channel, chi = (row_lo + rows - 1) / M_per_channel;
+        for (int ch = clo; ch <= chi; ch++) tile_wait(p.flags + ch, p.wait_target, p.ctl, ch);
+      }
+      __syncthreads();
+    }
+    gemm_tile<Cfg>(p.a_gathered + (long)row_lo * p.K, p.K, p.b + col_lo, p.N, p.c + (long)row_lo * p.N + col_lo, p.N, rows,
+                   cols, p.K, smem);
+  }
+}
+
+// Producer as a kernel of its own (small register/LDS footprint, so it can share compute units
+// with resident GEMM workgroups) for the side-stream binding.
+__global__ void __launch_bounds__(256) ag_producer_kernel(const AgGemmParams p) {
+  ag_producer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
+}
+
+// rank_notify for copies made by the runtime's copy path: raise `count` consecutive flags.
+__global__ void notify_kernel(unsigned* flags, int count, unsigned inc) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) tile_notify(flags + i, inc);
+}
+
+// ======================================================================================
+// ReduceScatter consumer: reduce tiles of the partial product.  Own segment: wait for every
+// peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
+// landing zone and notify it.
+// ======================================================================================
+__device__ __forceinline__ void acc_bf16x8(float (&s)[8], u32x4 v) {
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    s[2 * e] += __uint_as_float(v[e] << 16);
+    s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+  }
+}
+
+__device__ void rs_consumer(const GemmRsParams& p, int wg, int n_wg, int tid, int nthreads) {
+  const int n_rt = p.ncm * p.ncn;
+  const int cm_per_seg = p.seg_rows / p.Tm_r;
+  for (int i = wg; i < n_rt; i += n_wg) {
+    int cmi = i / p.ncn, cn = i - cmi * p.ncn;
+    int cm = cmi + p.rs_first_block;
+    if (cm >= p.ncm) cm -= p.ncm;
+    const int t = cm * p.ncn + cn;
+    const int row_lo = cm * p.Tm_r, col_lo = cn * p.Tn_r;
+    const int rows = min(p.Tm_r, p.M - row_lo), cols = min(p.Tn_r, p.N - col_lo);
+    const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
+    const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
+    const int seg_row = row_lo - dest * p.seg_rows;
+    if (tid == 0) {
+      if (p.do_wait) {
+        // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
+        unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
+        unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
+        tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);
+      }
+      if (dest == p.rank) {
+        // peer_tile_wait: every peer's contribution to this tile has landed
+        for (int q = 0; q < p.R; q++)
+          if (q != p.rank) tile_wait(p.arrived + q * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + q * p.tiles_per_seg + local);
+      }
+    }
+    __syncthreads();
+    const bf16_t* mine = p.partial + (long)row_lo * p.N + col_lo;
+    const int cpr = cols >> 3, total = rows * cpr;
+    if (dest == p.rank) {
+      bf16_t* o = p.out + (long)seg_row * p.N + col_lo;
+      for (int idx = tid; idx < total; idx += nthreads) {
+        int r = idx / cpr, c = idx - r * cpr;
+        long off = (long)r * p.N + c * 8;
+        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < p.R; q++) {
+          const bf16_t* src = (q == p.rank) ? mine : p.peer_recv[q] + (long)seg_row * p.N + col_lo;
+          acc_bf16x8(s, *(const u32x4*)(src + off));
+        }
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
+        *(bf16x8*)(o + off) = v;
+      }
+    } else {
+      // tile_push_data to the owner's landing zone, then peer_tile_notify
+      copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
+      __syncthreads();
+      if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);
+    }
+  }
+}
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x < p.n_comm) {
+    rs_consumer(p, blockIdx.x, p.n_comm, tid, Cfg::NTHREADS);
+    return;
+  }
+  if (!p.do_compute) return;
+  const int w = blockIdx.x - p.n_comm;
+  for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
+    int tile = sched_tile(p.sched, pos);
+    int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
+    int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
+    int rows = min(Cfg::BM, p.M - row_lo), cols = min(Cfg::BN, p.N - col_lo);
+    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, p.b + col_lo, p.N, p.partial + (long)row_lo * p.N + col_lo, p.N, rows, cols,
+                   p.K, smem);
+    if (p.do_notify) {
+      // producer_tile_notify: one release-add per reduce tile this GEMM tile overlaps
+      __syncthreads();
+      int cm_lo = row_lo / p.Tm_r, cm_hi = (row_lo + rows - 1) / p.Tm_r;
+      int cn_lo = col_lo / p.Tn_r, cn_hi = (col_lo + cols - 1) / p.Tn_r;
+      int ncols = cn_hi - cn_lo + 1, cnt = (cm_hi - cm_lo + 1) * ncols;
+      for (int i = tid; i < cnt; i += Cfg::NTHREADS) tile_notify(p.ready + (cm_lo + i / ncols) * p.ncn + cn_lo + i % ncols);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) rs_consumer_kernel(const GemmRsParams p) {
+  rs_consumer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
+}
+
+// Simulated peers: peer q's push of every tile of this rank's segment "arrives".
+__global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R, int rank) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < R * tiles_per_seg && i / tiles_per_seg != rank) tile_notify(arrived + i);
+}
+
+// ======================================================================================
+// Host side
+// ======================================================================================
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static const int kTileM[TILE_VARIANTS] = {256, 256, 128};
+static const int kTileN[TILE_VARIANTS] = {256, 224, 128};
+typedef TileCfg<256, 256, 2, 4> Cfg256x256;
+typedef TileCfg<256, 224, 8, 1> Cfg256x224;
+typedef TileCfg<128, 128, 2, 2> Cfg128x128;
+static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
+static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
+
+int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
+  const tl_config& c = ctx->cfg;
+  if (M <= 0 || N <= 0 || K <= 0) return fail(TL_ERR_INVALID_ARG, "M, N, K must be positive (got %d, %d, %d)", M, N, K);
+  const int R = c.world_size;
+  if (M % R) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d must divide M=%d", R, M);
+  if (K % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 64", K);
+  if (N % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "N=%d must be a multiple of 8", N);
+  memset(r, 0, sizeof *r);
+  // ---- compute tile
+  int v = -1;
+  if (c.tile_m || c.tile_n) {
+    for (int i = 0; i < TILE_VARIANTS; i++)
+      if (kTileM[i] == c.tile_m && kTileN[i] == c.tile_n) v = i;
+    if (v < 0) return fail(TL_ERR_UNSUPPORTED_SHAPE, "compute tile %dx%d is not one of 256x256, 256x224, 128x128", c.tile_m, c.tile_n);
+  } else if ((long)M * N <= 1024L * 1024L) {
+    v = TILE_128x128;
+  } else if (N % 256 != 0 && N % 224 == 0) {
+    v = TILE_256x224;
+  } else {
+    v = TILE_256x256;
+  }
+  r->variant = v;
+  r->tile_m = kTileM[v];
+  r->tile_n = kTileN[v];
+  r->threads = kThreads[v];
+  r->lds_bytes = kLds[v];
+  r->nbm = ceil_div(M, r->tile_m);
+  r->nbn = ceil_div(N, r->tile_n);
+  r->n_tiles = r->nbm * r->nbn;
+  r->rows_per_rank = M / R;
+  // ---- grid
+  int G = c.compute_workgroups > 0 ? c.compute_workgroups : ctx->num_cus;
+  if (G > r->n_tiles) G = r->n_tiles;
+  r->G = G;
+  int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : 16;
+  r->n_comm = (c.comm_mode == TL_COMM_NONE) ? 0 : n_comm;
+  // ---- communication tiles
+  if (op == TL_OP_AG_GEMM) {
+    const int C = c.channels_per_rank;
+    if (r->rows_per_rank % C) return fail(TL_ERR_UNSUPPORTED_SHAPE, "channels per rank %d must divide M/R=%d", C, r->rows_per_rank);
+    r->rows_per_channel = r->rows_per_rank / C;
+    int Tm_p = c.comm_tile_m;
+    if (Tm_p == 0) {
+      Tm_p = r->rows_per_channel;
+      while (Tm_p > 32 && Tm_p % 2 == 0) Tm_p /= 2;  // small row tiles: many producer tiles per channel keeps all copy workgroups busy
+      if (r->rows_per_channel % Tm_p) Tm_p = r->rows_per_channel;
+    }
+    if (Tm_p <= 0 || r->rows_per_channel % Tm_p)
+      return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer row tile %d must divide the rows per channel M/(R*C)=%d", Tm_p, r->rows_per_channel);
+    int Tn_p = c.comm_tile_n ? c.comm_tile_n : K;
+    if (Tn_p <= 0 || K % Tn_p || Tn_p % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer column tile %d must divide K=%d and be a multiple of 8", Tn_p, K);
+    r->Tm_p = Tm_p;
+    r->Tn_p = Tn_p;
+    r->n_ptm = M / Tm_p;
+    r->n_ptn = K / Tn_p;
+    r->expected = (r->rows_per_channel / Tm_p) * r->n_ptn;
+    r->first_block = 0;
+    if (c.tile_order == TL_ORDER_RING) {
+      if (r->nbm % R == 0) r->first_block = c.rank * (r->nbm / R);
+    }
+  } else {
+    int Tm_r = c.comm_tile_m ? c.comm_tile_m : (r->tile_m <= r->rows_per_rank ? r->tile_m : r->rows_per_rank);
+    int Tn_r = c.comm_tile_n ? c.comm_tile_n : (N % r->tile_n == 0 ? r->tile_n : N);
+    if (Tm_r <= 0 || r->rows_per_rank % Tm_r) return fail(TL_ERR_UNSUPPORTED_SHAPE, "reduce row tile %d must divide M/R=%d", Tm_r, r->rows_per_rank);
+    if (Tn_r <= 0 || N % Tn_r || Tn_r % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "reduce column tile %d must divide N=%d and be a multiple of 8", Tn_r, N);
+    r->Tm_p = Tm_r;
+    r->Tn_p = Tn_r;
+    r->n_ptm = M / Tm_r;
+    r->n_ptn = N / Tn_r;
+    r->expected = 0;
+    r->first_block = 0;
+    if (c.tile_order == TL_ORDER_RING && r->nbm % R == 0) r->first_block = ((c.rank + 1) % R) * (r->nbm / R);
+  }
+  return TL_OK;
+}
+
+static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
+  Sched s;
+  s.nbm = r.nbm;
+  s.nbn = r.nbn;
+  s.n_tiles = r.n_tiles;
+  s.G = r.G;
+  s.first_block = r.first_block;
+  s.swizzle = ctx->cfg.xcd_swizzle;
+  return s;
+}
+
+static WaitCtl make_ctl(const tl_ctx* ctx, void* workspace) {
+  WaitCtl c;
+  c.status = (int*)workspace;
+  c.timeout = (unsigned long long)ctx->cfg.spin_timeout_us * 100ull;  // 100 MHz wall clock
+  return c;
+}
+
+template <class Cfg, class P>
+static int launch_fused(void (*kernel)(const P), const P& p, int grid, hipStream_t stream) {
+  TL_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES));
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, stream, p);
+  TL_HIP(hipGetLastError());
+  return TL_OK;
+}
+
+static int launch_ag_gemm(int variant, const AgGemmParams& p, int grid, hipStream_t s) {
+  switch (variant) {
+    case TILE_256x256: return launch_fused<Cfg256x256>(ag_gemm_kernel<Cfg256x256>, p, grid, s);
+    case TILE_256x224: return launch_fused<Cfg256x224>(ag_gemm_kernel<Cfg256x224>, p, grid, s);
+    default: return launch_fused<Cfg128x128>(ag_gemm_kernel<Cfg128x128>, p, grid, s);
+  }
+}
+
+static int launch_gemm_rs(int variant, const GemmRsParams& p, int grid, hipStream_t s) {
+  switch (variant) {
+    case TILE_256x256: return launch_fused<Cfg256x256>(gemm_rs_kernel<Cfg256x256>, p, grid, s);
+    case TILE_256x224: return launch_fused<Cfg256x224>(gemm_rs_kernel<Cfg256x224>, p, grid, s);
+    default: return launch_fused<Cfg128x128>(gemm_rs_kernel<Cfg128x128>, p, grid, s);
+  }
+}
+
+static int check_ctx(const tl_ctx* ctx) {
+  if (!ctx) return fail(TL_ERR_INVALID_ARG, "context is null");
+  return TL_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace tl
+
+using namespace tl;
+
+extern "C" {
+
+const char* tl_last_error(void) { return g_err; }
+const char* tl_version(void) { return "tilelink_mi355 0.1 (gfx950)"; }
+
+int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
+  if (!cfg || !out) return fail(TL_ERR_INVALID_ARG, "cfg and out must not be null");
+  if (cfg->world_size < 1 || cfg->world_size > kMaxWorld) return fail(TL_ERR_INVALID_ARG, "world_size %d outside [1,%d]", cfg->world_size, kMaxWorld);
+  if (cfg->rank < 0 || cfg->rank >= cfg->world_size) return fail(TL_ERR_INVALID_ARG, "rank %d outside [0,%d)", cfg->rank, cfg->world_size);
+  if (cfg->channels_per_rank < 1) return fail(TL_ERR_INVALID_ARG, "channels_per_rank must be >= 1");
+  if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_EXTERNAL) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
+  if (cfg->tile_order != TL_ORDER_NATURAL && cfg->tile_order != TL_ORDER_RING) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
+  if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0)
+    return fail(TL_ERR_INVALID_ARG, "negative workgroup count or tile size");
+  int dev = 0;
+  TL_HIP(hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  TL_HIP(hipGetDeviceProperties(&prop, dev));
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(TL_ERR_HIP, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+  tl_ctx* c = new tl_ctx;
+  c->cfg = *cfg;
+  c->device = dev;
+  c->num_cus = prop.multiProcessorCount;
+  *out = c;
+  return TL_OK;
+}
+
+int tl_ctx_destroy(tl_ctx* ctx) {
+  delete ctx;
+  return TL_OK;
+}
+
+int tl_resolve(const tl_ctx* ctx, int op, const long long* dims, int* info) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!dims || !info) return fail(TL_ERR_INVALID_ARG, "dims and info must not be null");
+  if (op != TL_OP_AG_GEMM && op != TL_OP_GEMM_RS) return fail(TL_ERR_INVALID_ARG, "tl_resolve: operator %d has no dense tile geometry", op);
+  Resolved r;
+  if (int e = resolve_dense(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], &r)) return e;
+  int v[12] = {r.tile_m, r.tile_n, 64, r.G, r.n_comm, r.Tm_p, r.Tn_p, r.n_tiles, r.n_ptm * r.n_ptn, r.expected, r.threads, r.lds_bytes};
+  memcpy(info, v, sizeof v);
+  return TL_OK;
+}
+
+int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t* ws_bytes, size_t* n_flags) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!dims || !ws_bytes || !n_flags) return fail(TL_ERR_INVALID_ARG, "dims, ws_bytes and n_flags must not be null");
+  if (op == TL_OP_AG_GEMM || op == TL_OP_GEMM_RS) {
+    Resolved r;
+    if (int e = resolve_dense(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], &r)) return e;
+    *ws_bytes = 256;  // status word (+ padding)
+    if (op == TL_OP_AG_GEMM) {
+      *n_flags = (size_t)ctx->cfg.world_size * ctx->cfg.channels_per_rank;
+    } else {
+      size_t tiles_per_seg = (size_t)(r.rows_per_rank / r.Tm_p) * r.n_ptn;
+      *n_flags = (size_t)r.n_ptm * r.n_ptn + 2 * (size_t)ctx->cfg.world_size * tiles_per_seg;
+    }
+    return TL_OK;
+  }
+  return fail(TL_ERR_INVALID_ARG, "unknown operator %d", op);
+}
+
+int tl_check_status(tl_ctx* ctx, void* workspace) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!workspace) return fail(TL_ERR_INVALID_ARG, "workspace is null");
+  int st = 0;
+  TL_HIP(hipMemcpy(&st, workspace, sizeof st, hipMemcpyDeviceToHost));
+  if (st != 0) {
+    int zero = 0;
+    TL_HIP(hipMemcpy(workspace, &zero, sizeof zero, hipMemcpyHostToDevice));
+    return fail(TL_ERR_TIMEOUT, "a flag wait expired (flag index %d)", st - 1);
+  }
+  return TL_OK;
+}
+
+int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K,
+               unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (int e = check_ctx(ctx)) return e;
+  const tl_config& cfg = ctx->cfg;
+  if (!a_shards || !a_gathered || !b || !c || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: null pointer argument");
+  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: epoch starts at 1");
+  Resolved r;
+  if (int e = resolve_dense(ctx, TL_OP_AG_GEMM, M, N, K, &r)) return e;
+  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_ag_gemm: workspace of %zu bytes, 256 needed", ws_bytes);
+  const int R = cfg.world_size;
+  if (!aligned16(a_gathered) || !aligned16(b) || !aligned16(c)) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: device pointers must be 16-byte aligned");
+  for (int q = 0; q < R; q++)
+    if (!a_shards[q] || !aligned16(a_shards[q])) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: a_shards[%d] is null or misaligned", q);
+
+  AgGemmParams p;
+  memset(&p, 0, sizeof p);
+  for (int q = 0; q < R; q++) p.a_shards[q] = (const bf16_t*)a_shards[q];
+  p.a_gathered = (bf16_t*)a_gathered;
+  p.b = (const bf16_t*)b;
+  p.c = (bf16_t*)c;
+  p.M = M; p.N = N; p.K = K;
+  p.R = R; p.rank = cfg.rank; p.C = cfg.channels_per_rank;
+  p.sched = make_sched(ctx, r);
+  p.Tm_p = r.Tm_p; p.Tn_p = r.Tn_p; p.n_ptm = r.n_ptm; p.n_ptn = r.n_ptn;
+  p.rows_per_rank = r.rows_per_rank; p.rows_per_channel = r.rows_per_channel;
+  p.local_in_place = (const bf16_t*)a_shards[cfg.rank] == (const bf16_t*)a_gathered + (size_t)cfg.rank * r.rows_per_rank * K;
+  p.flags = flags;
+  p.ctl = make_ctl(ctx, workspace);
+  hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
+
+  switch (cfg.comm_mode) {
+    case TL_COMM_NONE:
+      p.n_comm = 0; p.do_compute = 1; p.do_wait = 0;
+      return launch_ag_gemm(r.variant, p, r.G, cs);
+    case TL_COMM_WAVES:
+      p.n_comm = r.n_comm; p.do_compute = 1; p.do_wait = 1;
+      p.wait_target = epoch * (unsigned)r.expected;
+      return launch_ag_gemm(r.variant, p, r.G + r.n_comm, cs);
+    case TL_COMM_ONLY:
+      p.n_comm = r.n_comm; p.do_compute = 0; p.do_wait = 0;
+      return launch_ag_gemm(r.variant, p, r.n_comm, cs);
+    case TL_COMM_EXTERNAL:
+      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      p.wait_target = epoch * (unsigned)r.expected;
+      return launch_ag_gemm(r.variant, p, r.G, cs);
+    case TL_COMM_SIDE_KERNEL: {
+      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      p.wait_target = epoch * (unsigned)r.expected;
+      hipLaunchKernelGGL(ag_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
+      TL_HIP(hipGetLastError());
+      return launch_ag_gemm(r.variant, p, r.G, cs);
+    }
+    case TL_COMM_STREAM: {
+      // rank_copy_data + rank_notify per source rank, ring order, through the runtime's copy path
+      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      p.wait_target = epoch;
+      const size_t shard_bytes = (size_t)r.rows_per_rank * K * sizeof(bf16_t);
+      for (int i = 0; i < R; i++) {
+        int q = (cfg.rank + i) % R;  // local shard first (it is usually free), then rank+1, ...
+        char* dst = (char*)a_gathered + (size_t)q * shard_bytes;
+        if (!(q == cfg.rank && p.local_in_place)) TL_HIP(hipMemcpyAsync(dst, a_shards[q], shard_bytes, hipMemcpyDeviceToDevice, ms));
+        hipLaunchKernelGGL(notify_kernel, dim3(1), dim3(64), 0, ms, flags + q * cfg.channels_per_rank, cfg.channels_per_rank, 1u);
+        TL_HIP(hipGetLastError());
+      }
+      return launch_ag_gemm(r.variant, p, r.G, cs);
+    }
+  }
+  return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: unknown comm_mode");
+}
+
+int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv, void* const* peer_push,
+               void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes,
+               void* compute_stream, void* comm_stream) {
+  if (int e = check_ctx(ctx)) return e;
+  const tl_config& cfg = ctx->cfg;
+  if (!a || !b || !partial || !peer_recv || !peer_push || !out || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: null pointer argument");
+  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: epoch starts at 1");
+  Resolved r;
+  if (int e = resolve_dense(ctx, TL_OP_GEMM_RS, M, N, K, &r)) return e;
+  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_gemm_rs: workspace of %zu bytes, 256 needed", ws_bytes);
+  const int R = cfg.world_size;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(partial) || !aligned16(out)) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: device pointers must be 16-byte aligned");
+  for (int q = 0; q < R; q++)
+    if (q != cfg.rank && (!peer_recv[q] || !peer_push[q] || !aligned16(peer_recv[q]) || !aligned16(peer_push[q])))
+      return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: peer_recv[%d] or peer_push[%d] is null or misaligned", q, q);
+
+  GemmRsParams p;
+  memset(&p, 0, sizeof p);
+  p.a = (const bf16_t*)a; p.b = (const bf16_t*)b; p.partial = (bf16_t*)partial; p.out = (bf16_t*)out;
+  for (int q = 0; q < R; q++) {
+    p.peer_recv[q] = (const bf16_t*)peer_recv[q];
+    p.peer_push[q] = (bf16_t*)peer_push[q];
+  }
+  p.M = M; p.N = N; p.K = K; p.R = R; p.rank = cfg.rank;
+  p.sched = make_sched(ctx, r);
+  p.tile_m = r.tile_m; p.tile_n = r.tile_n;
+  p.Tm_r = r.Tm_p; p.Tn_r = r.Tn_p; p.ncm = r.n_ptm; p.ncn = r.n_ptn;
+  p.seg_rows = r.rows_per_rank;
+  p.tiles_per_seg = (r.rows_per_rank / r.Tm_p) * r.n_ptn;
+  p.rs_first_block = 0;
+  if (cfg.tile_order == TL_ORDER_RING) p.rs_first_block = ((cfg.rank + 1) % R) * (r.rows_per_rank / r.Tm_p);
+  p.epoch = epoch;
+  p.ready = flags;
+  p.arrived = flags + (size_t)p.ncm * p.ncn;
+  p.pushed = p.arrived + (size_t)R * p.tiles_per_seg;
+  p.ctl = make_ctl(ctx, workspace);
+  hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
+
+  auto peers_arrive = [&](hipStream_t s) -> int {
+    int n = R * p.tiles_per_seg;
+    hipLaunchKernelGGL(peers_arrive_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.arrived, p.tiles_per_seg, R, cfg.rank);
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+  };
+
+  switch (cfg.comm_mode) {
+    case TL_COMM_NONE:
+      p.n_comm = 0; p.do_compute = 1; p.do_notify = 0; p.do_wait = 0;
+      return launch_gemm_rs(r.variant, p, r.G, cs);
+    case TL_COMM_WAVES:
+      if (int e = peers_arrive(ms)) return e;
+      p.n_comm = r.n_comm; p.do_compute = 1; p.do_notify = 1; p.do_wait = 1;
+      return launch_gemm_rs(r.variant, p, r.G + r.n_comm, cs);
+    case TL_COMM_ONLY:
+      if (int e = peers_arrive(cs)) return e;
+      p.n_comm = r.n_comm; p.do_compute = 0; p.do_notify = 0; p.do_wait = 0;
+      return launch_gemm_rs(r.variant, p, r.n_comm, cs);
+    case TL_COMM_EXTERNAL:
+      return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: TL_COMM_EXTERNAL is not defined for this operator");
+    case TL_COMM_STREAM:
+    case TL_COMM_SIDE_KERNEL: {
+      if (int e = peers_arrive(ms)) return e;
+      p.n_comm = 0; p.do_compute = 1; p.do_notify = 1; p.do_wait = 1;
+      hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
+      TL_HIP(hipGetLastError());
+      return launch_gemm_rs(r.variant, p, r.G, cs);
+    }
+  }
+  return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: unknown comm_mode");
+}
+
+int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims, int* out, size_t cap, size_t* n) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!dims || !n) return fail(TL_ERR_INVALID_ARG, "dims and n must not be null");
+  if (op != TL_OP_AG_GEMM && op != TL_OP_GEMM_RS) return fail(TL_ERR_INVALID_ARG, "tl_dump_schedule: operator %d has no static schedule", op);
+  const int M = (int)dims[0], N = (int)dims[1], K = (int)dims[2];
+  Resolved r;
+  if (int e = resolve_dense(ctx, op, M, N, K, &r)) return e;
+  const tl_config& cfg = ctx->cfg;
+  Sched s = make_sched(ctx, r);
+  size_t need = (op == TL_OP_AG_GEMM) ? (size_t)r.n_tiles * 8 : (size_t)r.n_tiles * 9 + (size_t)r.n_ptm * r.n_ptn * 9;
+  *n = need;
+  if (!out || cap < need) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_dump_schedule: %zu ints needed, capacity %zu", need, cap);
+  int* o = out;
+  for (int pos = 0; pos < r.n_tiles; pos++) {
+    int t = sched_tile(s, pos);
+    int bm = t / r.nbn, bn = t % r.nbn;
+    int row_lo = bm * r.tile_m, row_hi = row_lo + r.tile_m < M ? row_lo + r.tile_m : M;
+    int col_lo = bn * r.tile_n, col_hi = col_lo + r.tile_n < N ? col_lo + r.tile_n : N;
+    if (op == TL_OP_AG_GEMM) {
+      int rec[8] = {t, bm, bn, row_lo, row_hi, row_lo / r.rows_per_channel, (row_hi - 1) / r.rows_per_channel, 0};
+      memcpy(o, rec, sizeof rec);
+      o += 8;
+    } else {
+      int rec[9] = {t, bm, bn, row_lo, row_hi, row_lo / r.Tm_p, (row_hi - 1) / r.Tm_p, col_lo / r.Tn_p, (col_hi - 1) / r.Tn_p};
+      memcpy(o, rec, sizeof rec);
+      o += 9;
+    }
+  }
+  if (op == TL_OP_GEMM_RS) {
+    int first = cfg.tile_order == TL_ORDER_RING ? ((cfg.rank + 1) % cfg.world_size) * (r.rows_per_rank / r.Tm_p) : 0;
+    for (int i = 0; i < r.n_ptm * r.n_ptn; i++) {
+      int cm = (i / r.n_ptn + first) % r.n_ptm, cn = i % r.n_ptn;
+      int row_lo = cm * r.Tm_p, row_hi = row_lo + r.Tm_p, col_lo = cn * r.Tn_p, col_hi = col_lo + r.Tn_p;
+      int n_m = (row_hi - 1) / r.tile_m - row_lo / r.tile_m + 1, n_n = (col_hi - 1) / r.tile_n - col_lo / r.tile_n + 1;
+      int rec[9] = {cm * r.n_ptn + cn, cm, cn, row_lo, row_hi, col_lo, col_hi, row_lo / r.rows_per_rank, n_m * n_n};
+      memcpy(o, rec, sizeof rec);
+      o += 9;
+    }
+  }
+  return TL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+// Device-side building blocks shared by the fused kernels: signal primitives with
+// acquire/release ordering (paper: "Signal Primitives", "Memory Consistency"), the
+// schedule-position -> tile map, and coalesced tile copies ("Data Primitives").
+// gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tl {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxWorld = 16;
+constexpr int kXcds = 8;  // workgroup w of a launch runs on die w % 8
+
+// ---------------------------------------------------------------------------------------
+// Signal primitives.  A barrier is a counter that only grows; notify adds 1 with release
+// ordering at device scope, wait spins until the counter reaches its target and then takes an
+// acquire fence, so that no later load of the waiting workgroup can be served from data cached
+// before the producer's stores became visible.  One lane per workgroup performs them; the
+// caller brackets them with workgroup barriers.
+// ---------------------------------------------------------------------------------------
+struct WaitCtl {
+  int* status;                 // status word: 0 = ok, else 1 + index of the flag whose wait expired
+  unsigned long long timeout;  // in ticks of the 100 MHz wall clock; 0 = unbounded
+};
+
+__device__ __forceinline__ void tile_notify(unsigned* flag, unsigned inc = 1u) {
+  __hip_atomic_fetch_add(flag, inc, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Returns false if the wait was abandoned (timeout here or earlier anywhere in the grid).
+__device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target, const WaitCtl& ctl, int flag_index) {
+  unsigned long long t0 = 0;
+  bool timed = ctl.timeout != 0;
+  if (timed) t0 = wall_clock64();
+  bool ok = true;
+  while ((int)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+    __builtin_amdgcn_s_sleep(4);
+    if (timed) {
+      if (__hip_atomic_load(ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = false; break; }
+      if (wall_clock64() - t0 > ctl.timeout) {
+        int expected = 0;
+        __hip_atomic_compare_exchange_strong(ctl.status, &expected, 1 + flag_index, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+        ok = false;
+        break;
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  return ok;
+}
+
+// ---------------------------------------------------------------------------------------
+// Tile order.  Position p of the schedule is computed by persistent workgroup p % G in its
+// round p / G.  Inside a full round the workgroups of one die get a contiguous run of G/8
+// logical tiles; logical tiles are row-major over (row block, column block) with the row
+// blocks optionally rotated so that `first_block` comes first.
+// ---------------------------------------------------------------------------------------
+struct Sched {
+  int nbm, nbn, n_tiles, G;
+  int first_block;  // rotation of row blocks (0 = natural)
+  int swizzle;
+};
+
+__host__ __device__ inline int sched_tile(const Sched& s, int p) {
+  int l = p;
+  if (s.swizzle && s.G % kXcds == 0) {
+    int rnd = p / s.G, w = p - rnd * s.G;
+    int span = s.n_tiles - rnd * s.G;
+    if (span > s.G) span = s.G;
+    if (span % kXcds == 0) l = rnd * s.G + (w % kXcds) * (span / kXcds) + w / kXcds;
+  }
+  int i = l / s.nbn, bn = l - i * s.nbn;
+  int bm = i + s.first_block;
+  if (bm >= s.nbm) bm -= s.nbm;
+  return bm * s.nbn + bn;
+}
+
+// ---------------------------------------------------------------------------------------
+// Copy of a rows x cols (bf16, cols % 8 == 0) tile by one workgroup, 16 bytes per lane and
+// access, four accesses in flight per lane.  Pointers must be 16-byte aligned.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void copy_tile(const bf16_t* __restrict__ src, long src_ld, bf16_t* __restrict__ dst, long dst_ld,
+                                          int rows, int cols, int tid, int nthreads) {
+  const int cpr = cols >> 3;  // 16-byte chunks per row
+  const int total = rows * cpr;
+  int i = tid;
+  for (; i + 3 * nthreads < total; i += 4 * nthreads) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      int idx = i + u * nthreads, r = idx / cpr, c = idx - r * cpr;
+      v[u] = __builtin_nontemporal_load((const u32x4*)(src + r * src_ld) + c);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      int idx = i + u * nthreads, r = idx / cpr, c = idx - r * cpr;
+      *((u32x4*)(dst + r * dst_ld) + c) = v[u];
+    }
+  }
+  for (; i < total; i += nthreads) {
+    int r = i / cpr, c = i - r * cpr;
+    *((u32x4*)(dst + r * dst_ld) + c) = __builtin_nontemporal_load((const u32x4*)(src + r * src_ld) + c);
+  }
+}
+
+}  // namespace tl
