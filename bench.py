@@ -1,0 +1,184 @@
+"""Benchmark of the overlapped tensor-parallel hot path on one MI355X.
+
+One step = AllGather+GEMM on one rank's TP=8 share of MLP-5's first half (8 shards of
+[1024,8192] gathered, B [8192,3584]) followed by GEMM+ReduceScatter on its second half
+(A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]); inputs are synthetic, seeded and
+already resident in HBM.  Prints ONE JSON line (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk x 2.4 GHz (dense bf16 MFMA)
+
+
+def cpu_baseline(np, wl, ops):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
+    AG+GEMM restricted to the first 1024 of the 3584 output columns, GEMM+RS to the first 2048 of 8192."""
+    t_gen = time.time()
+    w = wl.ag_gemm_inputs(8192, 1024, 8192, 8, config_id=2)
+    w3 = wl.gemm_rs_inputs(8192, 2048, 3584, 8, 0, config_id=3)
+    t0 = time.time()
+    ops.ag_gemm(w["a_shards"], w["b"])
+    ops.gemm_rs(w3["a"], w3["b"], w3["peer_segments"], 0)
+    dt = time.time() - t0
+    flop = 2.0 * 8192 * 8192 * 1024 + 2.0 * 8192 * 2048 * 3584
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "AG+GEMM 8192x1024x8192 (first 1024 of 3584 columns) + GEMM+RS 8192x2048x3584 (first 2048 of 8192 columns), "
+                      f"float64 numpy, {dt:.1f} s (+{t0 - t_gen:.1f} s input generation)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--comm-mode", default="waves", choices=["waves", "side", "stream"])
+    ap.add_argument("--comm-workgroups", type=int, default=0)
+    ap.add_argument("--channels", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the TP=8 layer; --gpus must be 1 "
+              "(peers are seeded buffers in the same HBM, there are no collectives)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_20313_amd as tl
+    import tl_workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    mode = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM}[args.comm_mode]
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).to(dev)
+
+    R, rank = 8, 0
+    # ---------------- AG+GEMM (configuration 2)
+    M, N, K = 8192, 3584, 8192
+    w2 = wl.ag_gemm_inputs(M, N, K, R, config_id=2)
+    shards = [up(s) for s in w2["a_shards"]]
+    gathered = torch.zeros((M, K), dtype=torch.int16, device=dev)
+    b2 = up(w2["b"])
+    c2 = torch.zeros((M, N), dtype=torch.int16, device=dev)
+    # ---------------- GEMM+RS (configuration 3)
+    M3, N3, K3 = 8192, 8192, 3584
+    w3 = wl.gemm_rs_inputs(M3, N3, K3, R, rank, config_id=3)
+    a3, b3 = up(w3["a"]), up(w3["b"])
+    partial = torch.zeros((M3, N3), dtype=torch.int16, device=dev)
+    recv = [0 if q == rank else up(w3["peer_segments"][q]) for q in range(R)]
+    push = [0 if q == rank else torch.zeros((M3 // R, N3), dtype=torch.int16, device=dev) for q in range(R)]
+    out3 = torch.zeros((M3 // R, N3), dtype=torch.int16, device=dev)
+
+    cs = torch.cuda.Stream()
+    ms = torch.cuda.Stream()
+
+    class Op:
+        def __init__(self, op, dims, comm_mode):
+            self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode,
+                                        comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_RING, xcd_swizzle=1,
+                                        spin_timeout_us=10_000_000)
+            self.op, self.dims = op, dims
+            self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
+            self.flags = torch.zeros(n_flags, dtype=torch.int32, device=dev)
+            self.wsp = torch.zeros(self.ws_bytes // 4, dtype=torch.int32, device=dev)
+            self.epoch = 0
+            self.info = tl.tl_resolve(self.ctx, op, dims)
+
+        def __call__(self):
+            self.epoch += 1
+            if self.op == tl.TL_OP_AG_GEMM:
+                tl.tl_ag_gemm(self.ctx, shards, gathered, b2, c2, M, N, K, self.flags, self.epoch, self.wsp, self.ws_bytes, cs, ms)
+            else:
+                tl.tl_gemm_rs(self.ctx, a3, b3, partial, recv, push, out3, M3, N3, K3, self.flags, self.epoch, self.wsp, self.ws_bytes, cs, ms)
+
+    def timed(fn, steps, warmup):
+        """Average ms per call over `steps` calls; events are recorded on the compute stream, and the
+        comm stream is joined into it before the closing event."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(cs)
+        for _ in range(steps):
+            fn()
+        cs.wait_stream(ms)
+        e1.record(cs)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall
+
+    flop2, flop3 = 2.0 * M * N * K, 2.0 * M3 * N3 * K3
+    res = {}
+    ops_ = {}
+    for name, op, dims in (("ag_gemm", tl.TL_OP_AG_GEMM, [M, N, K]), ("gemm_rs", tl.TL_OP_GEMM_RS, [M3, N3, K3])):
+        fused, alone, comm = Op(op, dims, mode), Op(op, dims, tl.TL_COMM_NONE), Op(op, dims, tl.TL_COMM_ONLY)
+        if op == tl.TL_OP_AG_GEMM:
+            fused()                      # leaves the gathered buffer complete for the compute-alone variant
+            torch.cuda.synchronize()
+        t_alone, _ = timed(alone, args.steps, args.warmup)
+        t_comm, _ = timed(comm, args.steps, args.warmup)
+        t_fused, _ = timed(fused, args.steps, args.warmup)
+        for o in (fused, alone, comm):
+            tl.tl_check_status(o.ctx, o.wsp)
+        fl = flop2 if op == tl.TL_OP_AG_GEMM else flop3
+        res[name] = {"fused_ms": round(t_fused, 4), "compute_alone_ms": round(t_alone, 4), "comm_alone_ms": round(t_comm, 4),
+                     "tflops": round(fl / t_fused / 1e9, 1), "frac_of_peak": round(fl / t_fused / 1e9 / PEAK_BF16_TFLOPS, 4),
+                     "compute_alone_tflops": round(fl / t_alone / 1e9, 1),
+                     "overlap_efficiency": round(max(t_alone, t_comm) / t_fused, 4),
+                     "paper_overlap_ratio": round((t_alone + t_comm - t_fused) / t_comm, 4),
+                     "tile": f"{fused.info['tile_m']}x{fused.info['tile_n']}", "compute_workgroups": fused.info["compute_workgroups"],
+                     "comm_workgroups": fused.info["comm_workgroups"]}
+        ops_[name] = fused
+
+    # ---------------- the timed region proper: K steps of the whole hot path
+    def step():
+        ops_["ag_gemm"]()
+        ops_["gemm_rs"]()
+
+    ms_step, wall_step = timed(step, args.steps, args.warmup)
+    for o in ops_.values():
+        tl.tl_check_status(o.ctx, o.wsp)
+    tflops = (flop2 + flop3) / ms_step / 1e9
+
+    # dominant kernel = the fused GEMM kernels (AG+GEMM and GEMM+RS have the same flop count); the
+    # average launch duration is the fused time measured above on the stream the kernel runs on
+    dom_ms = 0.5 * (res["ag_gemm"]["fused_ms"] + res["gemm_rs"]["fused_ms"])
+    achieved = flop2 / dom_ms / 1e9
+    out = {
+        "metric": "TFLOP/s + overlap efficiency, AG+GEMM & GEMM+RS at TP=8 share, 1 MI355X",
+        "value": round(tflops, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "MLP-5 TP=8 share: AG+GEMM 8x[1024,8192]->[8192,8192]x[8192,3584] then GEMM+RS [8192,3584]x[3584,8192]->[1024,8192]",
+                   "world_size": R, "rank": rank, "comm_mode": args.comm_mode, "channels_per_rank": args.channels},
+        "overlap_efficiency": round(min(res["ag_gemm"]["overlap_efficiency"], res["gemm_rs"]["overlap_efficiency"]), 4),
+        "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "ops": res,
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)"},
+        "host_wall_ms_per_step": round(wall_step, 4),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import ops as oracle_ops
+        out["cpu_baseline"] = cpu_baseline(np, wl, oracle_ops)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -81,6 +81,7 @@ typedef struct tl_config {
   int compute_workgroups;  /* persistent compute workgroups G; 0 = number of compute units */
   int tile_order;          /* TL_ORDER_* */
   int xcd_swizzle;         /* 1: workgroups on one die take neighbouring tiles (see tl_dump_schedule) */
+  int group_m;             /* row blocks walked together in the compute order (column block slowest inside a group); 0 = auto */
   unsigned spin_timeout_us;/* bound on every flag wait; 0 = unbounded */
 } tl_config;
 
@@ -157,9 +158,9 @@ int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims /*host*/, 
                      size_t* n /*host*/);
 
 /* The tile shape, grid sizes and flag geometry the library resolved for `dims` (host call).
- * info[0..11] = tile_m, tile_n, tile_k, compute_workgroups, comm_workgroups, comm_tile_m, comm_tile_n,
- *               n_consumer_tiles, n_comm_tiles, expected_per_channel, threads_per_workgroup, lds_bytes. */
-int tl_resolve(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* info /*host, 12 ints*/);
+ * info[0..12] = tile_m, tile_n, tile_k, compute_workgroups, comm_workgroups, comm_tile_m, comm_tile_n,
+ *               n_consumer_tiles, n_comm_tiles, expected_per_channel, threads_per_workgroup, lds_bytes, group_m. */
+int tl_resolve(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* info /*host, 13 ints*/);
 
 #ifdef __cplusplus
 }

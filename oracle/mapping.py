@@ -67,15 +67,19 @@ def consumer_tile(tile_id_c: int, M: int, N: int, R: int, C: int, Tm_c: int, Tn_
 # position p.  Workgroup w of a grid of G takes positions w, w+G, w+2G, ...
 # ---------------------------------------------------------------------------
 
-def logical_order(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool):
+def logical_order(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, group_m: int = 1):
     """Row-blocks in natural order, or rotated so that the row-blocks owned by
-    `first_rank` come first and the other ranks follow in ring order."""
+    `first_rank` come first and the other ranks follow in ring order.  The
+    (rotated) row blocks are taken in groups of `group_m`; inside a group all
+    row blocks of one column block come before the next column block."""
     blocks_per_rank = nbm // R if rotate else 0
+    rows = [(i + first_rank * blocks_per_rank) % nbm if rotate else i for i in range(nbm)]
     order = []
-    for i in range(nbm):
-        bm = (i + first_rank * blocks_per_rank) % nbm if rotate else i
+    for start in range(0, nbm, group_m):
+        group = rows[start:start + group_m]
         for bn in range(nbn):
-            order.append(bm * nbn + bn)
+            for bm in group:
+                order.append(bm * nbn + bn)
     return order
 
 
@@ -97,20 +101,20 @@ def xcd_positions(n_tiles: int, G: int):
     return pos
 
 
-def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool):
+def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool, group_m: int = 1):
     """Output-tile id at every schedule position."""
-    logical = logical_order(nbm, nbn, R, first_rank, rotate)
+    logical = logical_order(nbm, nbn, R, first_rank, rotate, group_m)
     n = nbm * nbn
     pos = xcd_positions(n, G) if swizzle else list(range(n))
     return [logical[pos[p]] for p in range(n)]
 
 
-def ag_gemm_schedule_records(M, N, K, R, C, rank, Tm_c, Tn_c, G, rotate=True, swizzle=True):
+def ag_gemm_schedule_records(M, N, K, R, C, rank, Tm_c, Tn_c, G, rotate=True, swizzle=True, group_m=1):
     """One 8-int record per schedule position:
     (tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0)."""
     nbm, nbn = ceil_div(M, Tm_c), ceil_div(N, Tn_c)
     recs = []
-    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle):
+    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle, group_m):
         bm, bn, lo, hi, clo, chi = consumer_tile(t, M, N, R, C, Tm_c, Tn_c)
         recs.append((t, bm, bn, lo, hi, clo, chi, 0))
     return recs
@@ -137,7 +141,7 @@ def rs_tile_table(M, N, R, rank, Tm_c, Tn_c, Tm_r, Tn_r):
     return out
 
 
-def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate=True, swizzle=True):
+def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate=True, swizzle=True, group_m=1):
     """GEMM tiles in schedule order; with `rotate` the row-blocks of rank+1 come
     first and this rank's own segment last (ring order), so that pushes leave
     early and the segment that needs every peer's data is computed last.
@@ -145,7 +149,7 @@ def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate
     cm/cn ranges (inclusive) are the reduce tiles the GEMM tile notifies."""
     nbm, nbn = ceil_div(M, Tm_c), ceil_div(N, Tn_c)
     recs = []
-    for t in tile_schedule(nbm, nbn, R, (rank + 1) % R, rotate, G, swizzle):
+    for t in tile_schedule(nbm, nbn, R, (rank + 1) % R, rotate, G, swizzle, group_m):
         bm, bn = divmod(t, nbn)
         rlo, rhi = bm * Tm_c, min(bm * Tm_c + Tm_c, M)
         clo, chi = bn * Tn_c, min(bn * Tn_c + Tn_c, N)

@@ -29,7 +29,7 @@ class tl_config(ctypes.Structure):
                 ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("comm_tile_m", ctypes.c_int),
                 ("comm_tile_n", ctypes.c_int), ("comm_mode", ctypes.c_int), ("comm_workgroups", ctypes.c_int),
                 ("compute_workgroups", ctypes.c_int), ("tile_order", ctypes.c_int), ("xcd_swizzle", ctypes.c_int),
-                ("spin_timeout_us", ctypes.c_uint)]
+                ("group_m", ctypes.c_int), ("spin_timeout_us", ctypes.c_uint)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -111,10 +111,10 @@ def tl_check_status(ctx, workspace):
 
 
 def tl_resolve(ctx, op, dims):
-    info = (_i * 12)()
+    info = (_i * 13)()
     _check(_lib.tl_resolve(ctx, op, _dims(dims), info))
     keys = ["tile_m", "tile_n", "tile_k", "compute_workgroups", "comm_workgroups", "comm_tile_m", "comm_tile_n",
-            "n_consumer_tiles", "n_comm_tiles", "expected_per_channel", "threads_per_workgroup", "lds_bytes"]
+            "n_consumer_tiles", "n_comm_tiles", "expected_per_channel", "threads_per_workgroup", "lds_bytes", "group_m"]
     return dict(zip(keys, list(info)))
 
 

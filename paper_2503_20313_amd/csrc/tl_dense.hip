@@ -242,9 +242,9 @@ int fail(int code, const char* fmt, ...) {
 
 static const int kTileM[TILE_VARIANTS] = {256, 256, 128};
 static const int kTileN[TILE_VARIANTS] = {256, 224, 128};
-typedef TileCfg<256, 256, 2, 4> Cfg256x256;
-typedef TileCfg<256, 224, 8, 1> Cfg256x224;
-typedef TileCfg<128, 128, 2, 2> Cfg128x128;
+typedef TileCfg<256, 256, 2, 4, 32, 4> Cfg256x256;
+typedef TileCfg<256, 224, 8, 1, 32, 4> Cfg256x224;
+typedef TileCfg<128, 128, 2, 2, 32, 4> Cfg128x128;
 static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
 static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
 
@@ -253,7 +253,7 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   if (M <= 0 || N <= 0 || K <= 0) return fail(TL_ERR_INVALID_ARG, "M, N, K must be positive (got %d, %d, %d)", M, N, K);
   const int R = c.world_size;
   if (M % R) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d must divide M=%d", R, M);
-  if (K % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 64", K);
+  if (K % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 64", K);  // every tile shape steps K by 32 or 64
   if (N % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "N=%d must be a multiple of 8", N);
   memset(r, 0, sizeof *r);
   // ---- compute tile
@@ -282,6 +282,17 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   int G = c.compute_workgroups > 0 ? c.compute_workgroups : ctx->num_cus;
   if (G > r->n_tiles) G = r->n_tiles;
   r->G = G;
+  {
+    // group of row blocks walked together: a power of two that keeps a group inside one rank's rows
+    int per_rank = (r->nbm % R == 0) ? r->nbm / R : r->nbm;
+    int gm = c.group_m;
+    if (gm <= 0) {
+      gm = 1;
+      while (gm < 4 && per_rank % (gm * 2) == 0) gm *= 2;
+    }
+    if (gm > r->nbm) gm = r->nbm;
+    r->group_m = gm;
+  }
   int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : 16;
   r->n_comm = (c.comm_mode == TL_COMM_NONE) ? 0 : n_comm;
   // ---- communication tiles
@@ -332,6 +343,7 @@ static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
   s.G = r.G;
   s.first_block = r.first_block;
   s.swizzle = ctx->cfg.xcd_swizzle;
+  s.group_m = r.group_m;
   return s;
 }
 
@@ -389,7 +401,7 @@ int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
   if (cfg->channels_per_rank < 1) return fail(TL_ERR_INVALID_ARG, "channels_per_rank must be >= 1");
   if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_EXTERNAL) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
   if (cfg->tile_order != TL_ORDER_NATURAL && cfg->tile_order != TL_ORDER_RING) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
-  if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0)
+  if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0 || cfg->group_m < 0)
     return fail(TL_ERR_INVALID_ARG, "negative workgroup count or tile size");
   int dev = 0;
   TL_HIP(hipGetDevice(&dev));
@@ -415,7 +427,7 @@ int tl_resolve(const tl_ctx* ctx, int op, const long long* dims, int* info) {
   if (op != TL_OP_AG_GEMM && op != TL_OP_GEMM_RS) return fail(TL_ERR_INVALID_ARG, "tl_resolve: operator %d has no dense tile geometry", op);
   Resolved r;
   if (int e = resolve_dense(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], &r)) return e;
-  int v[12] = {r.tile_m, r.tile_n, 64, r.G, r.n_comm, r.Tm_p, r.Tn_p, r.n_tiles, r.n_ptm * r.n_ptn, r.expected, r.threads, r.lds_bytes};
+  int v[13] = {r.tile_m, r.tile_n, 64, r.G, r.n_comm, r.Tm_p, r.Tn_p, r.n_tiles, r.n_ptm * r.n_ptn, r.expected, r.threads, r.lds_bytes, r.group_m};
   memcpy(info, v, sizeof v);
   return TL_OK;
 }

@@ -61,13 +61,16 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
 // ---------------------------------------------------------------------------------------
 // Tile order.  Position p of the schedule is computed by persistent workgroup p % G in its
 // round p / G.  Inside a full round the workgroups of one die get a contiguous run of G/8
-// logical tiles; logical tiles are row-major over (row block, column block) with the row
-// blocks optionally rotated so that `first_block` comes first.
+// logical tiles.  Logical tiles walk groups of `group_m` row blocks: inside a group the column
+// block advances slowest and the row block fastest, so a run of consecutive logical tiles covers
+// a compact (group_m x few columns) patch whose A rows and B columns are shared in the die's L2.
+// Row blocks are optionally rotated so that `first_block` comes first.
 // ---------------------------------------------------------------------------------------
 struct Sched {
   int nbm, nbn, n_tiles, G;
   int first_block;  // rotation of row blocks (0 = natural)
   int swizzle;
+  int group_m;      // >= 1
 };
 
 __host__ __device__ inline int sched_tile(const Sched& s, int p) {
@@ -78,7 +81,12 @@ __host__ __device__ inline int sched_tile(const Sched& s, int p) {
     if (span > s.G) span = s.G;
     if (span % kXcds == 0) l = rnd * s.G + (w % kXcds) * (span / kXcds) + w / kXcds;
   }
-  int i = l / s.nbn, bn = l - i * s.nbn;
+  int per_group = s.group_m * s.nbn;
+  int g = l / per_group, within = l - g * per_group;
+  int gsz = s.nbm - g * s.group_m;  // row blocks in this group (the last group may be short)
+  if (gsz > s.group_m) gsz = s.group_m;
+  int bn = within / gsz;
+  int i = g * s.group_m + (within - bn * gsz);
   int bm = i + s.first_block;
   if (bm >= s.nbm) bm -= s.nbm;
   return bm * s.nbn + bn;

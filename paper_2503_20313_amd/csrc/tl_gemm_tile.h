@@ -2,10 +2,13 @@
 // (K contiguous), B row-major as [K,N] (N contiguous), fp32 accumulation, bf16 (RNE) output.
 //
 // Design (gfx950):
-//  * global -> LDS with 16-byte direct-to-LDS loads (no register staging), two stages; the
-//    bijection between 16-byte chunks and LDS slots is chosen so that the later fragment reads
-//    are bank-conflict free (A: chunk index XOR (row/2)%8; B with a power-of-two row pitch:
-//    64-byte group XOR k%4; B tiles 224 wide need none).
+//  * global -> LDS with 16-byte direct-to-LDS loads (no register staging) into a ring of NS
+//    stages of BK k-values each.  The loads of a stage are requested NS-1 steps before they are
+//    used, so that several stages are in flight per compute unit at any time: measured on
+//    MI355X, a single stage in flight leaves the kernel bound by the latency of the load path.
+//    The bijection between 16-byte chunks and LDS slots is chosen so that the later fragment
+//    reads are bank-conflict free (A: chunk index XOR a function of the row; B with a
+//    power-of-two row pitch: 64-byte group XOR k%4; B tiles 224 wide need none).
 //  * the MFMA "A" operand is taken from the B tile with transposing LDS reads
 //    (ds_read_b64_tr_b16: a 16-lane block reads 4 k-rows x 16 columns and hands each lane the
 //    4 k-values of its column), the MFMA "B" operand from the A tile with 16-byte reads; the
@@ -13,22 +16,43 @@
 //    4 consecutive columns of one row of C, i.e. 8-byte stores.
 //  * v_mfma_f32_32x32x16_bf16, wave tile (BM/WM) x (BN/WN).
 #pragma once
+#include <type_traits>
+
 #include "tl_device.h"
 
 namespace tl {
 
-template <int BM_, int BN_, int WM_, int WN_>
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+template <int BM_, int BN_, int WM_, int WN_, int BK_ = 32, int NS_ = 4>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WM = WM_, WN = WN_;
   static constexpr int NWAVES = WM * WN, NTHREADS = NWAVES * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 32, NT = WTN / 32;
-  static constexpr int A_LOADS = BM * 8 / 64;  // wave-wide 1 KiB loads per stage, A tile
-  static constexpr int B_CPR = BN / 8;         // 16-byte chunks per k-row of the B tile
-  static constexpr int B_LOADS = B_CPR;        // 64 k-rows * B_CPR chunks / 64 lanes
+  static constexpr int SL = BK / 16;              // 16-wide k-slices (one MFMA deep) per stage
+  static constexpr int A_CPR = BK / 8;            // 16-byte chunks per row of the A tile
+  static constexpr int A_RPB = 256 / (BK * 2);    // A rows per 256 bytes of LDS (all 64 banks)
+  static constexpr int A_PITCH = BK * 2;          // bytes per A row in LDS
+  static constexpr int A_LOADS = BM * A_CPR / 64; // wave-wide 1 KiB loads per stage, A tile
+  static constexpr int B_CPR = BN / 8;            // 16-byte chunks per k-row of the B tile
+  static constexpr int B_LOADS = BK * B_CPR / 64;
   static constexpr bool B_SWZ = (B_CPR % 16) == 0;
-  static constexpr int A_BYTES = BM * 128, B_BYTES = 64 * BN * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+  static constexpr int A_PER_WAVE = (A_LOADS + NWAVES - 1) / NWAVES;
+  static constexpr int B_PER_WAVE = (B_LOADS + NWAVES - 1) / NWAVES;
+  // Direct-to-LDS loads per stage issued by every wave.  Every wave issues the same number (the vmcnt
+  // bookkeeping relies on it): where the loads do not divide evenly, the surplus waves repeat the last one.
+  static constexpr int LPW = A_PER_WAVE + B_PER_WAVE;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+  static_assert(SL % 2 == 0, "fragment double buffering assumes an even number of k-slices per stage");
+  static_assert((NS - 1) * LPW <= 63, "vmcnt is a 6-bit counter");
 };
 
 __device__ __forceinline__ void lds_load16(const void* g, char* lds_wave_base) {
@@ -40,62 +64,71 @@ __device__ __forceinline__ short4_t lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 63, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Computes one output tile.  `a` points at the tile's first row (column 0), `b` at row 0 of B
 // at the tile's first column, `c` at the tile's first element.  rows/cols = valid extent of
-// the tile (ragged edges): loads are clamped to valid memory, stores are masked.  K % 64 == 0.
-// All threads of the workgroup must call it; it ends with all LDS reads complete.
+// the tile (ragged edges): loads are clamped to valid memory, stores are masked.
+// K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS reads complete.
 template <class Cfg>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const bf16_t* __restrict__ b, long ldb,
                                           bf16_t* __restrict__ c, long ldc, int rows, int cols, int K, char* smem) {
+  constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
 
   // ---- per-lane global addresses of this wave's share of the stage loads
-  constexpr int A_PER_WAVE = (Cfg::A_LOADS + Cfg::NWAVES - 1) / Cfg::NWAVES;
-  constexpr int B_PER_WAVE = (Cfg::B_LOADS + Cfg::NWAVES - 1) / Cfg::NWAVES;
-  const char* a_src[A_PER_WAVE];
-  const char* b_src[B_PER_WAVE];
+  const char* a_src[Cfg::A_PER_WAVE];
+  const char* b_src[Cfg::B_PER_WAVE];
 #pragma unroll
-  for (int i = 0; i < A_PER_WAVE; i++) {
-    int j = wave + i * Cfg::NWAVES;           // wave-load index: LDS slots [64j, 64j+64)
-    int row = j * 8 + (lane >> 3);
-    int chunk = (lane & 7) ^ ((row >> 1) & 7);  // logical 16-byte chunk stored at this slot
+  for (int i = 0; i < Cfg::A_PER_WAVE; i++) {
+    int j = wave + i * Cfg::NWAVES;  // wave-load index: LDS slots [64j, 64j+64)
+    if (j >= Cfg::A_LOADS) j = Cfg::A_LOADS - 1;
+    int slot = j * 64 + lane;
+    int row = slot / Cfg::A_CPR;
+    int chunk = (slot % Cfg::A_CPR) ^ ((row / Cfg::A_RPB) % Cfg::A_CPR);  // logical 16-byte chunk stored at this slot
     int grow = row < rows ? row : rows - 1;
     a_src[i] = (const char*)(a + (long)grow * lda + chunk * 8);
   }
 #pragma unroll
-  for (int i = 0; i < B_PER_WAVE; i++) {
+  for (int i = 0; i < Cfg::B_PER_WAVE; i++) {
     int j = wave + i * Cfg::NWAVES;
+    if (j >= Cfg::B_LOADS) j = Cfg::B_LOADS - 1;
     int slot = j * 64 + lane;
     int k = slot / Cfg::B_CPR, ncp = slot - k * Cfg::B_CPR;
     int nc = Cfg::B_SWZ ? (ncp ^ ((k & 3) << 2)) : ncp;
     int col = nc * 8 < cols ? nc * 8 : cols - 8;
     b_src[i] = (const char*)(b + (long)k * ldb + col);
   }
-  const long b_step = ldb * 64 * 2;  // bytes per K-step
+  const long b_step = ldb * Cfg::BK * 2;  // bytes per K-step
 
-  auto issue_stage = [&](int stage) {
-    char* sa = smem + stage * Cfg::STAGE_BYTES;
-    char* sb = sa + Cfg::A_BYTES;
-#pragma unroll
-    for (int i = 0; i < A_PER_WAVE; i++) {
-      int j = wave + i * Cfg::NWAVES;
-      if (Cfg::A_LOADS % Cfg::NWAVES == 0 || j < Cfg::A_LOADS) lds_load16(a_src[i], sa + j * 1024);
-      a_src[i] += 128;
-    }
-#pragma unroll
-    for (int i = 0; i < B_PER_WAVE; i++) {
-      int j = wave + i * Cfg::NWAVES;
-      if (Cfg::B_LOADS % Cfg::NWAVES == 0 || j < Cfg::B_LOADS) lds_load16(b_src[i], sb + j * 1024);
-      b_src[i] += b_step;
+  // Load number L (0..LPW-1) of this wave's share of the next stage in K order, into ring slot `slot`:
+  // loads 0..A_PER_WAVE-1 belong to the A tile, the rest to the B tile.  Advances that load's pointer.
+  auto issue_load = [&](int slot, auto l_c) {
+    constexpr int L = decltype(l_c)::value;
+    char* sa = smem + slot * Cfg::STAGE_BYTES;
+    if constexpr (L < Cfg::A_PER_WAVE) {
+      int j = wave + L * Cfg::NWAVES;
+      lds_load16(a_src[L], sa + (j < Cfg::A_LOADS ? j : Cfg::A_LOADS - 1) * 1024);
+      a_src[L] += Cfg::BK * 2;
+    } else {
+      constexpr int LB = L - Cfg::A_PER_WAVE;
+      int j = wave + LB * Cfg::NWAVES;
+      lds_load16(b_src[LB], sa + Cfg::A_BYTES + (j < Cfg::B_LOADS ? j : Cfg::B_LOADS - 1) * 1024);
+      b_src[LB] += b_step;
     }
   };
+  auto issue_stage = [&](int slot) { static_for<0, LPW>([&](auto l_c) { issue_load(slot, l_c); }); };
 
   // ---- per-lane LDS read offsets
   // A fragment (MFMA B operand): lane holds row (lane%32) of the wave's m-tile, k = 8*(lane/32)..+7 of the 16-wide k-slice.
   const int a_row = wm * Cfg::WTM + (lane & 31);
-  const int a_x = (lane >> 5) ^ ((a_row >> 1) & 7);
-  const int a_off = a_row * 128;
+  const int a_x = (lane >> 5) ^ ((a_row / Cfg::A_RPB) % Cfg::A_CPR);
+  const int a_off = a_row * Cfg::A_PITCH;
   // B fragment (MFMA A operand) via transposing reads: lane supplies the address of k-row
   // 8*(lane/32) + (lane%16)/4 (+4 for the second read), columns 16*((lane/16)%2) + 4*(lane%4)..+3.
   const int b_k = 8 * (lane >> 5) + ((lane & 15) >> 2);
@@ -117,39 +150,100 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[mt][nt][e] = 0.f;
 
-  const int nk = K / 64;
-  issue_stage(0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; kt++) {
-    if (kt + 1 < nk) issue_stage((kt + 1) & 1);
-    const char* sa = smem + (kt & 1) * Cfg::STAGE_BYTES;
-    const char* sb = sa + Cfg::A_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < 4; kk++) {
-      bf16x8 af[Cfg::MT], bfr[Cfg::NT];
-#pragma unroll
-      for (int mt = 0; mt < Cfg::MT; mt++)
-        af[mt] = *(const bf16x8*)(sa + a_off + mt * 32 * 128 + ((a_x ^ (2 * kk)) << 4));
-#pragma unroll
-      for (int nt = 0; nt < Cfg::NT; nt++) {
-        const char* p = sb + b_off[nt] + kk * 16 * Cfg::B_CPR * 16;
-        short4_t lo = lds_read_tr(p);
-        short4_t hi = lds_read_tr(p + 4 * Cfg::B_CPR * 16);
-        typedef short short8_t __attribute__((ext_vector_type(8)));
-        short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        bfr[nt] = __builtin_bit_cast(bf16x8, v);
-      }
-#pragma unroll
-      for (int mt = 0; mt < Cfg::MT; mt++)
-#pragma unroll
-        for (int nt = 0; nt < Cfg::NT; nt++)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
+  bf16x8 af[2][Cfg::MT], bfr[2][Cfg::NT];
+  // One LDS fragment read of k-slice `sl` of the stage at LDS address `st` into register set BUF:
+  // reads 0..NT-1 fetch the B fragments (two transposing reads each), NT..NT+MT-1 the A fragments.
+  constexpr int N_READS = Cfg::NT + Cfg::MT;
+  constexpr int N_MFMA = Cfg::MT * Cfg::NT;
+  auto read_frag = [&](const char* st, int sl, auto buf_c, auto r_c) {
+    constexpr int BUF = decltype(buf_c)::value, R = decltype(r_c)::value;
+    if constexpr (R < Cfg::NT) {
+      const char* p = st + Cfg::A_BYTES + b_off[R] + sl * 16 * Cfg::B_CPR * 16;
+      short4_t lo = lds_read_tr(p);
+      short4_t hi = lds_read_tr(p + 4 * Cfg::B_CPR * 16);
+      typedef short short8_t __attribute__((ext_vector_type(8)));
+      short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      bfr[BUF][R] = __builtin_bit_cast(bf16x8, v);
+    } else {
+      constexpr int MTI = R - Cfg::NT;
+      af[BUF][MTI] = *(const bf16x8*)(st + a_off + MTI * 32 * Cfg::A_PITCH + ((a_x ^ (2 * sl)) << 4));
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  // One k-slice in fixed program order: the MFMAs of the slice held in register set CUR, with the
+  // fragment reads of the following slice (k-slice rsl of the stage at rst) placed after the first
+  // MFMA, RPG per MFMA: no read sits between the wait for this slice's fragments and its first MFMA,
+  // and the last read still has several MFMAs of cover.  BS = position of the slice in the loop body
+  // (which spans SL slices): the LPW global loads of a newly requested stage are spread evenly over
+  // the body's MFMAs, one at a time, so that no wave sits in a full memory-instruction queue while
+  // its MFMAs wait behind it.
+  auto slice = [&](auto cur_c, auto bs_c, auto reads_c, const char* rst, int rsl, bool issue, int islot) {
+    constexpr int CUR = decltype(cur_c)::value, BS = decltype(bs_c)::value;
+    constexpr bool READS = decltype(reads_c)::value;
+    constexpr int GAPS = N_MFMA > 2 ? N_MFMA - 2 : 1;
+    constexpr int RPG = (N_READS + GAPS - 1) / GAPS;
+    static_for<0, N_MFMA>([&](auto m_c) {
+      constexpr int M = decltype(m_c)::value;
+      constexpr int MTI = M / Cfg::NT, NTI = M % Cfg::NT;
+      acc[MTI][NTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[CUR][NTI], af[CUR][MTI], acc[MTI][NTI], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (BS >= 0) {
+        constexpr int G = BS * N_MFMA + M;  // MFMA index inside the loop body
+        static_for<0, LPW>([&](auto l_c) {
+          constexpr int L = decltype(l_c)::value;
+          if constexpr (G == ((2 * L + 1) * SL * N_MFMA) / (2 * LPW)) {
+            if (issue) issue_load(islot, l_c);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        });
+      }
+      if constexpr (READS) {
+        static_for<M * RPG, ((M + 1) * RPG < N_READS ? (M + 1) * RPG : N_READS)>([&](auto r_c) {
+          read_frag(rst, rsl, std::integral_constant<int, CUR ^ 1>{}, r_c);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
+  };
+  using std::integral_constant;
+  typedef integral_constant<bool, true> yes;
+  typedef integral_constant<bool, false> no;
+
+  // K loop: BK per step, ring of NS LDS stages, stage s lives in slot s % NS.  The loop body starts at
+  // the barrier:
+  //   wait + barrier : stage s+1 has landed for every wave; nobody reads stage s from LDS any more
+  //                    (the fragments of its last slice are already in registers)
+  //   body slice 0   : multiply the last slice of stage s, read (stage s+1, slice 0)
+  //   body slice j>0 : multiply slice j-1 of stage s+1, read (stage s+1, slice j)
+  //   throughout     : request stage s+NS into the slot stage s just left, one load at a time
+  // The last NS bodies request nothing and wait for all outstanding loads instead.
+  const int nk = K / Cfg::BK;
+  const int n_pre = nk < NS ? nk : NS;
+  for (int s = 0; s < n_pre; s++) issue_stage(s);
+  if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
+  __syncthreads();
+  static_for<0, N_READS>([&](auto r_c) { read_frag(smem, 0, integral_constant<int, 0>{}, r_c); });
+  static_for<0, SL - 1>([&](auto sl_c) {
+    constexpr int S = decltype(sl_c)::value;
+    slice(integral_constant<int, S & 1>{}, integral_constant<int, -1>{}, yes{}, smem, S + 1, false, 0);
+  });
+
+  int slot = 0;  // s % NS
+  for (int s = 0; s + 1 < nk; s++) {
+    const int nslot = slot + 1 == NS ? 0 : slot + 1;
+    const char* nst = smem + nslot * Cfg::STAGE_BYTES;
+    const bool more = s + NS < nk;  // a further stage remains to be requested
+    // stage s+1 must have landed; while requests continue, the NS-2 younger stages may stay in flight
+    if (more) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
     __syncthreads();
+    slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nst, 0, more, slot);
+    static_for<0, SL - 1>([&](auto sl_c) {
+      constexpr int S = decltype(sl_c)::value;
+      slice(integral_constant<int, S & 1>{}, integral_constant<int, S + 1>{}, yes{}, nst, S + 1, more, slot);
+    });
+    slot = nslot;
   }
+  slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, smem, 0, false, 0);
+  __syncthreads();  // all LDS reads of this tile are complete before the next tile's loads
 
   // ---- epilogue: accumulator register e of lane l holds C[row = l%32][col = (e/4)*8 + (l/32)*4 + e%4]
   const int c_row = wm * Cfg::WTM + (lane & 31);

@@ -39,6 +39,7 @@ struct Resolved {
   int expected;          // producer tiles per channel (AG) ; not used by RS
   int threads, lds_bytes;
   int first_block;       // rotation of row blocks in the compute order
+  int group_m;           // row blocks per group of the compute order
 };
 
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r);

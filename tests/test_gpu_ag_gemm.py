@@ -139,14 +139,14 @@ def test_withheld_flag_times_out_instead_of_hanging():
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (5, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0), (2, tl.TL_ORDER_RING, 0)])
-def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
+@pytest.mark.parametrize("rank,order,swz,gm", [(0, tl.TL_ORDER_RING, 1, 0), (5, tl.TL_ORDER_RING, 1, 8), (3, tl.TL_ORDER_NATURAL, 0, 1), (2, tl.TL_ORDER_RING, 0, 3)])
+def test_schedule_dump_matches_mapping_oracle(rank, order, swz, gm):
     M, N, K, R, C = 8192, 3584, 8192, 8, 4
-    ctx = make_ctx(world_size=R, rank=rank, channels_per_rank=C, tile_order=order, xcd_swizzle=swz)
+    ctx = make_ctx(world_size=R, rank=rank, channels_per_rank=C, tile_order=order, xcd_swizzle=swz, group_m=gm)
     info = tl.tl_resolve(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
     got = tl.tl_dump_schedule(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
     want = omap.ag_gemm_schedule_records(M, N, K, R, C, rank, info["tile_m"], info["tile_n"], info["compute_workgroups"],
-                                         rotate=(order == tl.TL_ORDER_RING), swizzle=bool(swz))
+                                         rotate=(order == tl.TL_ORDER_RING), swizzle=bool(swz), group_m=info["group_m"])
     assert got == [v for rec in want for v in rec]
     assert info["expected_per_channel"] == omap.channel_expected(M, K, R, C, info["comm_tile_m"], info["comm_tile_n"])
     tl.tl_ctx_destroy(ctx)

@@ -1,0 +1,116 @@
+"""GPU parity of tl_gemm_rs against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_20313_amd as tl
+import tl_workloads as wl
+from oracle import mapping as omap
+from oracle import ops
+from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
+
+pytestmark = pytest.mark.gpu
+
+MODES = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM}
+
+
+def run_gemm_rs(w, mode, epochs=1, **cfg):
+    M, N, K, R, rank = w["M"], w["N"], w["K"], w["world"], w["rank"]
+    ctx = make_ctx(world_size=R, rank=rank, comm_mode=mode, **cfg)
+    ws_bytes, n_flags = tl.tl_query_workspace(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+    info = tl.tl_resolve(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+    seg = M // R
+    a, b = up(w["a"]), up(w["b"])
+    partial = poison((M, N))
+    recv = [None if q == rank else up(w["peer_segments"][q]) for q in range(R)]
+    push = [None if q == rank else poison((seg, N)) for q in range(R)]
+    out = poison((seg, N))
+    flags = torch.zeros(n_flags, dtype=torch.int32, device=dev())
+    wsp = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=dev())
+    comm = torch.cuda.Stream()
+    host_a = w["a"]
+    for epoch in range(1, epochs + 1):
+        if epoch > 1:
+            host_a = wl.normal_bf16(host_a.shape, 1.0, 78, epoch)
+            a.copy_(up(host_a))
+            out.copy_(poison((seg, N)))
+        torch.cuda.synchronize()
+        tl.tl_gemm_rs(ctx, a, b, partial, [0 if t is None else t for t in recv], [0 if t is None else t for t in push], out,
+                      M, N, K, flags, epoch, wsp, ws_bytes, torch.cuda.current_stream(), comm)
+        torch.cuda.synchronize()
+        tl.tl_check_status(ctx, wsp)
+    tl.tl_ctx_destroy(ctx)
+    return host_a, down(partial), [None if t is None else down(t) for t in push], down(out), flags.cpu().numpy(), info
+
+
+def check(w, host_a, partial, push, out, what):
+    R, rank = w["world"], w["rank"]
+    seg = w["M"] // R
+    p_ref, _, out_ref = ops.gemm_rs(host_a, w["b"], w["peer_segments"], rank)
+    assert_close_bf16(partial, p_ref, what + " partial")
+    for q in range(R):
+        if q != rank:
+            # what was pushed to peer q is exactly this rank's partial rows of segment q
+            assert np.array_equal(push[q], partial[q * seg:(q + 1) * seg]), f"{what}: push to peer {q}"
+    # the reduction of the GPU's own partial with the peers' rows, recomputed by the oracle: tight check of the reducer
+    own = partial[rank * seg:(rank + 1) * seg]
+    red = ops.reduce_scatter_segment(own, w["peer_segments"], rank)
+    from oracle.bf16 import round_to_bf16, widen
+    exact = round_to_bf16(red)
+    diff = np.abs(widen(out) - widen(exact))
+    assert np.all(diff <= np.abs(widen(exact)) * 2.0 ** -7 + 1e-30), f"{what}: reducer differs by more than one bf16 ulp"
+    assert np.mean(out != exact) < 0.02, f"{what}: too many last-bit differences in the reducer"
+    return assert_close_bf16(out, out_ref, what + " out")
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("rank", [0, 1])
+def test_small(mode, rank):
+    w = wl.gemm_rs_inputs(256, 512, 512, 2, rank, config_id=21)
+    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=3, comm_workgroups=2)
+    check(w, ha, partial, push, out, f"small {mode} r={rank}")
+    n_rt = info["n_comm_tiles"]
+    tps = n_rt // 2
+    ready, arrived, pushed = flags[:n_rt], flags[n_rt:n_rt + 2 * tps], flags[n_rt + 2 * tps:]
+    assert ready.tolist() == [3] * n_rt                          # one GEMM tile per reduce tile here
+    other = 1 - rank
+    assert arrived[other * tps:(other + 1) * tps].tolist() == [3] * tps and arrived[rank * tps:(rank + 1) * tps].tolist() == [0] * tps
+    assert pushed[other * tps:(other + 1) * tps].tolist() == [3] * tps and pushed[rank * tps:(rank + 1) * tps].tolist() == [0] * tps
+
+
+@pytest.mark.parametrize("tile,rt", [((256, 256), (56, 152)), ((256, 224), (140, 456)), ((128, 128), (280, 8)), ((128, 128), (20, 152))])
+def test_ragged_and_mismatched_reduce_tiles(tile, rt):
+    # 4 segments of 280 rows, N = 456: ragged for every GEMM tile; reduce tiles smaller and larger than GEMM tiles
+    w = wl.gemm_rs_inputs(1120, 456, 192, 4, 1, config_id=22)
+    ha, partial, push, out, flags, info = run_gemm_rs(w, tl.TL_COMM_WAVES, epochs=2, tile_m=tile[0], tile_n=tile[1],
+                                                      comm_tile_m=rt[0], comm_tile_n=rt[1], comm_workgroups=3)
+    check(w, ha, partial, push, out, f"ragged tile={tile} reduce={rt}")
+    table = omap.rs_tile_table(1120, 456, 4, 1, tile[0], tile[1], rt[0], rt[1])
+    assert flags[:len(table)].tolist() == [2 * e[7] for e in table]
+
+
+@pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (7, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0)])
+def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
+    M, N, K, R = 8192, 8192, 3584, 8
+    ctx = make_ctx(world_size=R, rank=rank, tile_order=order, xcd_swizzle=swz, comm_tile_m=128, comm_tile_n=512)
+    info = tl.tl_resolve(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+    got = tl.tl_dump_schedule(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+    rot = order == tl.TL_ORDER_RING
+    gemm = omap.gemm_rs_schedule_records(M, N, K, R, rank, info["tile_m"], info["tile_n"], 128, 512, info["compute_workgroups"], rot, bool(swz), info["group_m"])
+    table = omap.rs_tile_table(M, N, R, rank, info["tile_m"], info["tile_n"], 128, 512)
+    order_rs = omap.rs_consumer_order(M, N, R, rank, 128, 512, rot)
+    want = [v for rec in gemm for v in rec]
+    for t in order_rs:
+        cm, cn, rlo, rhi, clo, chi, dest, exp = table[t]
+        want += [t, cm, cn, rlo, rhi, clo, chi, dest, exp]
+    assert got == want
+    tl.tl_ctx_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode", ["waves", "side"])
+def test_full_size_tp8_share(mode):
+    """BASELINE configuration 3: A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]."""
+    w = wl.gemm_rs_inputs(8192, 8192, 3584, 8, 0, config_id=3)
+    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=2 if mode == "waves" else 1)
+    rel, mx = check(w, ha, partial, push, out, f"cfg3 {mode}")
+    print(f"cfg3 {mode}: tile {info['tile_m']}x{info['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")

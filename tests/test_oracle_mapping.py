@@ -118,3 +118,12 @@ def test_rs_tables():
     order = mp.rs_consumer_order(1024, 512, 4, 1, 128, 128)
     assert sorted(order) == list(range(32))
     assert order[:4] == [16, 17, 18, 19] and order[-4:] == [12, 13, 14, 15]
+
+
+def test_grouped_order_hand_example():
+    # 4 row blocks, 3 column blocks, groups of 2 row blocks: (0,0)(1,0)(0,1)(1,1)(0,2)(1,2) then rows 2,3
+    assert mp.logical_order(4, 3, 1, 0, False, 2) == [0, 3, 1, 4, 2, 5, 6, 9, 7, 10, 8, 11]
+    # a short last group (5 row blocks, groups of 2) and rotation by rank 1 of 5 ranks (1 block per rank)
+    assert mp.logical_order(5, 2, 5, 1, True, 2) == [2, 4, 3, 5, 6, 8, 7, 9, 0, 1]
+    for gm in (1, 2, 3, 4, 8):
+        assert sorted(mp.logical_order(7, 5, 1, 0, False, gm)) == list(range(35))
