@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--comm-mode", default="waves", choices=["waves", "side", "stream"])
+    ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream"])
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -87,10 +87,10 @@ def main():
     ms = torch.cuda.Stream()
 
     class Op:
-        def __init__(self, op, dims, comm_mode):
+        def __init__(self, op, dims, comm_mode, comm_alone=0):
             self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode,
                                         comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_RING, xcd_swizzle=1,
-                                        spin_timeout_us=10_000_000)
+                                        spin_timeout_us=10_000_000, comm_alone=comm_alone)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
             self.flags = torch.zeros(n_flags, dtype=torch.int32, device=dev)
@@ -100,6 +100,7 @@ def main():
 
         def __call__(self):
             self.epoch += 1
+            ms.wait_stream(cs)          # the producer of this call may not run ahead into the previous call's GEMM
             if self.op == tl.TL_OP_AG_GEMM:
                 tl.tl_ag_gemm(self.ctx, shards, gathered, b2, c2, M, N, K, self.flags, self.epoch, self.wsp, self.ws_bytes, cs, ms)
             else:
@@ -126,7 +127,7 @@ def main():
     res = {}
     ops_ = {}
     for name, op, dims in (("ag_gemm", tl.TL_OP_AG_GEMM, [M, N, K]), ("gemm_rs", tl.TL_OP_GEMM_RS, [M3, N3, K3])):
-        fused, alone, comm = Op(op, dims, mode), Op(op, dims, tl.TL_COMM_NONE), Op(op, dims, tl.TL_COMM_ONLY)
+        fused, alone, comm = Op(op, dims, mode), Op(op, dims, tl.TL_COMM_NONE), Op(op, dims, mode, comm_alone=1)
         if op == tl.TL_OP_AG_GEMM:
             fused()                      # leaves the gathered buffer complete for the compute-alone variant
             torch.cuda.synchronize()

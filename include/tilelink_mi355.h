@@ -53,8 +53,7 @@ enum { TL_COMM_NONE = 0,   /* data already in place: no producer runs, consumers
                               copy path (rank_copy_data + rank_notify); reduce work runs as a second kernel there */
        TL_COMM_SIDE_KERNEL = 3, /* device-side copy/reduce workgroups launched as a small-footprint kernel of their
                               own on comm_stream, so that they can share compute units with resident GEMM workgroups */
-       TL_COMM_ONLY = 4,   /* communication side alone (no GEMM tiles, producer-consumer waits skipped): for timing */
-       TL_COMM_EXTERNAL = 5 /* consumers wait on the flags but the library runs no producer: the caller (a peer,
+       TL_COMM_EXTERNAL = 4 /* consumers wait on the flags but the library runs no producer: the caller (a peer,
                               another library) moves the data and raises the flags itself */ };
 
 /* Tile order of the compute side. */
@@ -83,6 +82,8 @@ typedef struct tl_config {
   int xcd_swizzle;         /* 1: workgroups on one die take neighbouring tiles (see tl_dump_schedule) */
   int group_m;             /* row blocks walked together in the compute order (column block slowest inside a group); 0 = auto */
   unsigned spin_timeout_us;/* bound on every flag wait; 0 = unbounded */
+  int comm_alone;          /* 1: run only the communication side of comm_mode (no GEMM tiles; producer-consumer waits
+                              skipped, the GEMM's output is taken as already complete): for timing */
 } tl_config;
 
 typedef struct tl_ctx tl_ctx;

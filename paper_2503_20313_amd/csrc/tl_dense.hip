@@ -264,10 +264,13 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     if (v < 0) return fail(TL_ERR_UNSUPPORTED_SHAPE, "compute tile %dx%d is not one of 256x256, 256x224, 128x128", c.tile_m, c.tile_n);
   } else if ((long)M * N <= 1024L * 1024L) {
     v = TILE_128x128;
-  } else if (N % 256 != 0 && N % 224 == 0) {
-    v = TILE_256x224;
   } else {
-    v = TILE_256x256;
+    // 256x256 unless the 224-wide tile divides N and fills the last round of workgroups better
+    auto fill = [&](int tm, int tn) {
+      long tiles = (long)ceil_div(M, tm) * ceil_div(N, tn), G = ctx->num_cus;
+      return (double)((long)M * N) / ((double)((tiles + G - 1) / G * G) * tm * tn);
+    };
+    v = (N % 224 == 0 && fill(256, 224) > fill(256, 256) + 1e-9) ? TILE_256x224 : TILE_256x256;
   }
   r->variant = v;
   r->tile_m = kTileM[v];
@@ -293,7 +296,9 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     if (gm > r->nbm) gm = r->nbm;
     r->group_m = gm;
   }
-  int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : 16;
+  // in-kernel communication workgroups each take a compute unit's worth of LDS and registers; as a kernel of
+  // their own they are small and share compute units with the GEMM, so many more of them pay off
+  int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : 128);
   r->n_comm = (c.comm_mode == TL_COMM_NONE) ? 0 : n_comm;
   // ---- communication tiles
   if (op == TL_OP_AG_GEMM) {
@@ -493,31 +498,34 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
   p.ctl = make_ctl(ctx, workspace);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
+  const bool alone = cfg.comm_alone != 0;  // communication side only (timing)
+  if (alone && (cfg.comm_mode == TL_COMM_NONE || cfg.comm_mode == TL_COMM_EXTERNAL))
+    return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: comm_alone needs a comm_mode in which the library runs a producer");
+  p.do_compute = alone ? 0 : 1;
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
-      p.n_comm = 0; p.do_compute = 1; p.do_wait = 0;
+      p.n_comm = 0; p.do_wait = 0;
       return launch_ag_gemm(r.variant, p, r.G, cs);
     case TL_COMM_WAVES:
-      p.n_comm = r.n_comm; p.do_compute = 1; p.do_wait = 1;
+      p.n_comm = r.n_comm; p.do_wait = 1;
       p.wait_target = epoch * (unsigned)r.expected;
-      return launch_ag_gemm(r.variant, p, r.G + r.n_comm, cs);
-    case TL_COMM_ONLY:
-      p.n_comm = r.n_comm; p.do_compute = 0; p.do_wait = 0;
-      return launch_ag_gemm(r.variant, p, r.n_comm, cs);
+      return launch_ag_gemm(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
-      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      p.n_comm = 0; p.do_wait = 1;
       p.wait_target = epoch * (unsigned)r.expected;
       return launch_ag_gemm(r.variant, p, r.G, cs);
     case TL_COMM_SIDE_KERNEL: {
-      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      // The producer is enqueued first: it waits for nothing, so even if both streams end up on one
+      // hardware queue the worst case is that the two kernels run one after the other.
+      p.n_comm = 0; p.do_wait = 1;
       p.wait_target = epoch * (unsigned)r.expected;
       hipLaunchKernelGGL(ag_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
       TL_HIP(hipGetLastError());
-      return launch_ag_gemm(r.variant, p, r.G, cs);
+      return alone ? TL_OK : launch_ag_gemm(r.variant, p, r.G, cs);
     }
     case TL_COMM_STREAM: {
       // rank_copy_data + rank_notify per source rank, ring order, through the runtime's copy path
-      p.n_comm = 0; p.do_compute = 1; p.do_wait = 1;
+      p.n_comm = 0; p.do_wait = 1;
       p.wait_target = epoch;
       const size_t shard_bytes = (size_t)r.rows_per_rank * K * sizeof(bf16_t);
       for (int i = 0; i < R; i++) {
@@ -527,7 +535,7 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
         hipLaunchKernelGGL(notify_kernel, dim3(1), dim3(64), 0, ms, flags + q * cfg.channels_per_rank, cfg.channels_per_rank, 1u);
         TL_HIP(hipGetLastError());
       }
-      return launch_ag_gemm(r.variant, p, r.G, cs);
+      return alone ? TL_OK : launch_ag_gemm(r.variant, p, r.G, cs);
     }
   }
   return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: unknown comm_mode");
@@ -578,27 +586,30 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
     return TL_OK;
   };
 
+  const bool alone = cfg.comm_alone != 0;  // reduce/push side only, on a partial product that is already complete
+  p.do_compute = alone ? 0 : 1;
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
-      p.n_comm = 0; p.do_compute = 1; p.do_notify = 0; p.do_wait = 0;
+      if (alone) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: comm_alone needs a comm_mode with a reduce side");
+      p.n_comm = 0; p.do_notify = 0; p.do_wait = 0;
       return launch_gemm_rs(r.variant, p, r.G, cs);
     case TL_COMM_WAVES:
-      if (int e = peers_arrive(ms)) return e;
-      p.n_comm = r.n_comm; p.do_compute = 1; p.do_notify = 1; p.do_wait = 1;
-      return launch_gemm_rs(r.variant, p, r.G + r.n_comm, cs);
-    case TL_COMM_ONLY:
-      if (int e = peers_arrive(cs)) return e;
-      p.n_comm = r.n_comm; p.do_compute = 0; p.do_notify = 0; p.do_wait = 0;
-      return launch_gemm_rs(r.variant, p, r.n_comm, cs);
+      if (int e = peers_arrive(alone ? cs : ms)) return e;
+      p.n_comm = r.n_comm; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      return launch_gemm_rs(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
       return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: TL_COMM_EXTERNAL is not defined for this operator");
     case TL_COMM_STREAM:
     case TL_COMM_SIDE_KERNEL: {
+      // The GEMM kernel is enqueued before the reduce kernel that waits on it: should both streams share a
+      // hardware queue, the reduce kernel then simply runs after the GEMM instead of blocking it.
+      p.n_comm = 0; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      if (!alone)
+        if (int e = launch_gemm_rs(r.variant, p, r.G, cs)) return e;
       if (int e = peers_arrive(ms)) return e;
-      p.n_comm = 0; p.do_compute = 1; p.do_notify = 1; p.do_wait = 1;
       hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
       TL_HIP(hipGetLastError());
-      return launch_gemm_rs(r.variant, p, r.G, cs);
+      return TL_OK;
     }
   }
   return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: unknown comm_mode");
