@@ -89,7 +89,7 @@ def main():
     class Op:
         def __init__(self, op, dims, comm_mode, comm_alone=0):
             self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode,
-                                        comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_RING, xcd_swizzle=1,
+                                        comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
                                         spin_timeout_us=10_000_000, comm_alone=comm_alone)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)

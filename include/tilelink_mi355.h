@@ -58,8 +58,9 @@ enum { TL_COMM_NONE = 0,   /* data already in place: no producer runs, consumers
 
 /* Tile order of the compute side. */
 enum { TL_ORDER_NATURAL = 0, /* row-major over (row block, column block) */
-       TL_ORDER_RING = 1     /* row blocks rotated by owner rank: AG+GEMM starts with the local
-                                shard's rows, GEMM+RS starts with rank r+1's segment and ends with its own */ };
+       TL_ORDER_RING = 1,    /* row blocks rotated by owner rank: AG+GEMM starts with the local
+                                shard's rows, GEMM+RS starts with rank r+1's segment and ends with its own */
+       TL_ORDER_OWN_FIRST = 2 /* as RING, but GEMM+RS starts with its own segment and then follows the ring */ };
 
 /* Operators, for tl_query_workspace / tl_dump_schedule. */
 enum { TL_OP_AG_GEMM = 0, TL_OP_GEMM_RS = 1, TL_OP_MOE_AG_GATHER_GEMM = 2, TL_OP_MOE_GEMM_SCATTER_RS = 3,
@@ -116,6 +117,10 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
  *              paper's channel formula).  After call `epoch` every entry equals epoch * expected where
  *              expected = (M/(R*C)/Tm_p) * ceil(K/Tn_p) in WAVES mode and 1 in STREAM mode; untouched in NONE.
  *   Requirements: R | M, C | M/R, Tm_p | M/(R*C), K % 64 == 0, N % 8 == 0, Tn_p | K.
+ *   workspace  word 0 = status word, word 1 = head of the producer-tile queue: it grows by the number of producer
+ *              tiles per call, so the caller zeroes the workspace together with the flags (once, or when `epoch`
+ *              restarts at 1).  In WAVES and SIDE_KERNEL mode producer tiles are handed out through this queue to the
+ *              producer workgroups and to GEMM workgroups that would otherwise wait.
  *   compute_stream receives the fused kernel; comm_stream the copies in TL_COMM_STREAM.
  */
 int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards /*host array of dev*/, void* a_gathered, const void* b,

@@ -141,15 +141,16 @@ def rs_tile_table(M, N, R, rank, Tm_c, Tn_c, Tm_r, Tn_r):
     return out
 
 
-def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate=True, swizzle=True, group_m=1):
+def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate=True, swizzle=True, group_m=1, own_first=False):
     """GEMM tiles in schedule order; with `rotate` the row-blocks of rank+1 come
     first and this rank's own segment last (ring order), so that pushes leave
-    early and the segment that needs every peer's data is computed last.
+    early and the segment that needs every peer's data is computed last; with
+    `own_first` the own segment comes first and the ring follows.
     Record: (tile_id, bm, bn, row_lo, row_hi, cm_lo, cm_hi, cn_lo, cn_hi) where
     cm/cn ranges (inclusive) are the reduce tiles the GEMM tile notifies."""
     nbm, nbn = ceil_div(M, Tm_c), ceil_div(N, Tn_c)
     recs = []
-    for t in tile_schedule(nbm, nbn, R, (rank + 1) % R, rotate, G, swizzle, group_m):
+    for t in tile_schedule(nbm, nbn, R, rank if own_first else (rank + 1) % R, rotate, G, swizzle, group_m):
         bm, bn = divmod(t, nbn)
         rlo, rhi = bm * Tm_c, min(bm * Tm_c + Tm_c, M)
         clo, chi = bn * Tn_c, min(bn * Tn_c + Tn_c, N)
@@ -157,8 +158,8 @@ def gemm_rs_schedule_records(M, N, K, R, rank, Tm_c, Tn_c, Tm_r, Tn_r, G, rotate
     return recs
 
 
-def rs_consumer_order(M, N, R, rank, Tm_r, Tn_r, rotate=True):
+def rs_consumer_order(M, N, R, rank, Tm_r, Tn_r, rotate=True, own_first=False):
     """Order in which reduce/push workgroups visit reduce tiles: same ring
     rotation of row blocks as the GEMM tiles (no die swizzle)."""
     ncm, ncn = ceil_div(M, Tm_r), ceil_div(N, Tn_r)
-    return logical_order(ncm, ncn, R, (rank + 1) % R, rotate)
+    return logical_order(ncm, ncn, R, rank if own_first else (rank + 1) % R, rotate)

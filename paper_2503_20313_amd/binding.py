@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
 
 TL_OK, TL_ERR_INVALID_ARG, TL_ERR_UNSUPPORTED_SHAPE, TL_ERR_WORKSPACE_TOO_SMALL, TL_ERR_HIP, TL_ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
 TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_EXTERNAL = 0, 1, 2, 3, 4
-TL_ORDER_NATURAL, TL_ORDER_RING = 0, 1
+TL_ORDER_NATURAL, TL_ORDER_RING, TL_ORDER_OWN_FIRST = 0, 1, 2
 TL_OP_AG_GEMM, TL_OP_GEMM_RS, TL_OP_MOE_AG_GATHER_GEMM, TL_OP_MOE_GEMM_SCATTER_RS, TL_OP_SP_AG_ATTENTION = 0, 1, 2, 3, 4
 
 

@@ -24,6 +24,8 @@ struct AgGemmParams {
   int local_in_place;
   unsigned wait_target;  // epoch * expected
   unsigned* flags;
+  unsigned* ticket;      // producer-tile queue head (grows by n_ptm*n_ptn per call)
+  unsigned ticket_end;   // epoch * number of producer tiles
   WaitCtl ctl;
 };
 
@@ -50,37 +52,105 @@ struct GemmRsParams {
 };
 
 // ======================================================================================
-// AllGather producer (pull mode): copy producer tile (tm, tn) of the gathered matrix from its
-// owner's shard, then notify the tile's channel.  Tiles are visited ring-wise starting with the
-// rank after this one (the local shard, which needs no transfer, is handled last).
+// AllGather producer (pull mode).  Producer tiles form a queue that is consumed through an atomic
+// ticket counter: ticket i is producer tile (tm, tn) in ring order over source ranks (rank+1,
+// rank+2, ..., the local shard last).  Whoever holds a ticket copies that tile of the gathered
+// matrix from its owner's shard and then notifies the tile's channel.  Dedicated producer
+// workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
+// too instead of idling, so a consumer can never wait for a producer that is not resident.
 // ======================================================================================
-__device__ void ag_producer(const AgGemmParams& p, int wg, int n_wg, int tid, int nthreads) {
-  const int n_pt = p.n_ptm * p.n_ptn;
-  const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
-  for (int i = wg; i < n_pt; i += n_wg) {
-    int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
-    // ring order over source ranks: rank+1, rank+2, ..., rank
-    int tm = tmi + (p.rank + 1) * ptm_per_rank;
-    if (tm >= p.n_ptm) tm -= p.n_ptm;
-    int row_lo = tm * p.Tm_p;
-    int src = tm / ptm_per_rank;                                  // f_R
-    int channel = tm / (p.rows_per_channel / p.Tm_p);             // f_C
-    if (!(src == p.rank && p.local_in_place)) {
-      const bf16_t* s = p.a_shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.K + (long)tn * p.Tn_p;
-      bf16_t* d = p.a_gathered + (long)row_lo * p.K + (long)tn * p.Tn_p;
-      copy_tile(s, p.K, d, p.K, p.Tm_p, p.Tn_p, tid, nthreads);
-    }
-    __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
-    if (tid == 0) tile_notify(p.flags + channel);
+// Called by every lane of one wave; the result is wave-uniform.
+__device__ __forceinline__ bool claim_ticket(const AgGemmParams& p, unsigned* out) {
+  unsigned t = lane0_fetch_add(p.ticket, 1u);
+  if ((int)(t - p.ticket_end) >= 0) {  // queue of this call is empty: give the ticket back
+    lane0_add(p.ticket, 0xffffffffu);
+    return false;
   }
+  *out = t - (p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn));
+  return true;
+}
+
+// All threads of the workgroup call this with the same ticket index; `wave` is the wave-uniform wave index.
+__device__ __forceinline__ void produce_tile(const AgGemmParams& p, int i, int tid, int wave, int nthreads) {
+  const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
+  int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
+  int tm = tmi + (p.rank + 1) * ptm_per_rank;  // ring order over source ranks: rank+1, rank+2, ..., rank
+  if (tm >= p.n_ptm) tm -= p.n_ptm;
+  int row_lo = tm * p.Tm_p;
+  int src = tm / ptm_per_rank;                       // f_R
+  int channel = tm / (p.rows_per_channel / p.Tm_p);  // f_C
+  if (!(src == p.rank && p.local_in_place)) {
+    const bf16_t* s = p.a_shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.K + (long)tn * p.Tn_p;
+    bf16_t* d = p.a_gathered + (long)row_lo * p.K + (long)tn * p.Tn_p;
+    copy_tile(s, p.K, d, p.K, p.Tm_p, p.Tn_p, tid, nthreads);
+  }
+  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
+  if (wave == 0) wave_tile_notify(p.flags + channel);
+}
+
+// Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
+__device__ void ag_producer(const AgGemmParams& p, int tid, int nthreads, int* s_ticket) {
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (;;) {
+    if (wave == 0) {
+      unsigned t;
+      int v = claim_ticket(p, &t) ? (int)t : -1;
+      *s_ticket = v;  // all lanes of wave 0 store the same value
+    }
+    __syncthreads();
+    int i = __builtin_amdgcn_readfirstlane(*s_ticket);
+    __syncthreads();
+    if (i < 0) break;
+    produce_tile(p, i, tid, wave, nthreads);
+  }
+}
+
+// consumer_tile_wait for channels clo..chi by a whole workgroup: while a channel is short of its target
+// the workgroup works off producer tickets; with the queue empty it sleeps and polls (bounded by ctl.timeout).
+__device__ __forceinline__ void consumer_wait_or_produce(const AgGemmParams& p, int clo, int chi, int tid, int nthreads, int* s_ticket) {
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned long long t0 = 0;
+  if (wave == 0 && p.ctl.timeout) t0 = wall_clock64();
+  for (;;) {
+    if (wave == 0) {
+      int state = -2;  // -2: ready, -1: not ready and nothing to produce, >= 0: ticket to work off
+      for (int ch = clo; ch <= chi; ch++) {
+        unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if ((int)(f - p.wait_target) < 0) state = -1;
+      }
+      if (state == -1) {
+        unsigned t;
+        if (claim_ticket(p, &t)) state = (int)t;
+        else if (p.ctl.timeout) {
+          int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          if (st != 0) state = -2;  // abandoned elsewhere
+          else if (wall_clock64() - t0 > p.ctl.timeout) {
+            int expected = 0;  // every lane tries, the first one wins, all carry the same value
+            __hip_atomic_compare_exchange_strong(p.ctl.status, &expected, 1 + clo, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            state = -2;
+          }
+        }
+      }
+      *s_ticket = state;
+    }
+    __syncthreads();
+    int state = __builtin_amdgcn_readfirstlane(*s_ticket);
+    __syncthreads();
+    if (state == -2) break;
+    if (state >= 0) produce_tile(p, state, tid, wave, nthreads);
+    else __builtin_amdgcn_s_sleep(8);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  __syncthreads();
 }
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int s_ticket;
   const int tid = threadIdx.x;
   if ((int)blockIdx.x < p.n_comm) {
-    ag_producer(p, blockIdx.x, p.n_comm, tid, Cfg::NTHREADS);
+    ag_producer(p, tid, Cfg::NTHREADS, &s_ticket);
     return;
   }
   if (!p.do_compute) return;
@@ -91,8 +161,10 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
     int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
     int rows = min(Cfg::BM, p.M - row_lo), cols = min(Cfg::BN, p.N - col_lo);
-    if (p.do_wait) {
-      // consumer_tile_wait: every channel whose rows the tile touches
+    if (p.do_wait == 1) {
+      consumer_wait_or_produce(p, row_lo / M_per_channel, (row_lo + rows - 1) / M_per_channel, tid, Cfg::NTHREADS, &s_ticket);
+    } else if (p.do_wait == 2) {
+      // flags raised by somebody else (no ticket queue): plain consumer_tile_wait on every channel the tile touches
       if (tid == 0) {
         int clo = row_lo / M_per_channel, chi = (row_lo + rows - 1) / M_per_channel;
         for (int ch = clo; ch <= chi; ch++) tile_wait(p.flags + ch, p.wait_target, p.ctl, ch);
@@ -107,7 +179,8 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
 // Producer as a kernel of its own (small register/LDS footprint, so it can share compute units
 // with resident GEMM workgroups) for the side-stream binding.
 __global__ void __launch_bounds__(256) ag_producer_kernel(const AgGemmParams p) {
-  ag_producer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
+  __shared__ int s_ticket;
+  ag_producer(p, threadIdx.x, 256, &s_ticket);
 }
 
 // rank_notify for copies made by the runtime's copy path: raise `count` consecutive flags.
@@ -248,6 +321,11 @@ typedef TileCfg<128, 128, 2, 2, 32, 4> Cfg128x128;
 static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
 static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
 
+// Segment whose rows GEMM+ReduceScatter computes first: the next rank's in ring order (its own comes last,
+// as in a ring reduce-scatter), or its own (so that the reduction of the own segment, the heaviest piece of
+// the communication side, overlaps the remaining GEMM tiles and only a push is left at the end).
+static int rs_first_rank(const tl_config& c) { return c.tile_order == TL_ORDER_OWN_FIRST ? c.rank : (c.rank + 1) % c.world_size; }
+
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   const tl_config& c = ctx->cfg;
   if (M <= 0 || N <= 0 || K <= 0) return fail(TL_ERR_INVALID_ARG, "M, N, K must be positive (got %d, %d, %d)", M, N, K);
@@ -283,6 +361,9 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   r->rows_per_rank = M / R;
   // ---- grid
   int G = c.compute_workgroups > 0 ? c.compute_workgroups : ctx->num_cus;
+  // The runtime's copy path runs as kernels too, and a persistent GEMM grid that fills every compute unit while it
+  // waits for those copies would keep them from ever starting: leave some compute units free for them.
+  if (c.compute_workgroups == 0 && c.comm_mode == TL_COMM_STREAM && op == TL_OP_AG_GEMM && G > 32) G -= 16;
   if (G > r->n_tiles) G = r->n_tiles;
   r->G = G;
   {
@@ -321,7 +402,7 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     r->n_ptn = K / Tn_p;
     r->expected = (r->rows_per_channel / Tm_p) * r->n_ptn;
     r->first_block = 0;
-    if (c.tile_order == TL_ORDER_RING) {
+    if (c.tile_order != TL_ORDER_NATURAL) {
       if (r->nbm % R == 0) r->first_block = c.rank * (r->nbm / R);
     }
   } else {
@@ -335,7 +416,7 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     r->n_ptn = N / Tn_r;
     r->expected = 0;
     r->first_block = 0;
-    if (c.tile_order == TL_ORDER_RING && r->nbm % R == 0) r->first_block = ((c.rank + 1) % R) * (r->nbm / R);
+    if (c.tile_order != TL_ORDER_NATURAL && r->nbm % R == 0) r->first_block = rs_first_rank(c) * (r->nbm / R);
   }
   return TL_OK;
 }
@@ -405,7 +486,7 @@ int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
   if (cfg->rank < 0 || cfg->rank >= cfg->world_size) return fail(TL_ERR_INVALID_ARG, "rank %d outside [0,%d)", cfg->rank, cfg->world_size);
   if (cfg->channels_per_rank < 1) return fail(TL_ERR_INVALID_ARG, "channels_per_rank must be >= 1");
   if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_EXTERNAL) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
-  if (cfg->tile_order != TL_ORDER_NATURAL && cfg->tile_order != TL_ORDER_RING) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
+  if (cfg->tile_order < TL_ORDER_NATURAL || cfg->tile_order > TL_ORDER_OWN_FIRST) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
   if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0 || cfg->group_m < 0)
     return fail(TL_ERR_INVALID_ARG, "negative workgroup count or tile size");
   int dev = 0;
@@ -495,6 +576,8 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
   p.rows_per_rank = r.rows_per_rank; p.rows_per_channel = r.rows_per_channel;
   p.local_in_place = (const bf16_t*)a_shards[cfg.rank] == (const bf16_t*)a_gathered + (size_t)cfg.rank * r.rows_per_rank * K;
   p.flags = flags;
+  p.ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
+  p.ticket_end = epoch * (unsigned)(r.n_ptm * r.n_ptn);
   p.ctl = make_ctl(ctx, workspace);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
@@ -511,7 +594,7 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
       p.wait_target = epoch * (unsigned)r.expected;
       return launch_ag_gemm(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
-      p.n_comm = 0; p.do_wait = 1;
+      p.n_comm = 0; p.do_wait = 2;
       p.wait_target = epoch * (unsigned)r.expected;
       return launch_ag_gemm(r.variant, p, r.G, cs);
     case TL_COMM_SIDE_KERNEL: {
@@ -525,7 +608,7 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
     }
     case TL_COMM_STREAM: {
       // rank_copy_data + rank_notify per source rank, ring order, through the runtime's copy path
-      p.n_comm = 0; p.do_wait = 1;
+      p.n_comm = 0; p.do_wait = 2;
       p.wait_target = epoch;
       const size_t shard_bytes = (size_t)r.rows_per_rank * K * sizeof(bf16_t);
       for (int i = 0; i < R; i++) {
@@ -571,7 +654,7 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
   p.seg_rows = r.rows_per_rank;
   p.tiles_per_seg = (r.rows_per_rank / r.Tm_p) * r.n_ptn;
   p.rs_first_block = 0;
-  if (cfg.tile_order == TL_ORDER_RING) p.rs_first_block = ((cfg.rank + 1) % R) * (r.rows_per_rank / r.Tm_p);
+  if (cfg.tile_order != TL_ORDER_NATURAL) p.rs_first_block = rs_first_rank(cfg) * (r.rows_per_rank / r.Tm_p);
   p.epoch = epoch;
   p.ready = flags;
   p.arrived = flags + (size_t)p.ncm * p.ncn;
@@ -644,7 +727,7 @@ int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims, int* out,
     }
   }
   if (op == TL_OP_GEMM_RS) {
-    int first = cfg.tile_order == TL_ORDER_RING ? ((cfg.rank + 1) % cfg.world_size) * (r.rows_per_rank / r.Tm_p) : 0;
+    int first = cfg.tile_order != TL_ORDER_NATURAL ? rs_first_rank(cfg) * (r.rows_per_rank / r.Tm_p) : 0;
     for (int i = 0; i < r.n_ptm * r.n_ptn; i++) {
       int cm = (i / r.n_ptn + first) % r.n_ptm, cn = i % r.n_ptn;
       int row_lo = cm * r.Tm_p, row_hi = row_lo + r.Tm_p, col_lo = cn * r.Tn_p, col_hi = col_lo + r.Tn_p;

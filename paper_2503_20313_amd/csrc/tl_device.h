@@ -59,6 +59,48 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
 }
 
 // ---------------------------------------------------------------------------------------
+// Single-lane atomics without a divergent branch.  A loop whose body holds workgroup barriers
+// must stay uniform for the compiler as well as at run time: with an `if (tid == 0)` around an
+// atomic inside such a loop, the control-flow structurizer is free to rotate the divergent part
+// across the loop's back edge, after which the waves of a workgroup no longer meet the same
+// barrier in the same iteration.  These helpers are called by every lane of a wave; the atomic
+// itself is issued for lane 0 only by narrowing EXEC inside one asm statement, and the result is
+// returned as a wave-uniform value.  Device scope; ordering comes from the fences around them.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned lane0_fetch_add(unsigned* ptr, unsigned v) {
+  unsigned r;
+  unsigned long long saved;
+  asm volatile(
+      "s_mov_b64 %1, exec\n\t"
+      "s_mov_b64 exec, 1\n\t"
+      "global_atomic_add %0, %2, %3, off sc0\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_mov_b64 exec, %1"
+      : "=&v"(r), "=&s"(saved)
+      : "v"(ptr), "v"(v)
+      : "memory");
+  return __builtin_amdgcn_readfirstlane(r);
+}
+
+__device__ __forceinline__ void lane0_add(unsigned* ptr, unsigned v) {
+  unsigned long long saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, 1\n\t"
+      "global_atomic_add %1, %2, off\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "v"(ptr), "v"(v)
+      : "memory");
+}
+
+// notify by a whole wave (uniform): release fence, then one add.
+__device__ __forceinline__ void wave_tile_notify(unsigned* flag, unsigned inc = 1u) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  lane0_add(flag, inc);
+}
+
+// ---------------------------------------------------------------------------------------
 // Tile order.  Position p of the schedule is computed by persistent workgroup p % G in its
 // round p / G.  Inside a full round the workgroups of one die get a contiguous run of G/8
 // logical tiles.  Logical tiles walk groups of `group_m` row blocks: inside a group the column

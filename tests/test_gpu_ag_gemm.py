@@ -165,11 +165,14 @@ def test_invalid_arguments_are_rejected_before_launch():
 
 @pytest.mark.parametrize("mode", ["waves", "side", "stream"])
 def test_full_size_tp8_share(mode):
-    """BASELINE configuration 2: 8 shards of [1024,8192], B [8192,3584]; whole output compared."""
+    """BASELINE configuration 2: 8 shards of [1024,8192], B [8192,3584]; whole output compared.  `side` is the
+    launch configuration bench.py times.  In `stream` mode the copies are kernels of the runtime that must become
+    resident beside the persistent GEMM grid, so that case leaves a quarter of the compute units to them."""
     w = wl.ag_gemm_inputs(8192, 3584, 8192, 8, config_id=2)
     a_ref, _, c_ref = ops.ag_gemm(w["a_shards"], w["b"])
-    hs, g, c, flags, info = run_ag_gemm(w, 0, 4, MODES[mode], epochs=2 if mode == "waves" else 1)
-    if mode == "waves":
+    extra = dict(compute_workgroups=192, tile_m=256, tile_n=256) if mode == "stream" else {}
+    hs, g, c, flags, info = run_ag_gemm(w, 0, 4, MODES[mode], epochs=2 if mode != "stream" else 1, **extra)
+    if mode != "stream":
         a_ref, _, c_ref = ops.ag_gemm(hs, w["b"])
     assert np.array_equal(g, a_ref)
     rel, mx = assert_close_bf16(c, c_ref, f"cfg2 {mode}")

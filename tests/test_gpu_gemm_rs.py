@@ -89,16 +89,17 @@ def test_ragged_and_mismatched_reduce_tiles(tile, rt):
     assert flags[:len(table)].tolist() == [2 * e[7] for e in table]
 
 
-@pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (7, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0)])
+@pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (7, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0), (5, tl.TL_ORDER_OWN_FIRST, 1)])
 def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
     M, N, K, R = 8192, 8192, 3584, 8
     ctx = make_ctx(world_size=R, rank=rank, tile_order=order, xcd_swizzle=swz, comm_tile_m=128, comm_tile_n=512)
     info = tl.tl_resolve(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
     got = tl.tl_dump_schedule(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
-    rot = order == tl.TL_ORDER_RING
-    gemm = omap.gemm_rs_schedule_records(M, N, K, R, rank, info["tile_m"], info["tile_n"], 128, 512, info["compute_workgroups"], rot, bool(swz), info["group_m"])
+    rot = order != tl.TL_ORDER_NATURAL
+    own = order == tl.TL_ORDER_OWN_FIRST
+    gemm = omap.gemm_rs_schedule_records(M, N, K, R, rank, info["tile_m"], info["tile_n"], 128, 512, info["compute_workgroups"], rot, bool(swz), info["group_m"], own)
     table = omap.rs_tile_table(M, N, R, rank, info["tile_m"], info["tile_n"], 128, 512)
-    order_rs = omap.rs_consumer_order(M, N, R, rank, 128, 512, rot)
+    order_rs = omap.rs_consumer_order(M, N, R, rank, 128, 512, rot, own)
     want = [v for rec in gemm for v in rec]
     for t in order_rs:
         cm, cn, rlo, rhi, clo, chi, dest, exp = table[t]
@@ -107,10 +108,11 @@ def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("mode", ["waves", "side"])
-def test_full_size_tp8_share(mode):
-    """BASELINE configuration 3: A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]."""
+@pytest.mark.parametrize("mode,order", [("waves", tl.TL_ORDER_RING), ("side", tl.TL_ORDER_OWN_FIRST)])
+def test_full_size_tp8_share(mode, order):
+    """BASELINE configuration 3: A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]; the side-kernel /
+    own-first combination is the launch configuration bench.py times."""
     w = wl.gemm_rs_inputs(8192, 8192, 3584, 8, 0, config_id=3)
-    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=2 if mode == "waves" else 1)
+    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=2, tile_order=order)
     rel, mx = check(w, ha, partial, push, out, f"cfg3 {mode}")
     print(f"cfg3 {mode}: tile {info['tile_m']}x{info['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")

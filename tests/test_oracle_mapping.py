@@ -127,3 +127,10 @@ def test_grouped_order_hand_example():
     assert mp.logical_order(5, 2, 5, 1, True, 2) == [2, 4, 3, 5, 6, 8, 7, 9, 0, 1]
     for gm in (1, 2, 3, 4, 8):
         assert sorted(mp.logical_order(7, 5, 1, 0, False, gm)) == list(range(35))
+
+
+def test_rs_own_first_order():
+    recs = mp.gemm_rs_schedule_records(1024, 512, 64, 4, 1, 256, 256, 128, 128, 8, True, False, 1, True)
+    assert [r[1] for r in recs] == [1, 1, 2, 2, 3, 3, 0, 0]            # own segment (rank 1), then the ring 2, 3, 0
+    order = mp.rs_consumer_order(1024, 512, 4, 1, 128, 128, True, True)
+    assert order[:4] == [8, 9, 10, 11] and order[-4:] == [4, 5, 6, 7] and sorted(order) == list(range(32))
