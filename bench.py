@@ -15,6 +15,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk x 2.4 GHz (dense bf16 MFMA)
+# HBM/fabric bytes per fused GEMM launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md (scaled by the plain-copy calibration): mean of AG+GEMM (832 + 187 MiB)
+# and GEMM+RS (672 + 194 MiB).  A measured constant, not recomputed by this script.
+HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (832 + 187 + 672 + 194) * 2 ** 20)
 
 
 def cpu_baseline(np, wl, ops):
@@ -47,6 +51,8 @@ def main():
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (5 times): the known-size kernel against which the FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the TP=8 layer; --gpus must be 1 "
@@ -61,6 +67,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.zeros_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
+        return
     mode = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM}[args.comm_mode]
 
     def up(bits):
@@ -171,7 +185,7 @@ def main():
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "ops": res,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": HBM_TRAFFIC_BYTES_PER_LAUNCH,
                      "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)"},
         "host_wall_ms_per_step": round(wall_step, 4),
     }
