@@ -150,6 +150,67 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
                unsigned epoch, void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
 
 /*
+ * MoE routing -> dynamic mapping tables (paper: "Tile-Centric Mapping", dynamic mapping: lookup tables f_S_low,
+ * f_S_high, f_R, f_C "filled at runtime by other dynamic logics (e.g., dynamic routing)").  Enqueued on `stream`.
+ *   gate_logits dev [T,E] fp32.  Per token the `topk` experts with the largest logits are taken (equal logits: the
+ *               lower expert index first; listed by descending logit); weight = softmax over all E experts,
+ *               divided by the sum over the selected ones if `renormalize`.
+ *   topk_ids    dev [T,topk] int (written)      topk_w dev [T,topk] fp32 (written)
+ *   Routed row (t,j) has id t*topk+j.  Rows are sorted by expert, ascending id inside an expert (stable):
+ *   expert_offsets dev [E+1] int (written), sorted_row dev [T*topk] int (written).
+ *   tile_tables dev [max_row_tiles, 8] int (written): expert e owns ceil(count[e]/tile_m) row tiles over its run of
+ *               sorted rows, the last one short; one record per tile, experts ascending:
+ *               f_S_low, f_S_high, expert, chan_mask_lo, chan_mask_hi, f_R_lo, f_R_hi, 0
+ *               chan_mask bit (rank*C + local channel) = AllGather channel holding a token of the tile;
+ *               f_R_lo..f_R_hi = span of source ranks.   n_tiles dev int[1] (written).
+ *   tile_m      row-tile height; use info[0] of tl_moe_query; max_row_tiles = info[2].
+ *   Requirements: E <= 64, topk <= 8, topk <= E, R | T, C | T/R, R*C <= 64.
+ */
+int tl_moe_route(tl_ctx* ctx, const float* gate_logits /*dev*/, int T, int E, int topk, int renormalize, int tile_m,
+                 int* topk_ids /*dev*/, float* topk_w /*dev*/, int* expert_offsets /*dev*/, int* sorted_row /*dev*/,
+                 int* tile_tables /*dev*/, int* n_tiles /*dev*/, void* stream);
+
+/* Geometry of a MoE half (op = TL_OP_MOE_AG_GATHER_GEMM or TL_OP_MOE_GEMM_SCATTER_RS), host call:
+ * info[0..7] = tile_m, tile_n, max_row_tiles, n_flags, workspace bytes, expected notifications per AllGather channel
+ *              (part 1), tokens per top-k reduce tile (part 2), column blocks. */
+int tl_moe_query(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk, int* info /*host, 8 ints*/);
+
+/*
+ * MoE part 1: AllGather + Gather + GroupGEMM (paper: "Kernel Design", AG + MoE; evaluation, MoE layer).
+ * Y1[s,:] = bf16( X[sorted_row[s]/topk, :] . W1[expert(s)] ) for every sorted row s; X = AllGather of the token shards.
+ * A grouped-GEMM tile waits (consumer_tile_wait through the table's channel mask) for exactly the AllGather channels
+ * that hold its tokens, and loads its A rows by index.
+ *   x_shards host array of R dev pointers, each [T/R,H] bf16;  x_gathered dev [T,H] bf16 (written)
+ *   w1 dev [E,H,I] bf16;  sorted_row / tile_tables / n_tiles: device outputs of tl_moe_route (same tile_m)
+ *   y1 dev [T*topk, I] bf16 in sorted row order (written)
+ *   flags dev unsigned[R*C], workspace as for tl_ag_gemm.  comm_mode: NONE, WAVES or SIDE_KERNEL.
+ *   Requirements: those of tl_moe_route, H % 64 == 0, I % 64 == 0.
+ */
+int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards /*host array of dev*/, void* x_gathered, const void* w1,
+                          const int* sorted_row, const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E,
+                          int topk, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/, size_t ws_bytes,
+                          void* compute_stream, void* comm_stream);
+
+/*
+ * MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter (paper: evaluation, MoE layer: "overlaps three kernels").
+ *   stage A  Z[s,:] = bf16( topk_w[row] * (X2[s,:] . W2[expert(s)]) ) stored at scatter_buf[row,:], row = sorted_row[s]
+ *   stage B  partial[t,:] = bf16( sum_j scatter_buf[t*topk+j,:] )            (fp32 sum)
+ *   stage C  ReduceScatter of partial over ranks as in tl_gemm_rs (own segment reduced into `out`, others pushed)
+ * Each stage notifies the next per tile: A -> B through per (token block, column block) row counters, B -> C per reduce tile.
+ *   x2 dev [T*topk, I] bf16 sorted row order; w2 dev [E,I,H] bf16; topk_w dev [T,topk] fp32
+ *   scatter_buf dev [T*topk,H] bf16 (written); partial dev [T,H] bf16 (written)
+ *   peer_recv / peer_push host arrays of R dev pointers, each [T/R,H] bf16; out dev [T/R,H] bf16 (written)
+ *   flags dev unsigned[info[3] of tl_moe_query]: row counters | reduce-tile ready | peer arrived | pushed
+ *   Requirements: those of tl_moe_route, H % tile_n == 0, tokens per reduce tile | T/R.  comm_mode: NONE (stage A only),
+ *   WAVES or SIDE_KERNEL.
+ */
+int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const int* sorted_row, const int* tile_tables,
+                           const int* n_tiles, const float* topk_w, void* scatter_buf, void* partial,
+                           const void* const* peer_recv /*host array of dev*/, void* const* peer_push /*host array of dev*/, void* out,
+                           int T, int H, int I, int E, int topk, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/,
+                           size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/*
  * Schedule dump for bit-exact checks (host call, no GPU work).  Writes int records in schedule order
  * (position p is taken by persistent workgroup p % G in its round p / G):
  *   TL_OP_AG_GEMM : 8 ints per consumer tile: tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0

@@ -49,6 +49,13 @@ _lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ct
 _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_rs.argtypes = [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 
+_ip, _fp = ctypes.c_void_p, ctypes.c_void_p
+_lib.tl_moe_query.argtypes = [_vp, _i, _i, _i, _i, _i, _i, ctypes.POINTER(_i)]
+_lib.tl_moe_route.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.tl_moe_ag_gather_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_moe_gemm_scatter_rs.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp,
+                                        _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+
 
 def _ptr(x):
     if x is None:
@@ -137,3 +144,29 @@ def tl_ag_gemm(ctx, a_shards, a_gathered, b, c, M, N, K, flags, epoch, workspace
 def tl_gemm_rs(ctx, a, b, partial, peer_recv, peer_push, out, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
     _check(_lib.tl_gemm_rs(ctx, _ptr(a), _ptr(b), _ptr(partial), _ptr_array(peer_recv), _ptr_array(peer_push), _ptr(out), M, N, K,
                            _ptr(flags), epoch, _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_moe_query(ctx, op, T, H, I, E, topk):
+    info = (_i * 8)()
+    _check(_lib.tl_moe_query(ctx, op, T, H, I, E, topk, info))
+    keys = ["tile_m", "tile_n", "max_row_tiles", "n_flags", "ws_bytes", "expected_per_channel", "tokens_per_reduce_tile", "col_blocks"]
+    return dict(zip(keys, list(info)))
+
+
+def tl_moe_route(ctx, gate_logits, T, E, topk, renormalize, tile_m, topk_ids, topk_w, expert_offsets, sorted_row, tile_tables, n_tiles, stream=None):
+    _check(_lib.tl_moe_route(ctx, _ptr(gate_logits), T, E, topk, int(renormalize), tile_m, _ptr(topk_ids), _ptr(topk_w), _ptr(expert_offsets),
+                             _ptr(sorted_row), _ptr(tile_tables), _ptr(n_tiles), _stream(stream)))
+
+
+def tl_moe_ag_gather_gemm(ctx, x_shards, x_gathered, w1, sorted_row, tile_tables, n_tiles, y1, T, H, I, E, topk, flags, epoch, workspace, ws_bytes,
+                          compute_stream=None, comm_stream=None):
+    _check(_lib.tl_moe_ag_gather_gemm(ctx, _ptr_array(x_shards), _ptr(x_gathered), _ptr(w1), _ptr(sorted_row), _ptr(tile_tables), _ptr(n_tiles),
+                                      _ptr(y1), T, H, I, E, topk, _ptr(flags), epoch, _ptr(workspace), ws_bytes, _stream(compute_stream),
+                                      _stream(comm_stream)))
+
+
+def tl_moe_gemm_scatter_rs(ctx, x2, w2, sorted_row, tile_tables, n_tiles, topk_w, scatter_buf, partial, peer_recv, peer_push, out, T, H, I, E, topk,
+                           flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_moe_gemm_scatter_rs(ctx, _ptr(x2), _ptr(w2), _ptr(sorted_row), _ptr(tile_tables), _ptr(n_tiles), _ptr(topk_w), _ptr(scatter_buf),
+                                       _ptr(partial), _ptr_array(peer_recv), _ptr_array(peer_push), _ptr(out), T, H, I, E, topk, _ptr(flags), epoch,
+                                       _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))

@@ -1,0 +1,119 @@
+// AllGather side shared by the operators that gather row shards (AG+GEMM, AG+gather+grouped GEMM):
+// producer-tile queue, producers, and the consumer wait that helps producing.  gfx950 only.
+#pragma once
+#include "tl_device.h"
+
+namespace tl {
+
+struct AgProducer {
+  const bf16_t* shards[kMaxWorld];  // shard q = rows [q*rows_per_rank, (q+1)*rows_per_rank), each [rows_per_rank, ld]
+  bf16_t* gathered;                 // [R*rows_per_rank, ld]
+  int ld;                           // row length in elements (K of AG+GEMM, H of the MoE token buffer)
+  int R, rank;
+  int Tm_p, Tn_p, n_ptm, n_ptn;     // producer tile and the number of tiles along rows / columns
+  int rows_per_rank, rows_per_channel;
+  int local_in_place;
+  unsigned wait_target;             // epoch * expected
+  unsigned* flags;                  // [R*C]
+  unsigned* ticket;                 // producer-tile queue head (grows by n_ptm*n_ptn per call)
+  unsigned ticket_end;              // epoch * number of producer tiles
+  WaitCtl ctl;
+};
+
+// ======================================================================================
+// AllGather producer (pull mode).  Producer tiles form a queue that is consumed through an atomic
+// ticket counter: ticket i is producer tile (tm, tn) in ring order over source ranks (rank+1,
+// rank+2, ..., the local shard last).  Whoever holds a ticket copies that tile of the gathered
+// matrix from its owner's shard and then notifies the tile's channel.  Dedicated producer
+// workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
+// too instead of idling, so a consumer can never wait for a producer that is not resident.
+// ======================================================================================
+// Called by every lane of one wave; the result is wave-uniform.
+__device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out) {
+  unsigned t = lane0_fetch_add(p.ticket, 1u);
+  if ((int)(t - p.ticket_end) >= 0) {  // queue of this call is empty: give the ticket back
+    lane0_add(p.ticket, 0xffffffffu);
+    return false;
+  }
+  *out = t - (p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn));
+  return true;
+}
+
+// All threads of the workgroup call this with the same ticket index; `wave` is the wave-uniform wave index.
+__device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid, int wave, int nthreads) {
+  const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
+  int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
+  int tm = tmi + (p.rank + 1) * ptm_per_rank;  // ring order over source ranks: rank+1, rank+2, ..., rank
+  if (tm >= p.n_ptm) tm -= p.n_ptm;
+  int row_lo = tm * p.Tm_p;
+  int src = tm / ptm_per_rank;                       // f_R
+  int channel = tm / (p.rows_per_channel / p.Tm_p);  // f_C
+  if (!(src == p.rank && p.local_in_place)) {
+    const bf16_t* s = p.shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.ld + (long)tn * p.Tn_p;
+    bf16_t* d = p.gathered + (long)row_lo * p.ld + (long)tn * p.Tn_p;
+    copy_tile(s, p.ld, d, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
+  }
+  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
+  if (wave == 0) wave_tile_notify(p.flags + channel);
+}
+
+// Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
+__device__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_ticket) {
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (;;) {
+    if (wave == 0) {
+      unsigned t;
+      int v = claim_ticket(p, &t) ? (int)t : -1;
+      *s_ticket = v;  // all lanes of wave 0 store the same value
+    }
+    __syncthreads();
+    int i = __builtin_amdgcn_readfirstlane(*s_ticket);
+    __syncthreads();
+    if (i < 0) break;
+    produce_tile(p, i, tid, wave, nthreads);
+  }
+}
+
+// consumer_tile_wait for the channels set in chan_mask (bit = global channel index) by a whole workgroup: while a channel is short of its target
+// the workgroup works off producer tickets; with the queue empty it sleeps and polls (bounded by ctl.timeout).
+__device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, unsigned long long chan_mask, int tid, int nthreads, int* s_ticket) {
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned long long t0 = 0;
+  if (wave == 0 && p.ctl.timeout) t0 = wall_clock64();
+  for (;;) {
+    if (wave == 0) {
+      int state = -2;  // -2: ready, -1: not ready and nothing to produce, >= 0: ticket to work off
+      int first_short = 0;
+      for (unsigned long long m = chan_mask; m; m &= m - 1) {
+        int ch = __builtin_ctzll(m);
+        unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if ((int)(f - p.wait_target) < 0 && state == -2) { state = -1; first_short = ch; }
+      }
+      if (state == -1) {
+        unsigned t;
+        if (claim_ticket(p, &t)) state = (int)t;
+        else if (p.ctl.timeout) {
+          int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          if (st != 0) state = -2;  // abandoned elsewhere
+          else if (wall_clock64() - t0 > p.ctl.timeout) {
+            int expected = 0;  // every lane tries, the first one wins, all carry the same value
+            __hip_atomic_compare_exchange_strong(p.ctl.status, &expected, 1 + first_short, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            state = -2;
+          }
+        }
+      }
+      *s_ticket = state;
+    }
+    __syncthreads();
+    int state = __builtin_amdgcn_readfirstlane(*s_ticket);
+    __syncthreads();
+    if (state == -2) break;
+    if (state >= 0) produce_tile(p, state, tid, wave, nthreads);
+    else __builtin_amdgcn_s_sleep(8);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  __syncthreads();
+}
+
+
+}  // namespace tl

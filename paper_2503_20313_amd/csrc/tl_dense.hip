@@ -1,7 +1,9 @@
 // AllGather+GEMM and GEMM+ReduceScatter: fused persistent kernels, their producers/consumers,
 // host-side validation, mapping tables and launches.  gfx950 only.
+#include "tl_ag_producer.h"
 #include "tl_gemm_tile.h"
 #include "tl_host.h"
+#include "tl_rs_consumer.h"
 
 namespace tl {
 
@@ -9,140 +11,24 @@ namespace tl {
 // Kernel parameters
 // ======================================================================================
 struct AgGemmParams {
-  const bf16_t* a_shards[kMaxWorld];
-  bf16_t* a_gathered;
+  AgProducer prod;      // gathered A: shards, buffer, producer tiles, channel flags, ticket queue
   const bf16_t* b;
   bf16_t* c;
   int M, N, K;
-  int R, rank, C;
   Sched sched;
   int n_comm;           // producer workgroups at the front of the grid (0: none in this launch)
   int do_compute;       // 0: producers only
-  int do_wait;          // consumers wait on channel flags
-  int Tm_p, Tn_p, n_ptm, n_ptn;
-  int rows_per_rank, rows_per_channel;
-  int local_in_place;
-  unsigned wait_target;  // epoch * expected
-  unsigned* flags;
-  unsigned* ticket;      // producer-tile queue head (grows by n_ptm*n_ptn per call)
-  unsigned ticket_end;   // epoch * number of producer tiles
-  WaitCtl ctl;
+  int do_wait;          // 0: no wait, 1: wait on channel flags and help the producers, 2: wait only
 };
 
 struct GemmRsParams {
+  RsSide rs;            // partial product, peers, output, reduce tiles and their counters
   const bf16_t* a;
   const bf16_t* b;
-  bf16_t* partial;
-  const bf16_t* peer_recv[kMaxWorld];
-  bf16_t* peer_push[kMaxWorld];
-  bf16_t* out;
-  int M, N, K;
-  int R, rank;
+  int K;
   Sched sched;
-  int n_comm, do_compute, do_notify, do_wait;
-  int tile_m, tile_n;        // GEMM tile
-  int Tm_r, Tn_r, ncm, ncn;  // reduce tiles
-  int seg_rows, tiles_per_seg;
-  int rs_first_block;        // rotation of reduce row-blocks
-  unsigned epoch;
-  unsigned* ready;           // [ncm*ncn]
-  unsigned* arrived;         // [R*tiles_per_seg]
-  unsigned* pushed;          // [R*tiles_per_seg]
-  WaitCtl ctl;
+  int n_comm, do_compute, do_notify;
 };
-
-// ======================================================================================
-// AllGather producer (pull mode).  Producer tiles form a queue that is consumed through an atomic
-// ticket counter: ticket i is producer tile (tm, tn) in ring order over source ranks (rank+1,
-// rank+2, ..., the local shard last).  Whoever holds a ticket copies that tile of the gathered
-// matrix from its owner's shard and then notifies the tile's channel.  Dedicated producer
-// workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
-// too instead of idling, so a consumer can never wait for a producer that is not resident.
-// ======================================================================================
-// Called by every lane of one wave; the result is wave-uniform.
-__device__ __forceinline__ bool claim_ticket(const AgGemmParams& p, unsigned* out) {
-  unsigned t = lane0_fetch_add(p.ticket, 1u);
-  if ((int)(t - p.ticket_end) >= 0) {  // queue of this call is empty: give the ticket back
-    lane0_add(p.ticket, 0xffffffffu);
-    return false;
-  }
-  *out = t - (p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn));
-  return true;
-}
-
-// All threads of the workgroup call this with the same ticket index; `wave` is the wave-uniform wave index.
-__device__ __forceinline__ void produce_tile(const AgGemmParams& p, int i, int tid, int wave, int nthreads) {
-  const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
-  int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
-  int tm = tmi + (p.rank + 1) * ptm_per_rank;  // ring order over source ranks: rank+1, rank+2, ..., rank
-  if (tm >= p.n_ptm) tm -= p.n_ptm;
-  int row_lo = tm * p.Tm_p;
-  int src = tm / ptm_per_rank;                       // f_R
-  int channel = tm / (p.rows_per_channel / p.Tm_p);  // f_C
-  if (!(src == p.rank && p.local_in_place)) {
-    const bf16_t* s = p.a_shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.K + (long)tn * p.Tn_p;
-    bf16_t* d = p.a_gathered + (long)row_lo * p.K + (long)tn * p.Tn_p;
-    copy_tile(s, p.K, d, p.K, p.Tm_p, p.Tn_p, tid, nthreads);
-  }
-  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
-  if (wave == 0) wave_tile_notify(p.flags + channel);
-}
-
-// Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
-__device__ void ag_producer(const AgGemmParams& p, int tid, int nthreads, int* s_ticket) {
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  for (;;) {
-    if (wave == 0) {
-      unsigned t;
-      int v = claim_ticket(p, &t) ? (int)t : -1;
-      *s_ticket = v;  // all lanes of wave 0 store the same value
-    }
-    __syncthreads();
-    int i = __builtin_amdgcn_readfirstlane(*s_ticket);
-    __syncthreads();
-    if (i < 0) break;
-    produce_tile(p, i, tid, wave, nthreads);
-  }
-}
-
-// consumer_tile_wait for channels clo..chi by a whole workgroup: while a channel is short of its target
-// the workgroup works off producer tickets; with the queue empty it sleeps and polls (bounded by ctl.timeout).
-__device__ __forceinline__ void consumer_wait_or_produce(const AgGemmParams& p, int clo, int chi, int tid, int nthreads, int* s_ticket) {
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  unsigned long long t0 = 0;
-  if (wave == 0 && p.ctl.timeout) t0 = wall_clock64();
-  for (;;) {
-    if (wave == 0) {
-      int state = -2;  // -2: ready, -1: not ready and nothing to produce, >= 0: ticket to work off
-      for (int ch = clo; ch <= chi; ch++) {
-        unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        if ((int)(f - p.wait_target) < 0) state = -1;
-      }
-      if (state == -1) {
-        unsigned t;
-        if (claim_ticket(p, &t)) state = (int)t;
-        else if (p.ctl.timeout) {
-          int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-          if (st != 0) state = -2;  // abandoned elsewhere
-          else if (wall_clock64() - t0 > p.ctl.timeout) {
-            int expected = 0;  // every lane tries, the first one wins, all carry the same value
-            __hip_atomic_compare_exchange_strong(p.ctl.status, &expected, 1 + clo, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            state = -2;
-          }
-        }
-      }
-      *s_ticket = state;
-    }
-    __syncthreads();
-    int state = __builtin_amdgcn_readfirstlane(*s_ticket);
-    __syncthreads();
-    if (state == -2) break;
-    if (state >= 0) produce_tile(p, state, tid, wave, nthreads);
-    else __builtin_amdgcn_s_sleep(8);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  __syncthreads();
-}
 
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmParams p) {
@@ -150,35 +36,36 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
   __shared__ int s_ticket;
   const int tid = threadIdx.x;
   if ((int)blockIdx.x < p.n_comm) {
-    ag_producer(p, tid, Cfg::NTHREADS, &s_ticket);
+    ag_producer(p.prod, tid, Cfg::NTHREADS, &s_ticket);
     return;
   }
   if (!p.do_compute) return;
   const int w = blockIdx.x - p.n_comm;
-  const int M_per_channel = p.rows_per_channel;
+  const int M_per_channel = p.prod.rows_per_channel;
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
     int tile = sched_tile(p.sched, pos);
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
     int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
     int rows = min(Cfg::BM, p.M - row_lo), cols = min(Cfg::BN, p.N - col_lo);
+    // consumer_tile_wait: every channel whose rows the tile touches
+    const int clo = row_lo / M_per_channel, chi = (row_lo + rows - 1) / M_per_channel;
     if (p.do_wait == 1) {
-      consumer_wait_or_produce(p, row_lo / M_per_channel, (row_lo + rows - 1) / M_per_channel, tid, Cfg::NTHREADS, &s_ticket);
+      unsigned long long mask = ((chi - clo + 1 >= 64) ? ~0ull : ((1ull << (chi - clo + 1)) - 1)) << clo;
+      consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
     } else if (p.do_wait == 2) {
-      // flags raised by somebody else (no ticket queue): plain consumer_tile_wait on every channel the tile touches
-      if (tid == 0) {
-        int clo = row_lo / M_per_channel, chi = (row_lo + rows - 1) / M_per_channel;
-        for (int ch = clo; ch <= chi; ch++) tile_wait(p.flags + ch, p.wait_target, p.ctl, ch);
-      }
+      // flags raised by somebody else (no ticket queue): plain wait
+      if (tid == 0)
+        for (int ch = clo; ch <= chi; ch++) tile_wait(p.prod.flags + ch, p.prod.wait_target, p.prod.ctl, ch);
       __syncthreads();
     }
-    gemm_tile<Cfg>(p.a_gathered + (long)row_lo * p.K, p.K, p.b + col_lo, p.N, p.c + (long)row_lo * p.N + col_lo, p.N, rows,
-                   cols, p.K, smem);
+    gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
+                   DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem);
   }
 }
 
 // Producer as a kernel of its own (small register/LDS footprint, so it can share compute units
 // with resident GEMM workgroups) for the side-stream binding.
-__global__ void __launch_bounds__(256) ag_producer_kernel(const AgGemmParams p) {
+__global__ void __launch_bounds__(256) ag_producer_kernel(const AgProducer p) {
   __shared__ int s_ticket;
   ag_producer(p, threadIdx.x, 256, &s_ticket);
 }
@@ -189,108 +76,50 @@ __global__ void notify_kernel(unsigned* flags, int count, unsigned inc) {
   if (i < count) tile_notify(flags + i, inc);
 }
 
-// ======================================================================================
-// ReduceScatter consumer: reduce tiles of the partial product.  Own segment: wait for every
-// peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
-// landing zone and notify it.
-// ======================================================================================
-__device__ __forceinline__ void acc_bf16x8(float (&s)[8], u32x4 v) {
-#pragma unroll
-  for (int e = 0; e < 4; e++) {
-    s[2 * e] += __uint_as_float(v[e] << 16);
-    s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
-  }
-}
-
-__device__ void rs_consumer(const GemmRsParams& p, int wg, int n_wg, int tid, int nthreads) {
-  const int n_rt = p.ncm * p.ncn;
-  const int cm_per_seg = p.seg_rows / p.Tm_r;
-  for (int i = wg; i < n_rt; i += n_wg) {
-    int cmi = i / p.ncn, cn = i - cmi * p.ncn;
-    int cm = cmi + p.rs_first_block;
-    if (cm >= p.ncm) cm -= p.ncm;
-    const int t = cm * p.ncn + cn;
-    const int row_lo = cm * p.Tm_r, col_lo = cn * p.Tn_r;
-    const int rows = min(p.Tm_r, p.M - row_lo), cols = min(p.Tn_r, p.N - col_lo);
-    const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
-    const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
-    const int seg_row = row_lo - dest * p.seg_rows;
-    if (tid == 0) {
-      if (p.do_wait) {
-        // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
-        unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
-        unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
-        tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);
-      }
-      if (dest == p.rank) {
-        // peer_tile_wait: every peer's contribution to this tile has landed
-        for (int q = 0; q < p.R; q++)
-          if (q != p.rank) tile_wait(p.arrived + q * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + q * p.tiles_per_seg + local);
-      }
-    }
-    __syncthreads();
-    const bf16_t* mine = p.partial + (long)row_lo * p.N + col_lo;
-    const int cpr = cols >> 3, total = rows * cpr;
-    if (dest == p.rank) {
-      bf16_t* o = p.out + (long)seg_row * p.N + col_lo;
-      for (int idx = tid; idx < total; idx += nthreads) {
-        int r = idx / cpr, c = idx - r * cpr;
-        long off = (long)r * p.N + c * 8;
-        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int q = 0; q < p.R; q++) {
-          const bf16_t* src = (q == p.rank) ? mine : p.peer_recv[q] + (long)seg_row * p.N + col_lo;
-          acc_bf16x8(s, *(const u32x4*)(src + off));
-        }
-        bf16x8 v;
-#pragma unroll
-        for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
-        *(bf16x8*)(o + off) = v;
-      }
-    } else {
-      // tile_push_data to the owner's landing zone, then peer_tile_notify
-      copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
-      __syncthreads();
-      if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);
-    }
-  }
-}
-
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x;
   if ((int)blockIdx.x < p.n_comm) {
-    rs_consumer(p, blockIdx.x, p.n_comm, tid, Cfg::NTHREADS);
+    rs_consumer(p.rs, blockIdx.x, p.n_comm, tid, Cfg::NTHREADS);
     return;
   }
   if (!p.do_compute) return;
   const int w = blockIdx.x - p.n_comm;
+  const RsSide& rs = p.rs;
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
     int tile = sched_tile(p.sched, pos);
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
     int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
-    int rows = min(Cfg::BM, p.M - row_lo), cols = min(Cfg::BN, p.N - col_lo);
-    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, p.b + col_lo, p.N, p.partial + (long)row_lo * p.N + col_lo, p.N, rows, cols,
-                   p.K, smem);
+    int rows = min(Cfg::BM, rs.M - row_lo), cols = min(Cfg::BN, rs.N - col_lo);
+    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N,
+                   DenseRows{rs.partial + (long)row_lo * rs.N + col_lo, rs.N}, rows, cols, p.K, smem);
     if (p.do_notify) {
       // producer_tile_notify: one release-add per reduce tile this GEMM tile overlaps
       __syncthreads();
-      int cm_lo = row_lo / p.Tm_r, cm_hi = (row_lo + rows - 1) / p.Tm_r;
-      int cn_lo = col_lo / p.Tn_r, cn_hi = (col_lo + cols - 1) / p.Tn_r;
+      int cm_lo = row_lo / rs.Tm_r, cm_hi = (row_lo + rows - 1) / rs.Tm_r;
+      int cn_lo = col_lo / rs.Tn_r, cn_hi = (col_lo + cols - 1) / rs.Tn_r;
       int ncols = cn_hi - cn_lo + 1, cnt = (cm_hi - cm_lo + 1) * ncols;
-      for (int i = tid; i < cnt; i += Cfg::NTHREADS) tile_notify(p.ready + (cm_lo + i / ncols) * p.ncn + cn_lo + i % ncols);
+      for (int i = tid; i < cnt; i += Cfg::NTHREADS) tile_notify(rs.ready + (cm_lo + i / ncols) * rs.ncn + cn_lo + i % ncols);
     }
   }
-}
-
-__global__ void __launch_bounds__(256) rs_consumer_kernel(const GemmRsParams p) {
-  rs_consumer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
 }
 
 // Simulated peers: peer q's push of every tile of this rank's segment "arrives".
 __global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R, int rank) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < R * tiles_per_seg && i / tiles_per_seg != rank) tile_notify(arrived + i);
+}
+
+int launch_peers_arrive(const RsSide& rs, hipStream_t s) {
+  int n = rs.R * rs.tiles_per_seg;
+  hipLaunchKernelGGL(peers_arrive_kernel, dim3((n + 255) / 256), dim3(256), 0, s, rs.arrived, rs.tiles_per_seg, rs.R, rs.rank);
+  TL_HIP(hipGetLastError());
+  return TL_OK;
+}
+
+__global__ void __launch_bounds__(256) rs_consumer_kernel(const RsSide p) {
+  rs_consumer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
 }
 
 // ======================================================================================
@@ -313,13 +142,6 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
-static const int kTileM[TILE_VARIANTS] = {256, 256, 128};
-static const int kTileN[TILE_VARIANTS] = {256, 224, 128};
-typedef TileCfg<256, 256, 2, 4, 32, 4> Cfg256x256;
-typedef TileCfg<256, 224, 8, 1, 32, 4> Cfg256x224;
-typedef TileCfg<128, 128, 2, 2, 32, 4> Cfg128x128;
-static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
-static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
 
 // Segment whose rows GEMM+ReduceScatter computes first: the next rank's in ring order (its own comes last,
 // as in a ring reduce-scatter), or its own (so that the reduction of the own segment, the heaviest piece of
@@ -433,21 +255,6 @@ static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
   return s;
 }
 
-static WaitCtl make_ctl(const tl_ctx* ctx, void* workspace) {
-  WaitCtl c;
-  c.status = (int*)workspace;
-  c.timeout = (unsigned long long)ctx->cfg.spin_timeout_us * 100ull;  // 100 MHz wall clock
-  return c;
-}
-
-template <class Cfg, class P>
-static int launch_fused(void (*kernel)(const P), const P& p, int grid, hipStream_t stream) {
-  TL_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES));
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, stream, p);
-  TL_HIP(hipGetLastError());
-  return TL_OK;
-}
-
 static int launch_ag_gemm(int variant, const AgGemmParams& p, int grid, hipStream_t s) {
   switch (variant) {
     case TILE_256x256: return launch_fused<Cfg256x256>(ag_gemm_kernel<Cfg256x256>, p, grid, s);
@@ -463,13 +270,6 @@ static int launch_gemm_rs(int variant, const GemmRsParams& p, int grid, hipStrea
     default: return launch_fused<Cfg128x128>(gemm_rs_kernel<Cfg128x128>, p, grid, s);
   }
 }
-
-static int check_ctx(const tl_ctx* ctx) {
-  if (!ctx) return fail(TL_ERR_INVALID_ARG, "context is null");
-  return TL_OK;
-}
-
-static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace tl
 
@@ -565,20 +365,12 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
 
   AgGemmParams p;
   memset(&p, 0, sizeof p);
-  for (int q = 0; q < R; q++) p.a_shards[q] = (const bf16_t*)a_shards[q];
-  p.a_gathered = (bf16_t*)a_gathered;
+  fill_ag_producer(ctx, &p.prod, a_shards, a_gathered, K, r.Tm_p, r.Tn_p, r.n_ptm, r.n_ptn, r.rows_per_rank, r.rows_per_channel,
+                   flags, epoch, workspace);
   p.b = (const bf16_t*)b;
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;
-  p.R = R; p.rank = cfg.rank; p.C = cfg.channels_per_rank;
   p.sched = make_sched(ctx, r);
-  p.Tm_p = r.Tm_p; p.Tn_p = r.Tn_p; p.n_ptm = r.n_ptm; p.n_ptn = r.n_ptn;
-  p.rows_per_rank = r.rows_per_rank; p.rows_per_channel = r.rows_per_channel;
-  p.local_in_place = (const bf16_t*)a_shards[cfg.rank] == (const bf16_t*)a_gathered + (size_t)cfg.rank * r.rows_per_rank * K;
-  p.flags = flags;
-  p.ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
-  p.ticket_end = epoch * (unsigned)(r.n_ptm * r.n_ptn);
-  p.ctl = make_ctl(ctx, workspace);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
   const bool alone = cfg.comm_alone != 0;  // communication side only (timing)
@@ -591,30 +383,30 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
       return launch_ag_gemm(r.variant, p, r.G, cs);
     case TL_COMM_WAVES:
       p.n_comm = r.n_comm; p.do_wait = 1;
-      p.wait_target = epoch * (unsigned)r.expected;
+      p.prod.wait_target = epoch * (unsigned)r.expected;
       return launch_ag_gemm(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
       p.n_comm = 0; p.do_wait = 2;
-      p.wait_target = epoch * (unsigned)r.expected;
+      p.prod.wait_target = epoch * (unsigned)r.expected;
       return launch_ag_gemm(r.variant, p, r.G, cs);
     case TL_COMM_SIDE_KERNEL: {
       // The producer is enqueued first: it waits for nothing, so even if both streams end up on one
       // hardware queue the worst case is that the two kernels run one after the other.
       p.n_comm = 0; p.do_wait = 1;
-      p.wait_target = epoch * (unsigned)r.expected;
-      hipLaunchKernelGGL(ag_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
+      p.prod.wait_target = epoch * (unsigned)r.expected;
+      hipLaunchKernelGGL(ag_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.prod);
       TL_HIP(hipGetLastError());
       return alone ? TL_OK : launch_ag_gemm(r.variant, p, r.G, cs);
     }
     case TL_COMM_STREAM: {
       // rank_copy_data + rank_notify per source rank, ring order, through the runtime's copy path
       p.n_comm = 0; p.do_wait = 2;
-      p.wait_target = epoch;
+      p.prod.wait_target = epoch;
       const size_t shard_bytes = (size_t)r.rows_per_rank * K * sizeof(bf16_t);
       for (int i = 0; i < R; i++) {
         int q = (cfg.rank + i) % R;  // local shard first (it is usually free), then rank+1, ...
         char* dst = (char*)a_gathered + (size_t)q * shard_bytes;
-        if (!(q == cfg.rank && p.local_in_place)) TL_HIP(hipMemcpyAsync(dst, a_shards[q], shard_bytes, hipMemcpyDeviceToDevice, ms));
+        if (!(q == cfg.rank && p.prod.local_in_place)) TL_HIP(hipMemcpyAsync(dst, a_shards[q], shard_bytes, hipMemcpyDeviceToDevice, ms));
         hipLaunchKernelGGL(notify_kernel, dim3(1), dim3(64), 0, ms, flags + q * cfg.channels_per_rank, cfg.channels_per_rank, 1u);
         TL_HIP(hipGetLastError());
       }
@@ -642,43 +434,23 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
 
   GemmRsParams p;
   memset(&p, 0, sizeof p);
-  p.a = (const bf16_t*)a; p.b = (const bf16_t*)b; p.partial = (bf16_t*)partial; p.out = (bf16_t*)out;
-  for (int q = 0; q < R; q++) {
-    p.peer_recv[q] = (const bf16_t*)peer_recv[q];
-    p.peer_push[q] = (bf16_t*)peer_push[q];
-  }
-  p.M = M; p.N = N; p.K = K; p.R = R; p.rank = cfg.rank;
+  p.a = (const bf16_t*)a; p.b = (const bf16_t*)b; p.K = K;
   p.sched = make_sched(ctx, r);
-  p.tile_m = r.tile_m; p.tile_n = r.tile_n;
-  p.Tm_r = r.Tm_p; p.Tn_r = r.Tn_p; p.ncm = r.n_ptm; p.ncn = r.n_ptn;
-  p.seg_rows = r.rows_per_rank;
-  p.tiles_per_seg = (r.rows_per_rank / r.Tm_p) * r.n_ptn;
-  p.rs_first_block = 0;
-  if (cfg.tile_order != TL_ORDER_NATURAL) p.rs_first_block = rs_first_rank(cfg) * (r.rows_per_rank / r.Tm_p);
-  p.epoch = epoch;
-  p.ready = flags;
-  p.arrived = flags + (size_t)p.ncm * p.ncn;
-  p.pushed = p.arrived + (size_t)R * p.tiles_per_seg;
-  p.ctl = make_ctl(ctx, workspace);
+  fill_rs_side(ctx, &p.rs, partial, peer_recv, peer_push, out, M, N, r.tile_m, r.tile_n, r.Tm_p, r.Tn_p, flags, epoch, workspace);
+  if (cfg.tile_order != TL_ORDER_NATURAL) p.rs.rs_first_block = rs_first_rank(cfg) * (r.rows_per_rank / r.Tm_p);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
-
-  auto peers_arrive = [&](hipStream_t s) -> int {
-    int n = R * p.tiles_per_seg;
-    hipLaunchKernelGGL(peers_arrive_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.arrived, p.tiles_per_seg, R, cfg.rank);
-    TL_HIP(hipGetLastError());
-    return TL_OK;
-  };
+  auto peers_arrive = [&](hipStream_t s) -> int { return launch_peers_arrive(p.rs, s); };
 
   const bool alone = cfg.comm_alone != 0;  // reduce/push side only, on a partial product that is already complete
   p.do_compute = alone ? 0 : 1;
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
       if (alone) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: comm_alone needs a comm_mode with a reduce side");
-      p.n_comm = 0; p.do_notify = 0; p.do_wait = 0;
+      p.n_comm = 0; p.do_notify = 0; p.rs.do_wait = 0;
       return launch_gemm_rs(r.variant, p, r.G, cs);
     case TL_COMM_WAVES:
       if (int e = peers_arrive(alone ? cs : ms)) return e;
-      p.n_comm = r.n_comm; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      p.n_comm = r.n_comm; p.do_notify = alone ? 0 : 1; p.rs.do_wait = alone ? 0 : 1;
       return launch_gemm_rs(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
       return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: TL_COMM_EXTERNAL is not defined for this operator");
@@ -686,11 +458,11 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
     case TL_COMM_SIDE_KERNEL: {
       // The GEMM kernel is enqueued before the reduce kernel that waits on it: should both streams share a
       // hardware queue, the reduce kernel then simply runs after the GEMM instead of blocking it.
-      p.n_comm = 0; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      p.n_comm = 0; p.do_notify = alone ? 0 : 1; p.rs.do_wait = alone ? 0 : 1;
       if (!alone)
         if (int e = launch_gemm_rs(r.variant, p, r.G, cs)) return e;
       if (int e = peers_arrive(ms)) return e;
-      hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p);
+      hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.rs);
       TL_HIP(hipGetLastError());
       return TL_OK;
     }

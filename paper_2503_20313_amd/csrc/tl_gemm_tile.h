@@ -70,13 +70,24 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Computes one output tile.  `a` points at the tile's first row (column 0), `b` at row 0 of B
-// at the tile's first column, `c` at the tile's first element.  rows/cols = valid extent of
-// the tile (ragged edges): loads are clamped to valid memory, stores are masked.
-// K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS reads complete.
-template <class Cfg>
-__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const bf16_t* __restrict__ b, long ldb,
-                                          bf16_t* __restrict__ c, long ldc, int rows, int cols, int K, char* smem) {
+// Where the rows of an output tile go: dense = row r of the tile at c + r*ldc, unscaled.
+struct DenseRows {
+  static constexpr bool SCALED = false;
+  bf16_t* c;
+  long ldc;
+  __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
+};
+
+// Computes one output tile.  `a` points at column 0 of the A rows: tile row r is A row r, or A row
+// a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index); `b` points at
+// row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
+// column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED).
+// rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
+// masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS reads complete.
+template <class Cfg, class Out>
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
+                                          const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
+                                          char* smem) {
   constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
@@ -92,6 +103,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     int row = slot / Cfg::A_CPR;
     int chunk = (slot % Cfg::A_CPR) ^ ((row / Cfg::A_RPB) % Cfg::A_CPR);  // logical 16-byte chunk stored at this slot
     int grow = row < rows ? row : rows - 1;
+    if (a_rows) grow = a_rows[grow] / a_div;
     a_src[i] = (const char*)(a + (long)grow * lda + chunk * 8);
   }
 #pragma unroll
@@ -252,7 +264,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   for (int mt = 0; mt < Cfg::MT; mt++) {
     int row = c_row + mt * 32;
     if (row < rows) {
-      bf16_t* crow = c + (long)row * ldc;
+      float scale = 1.f;
+      bf16_t* crow = out.row(row, scale);
 #pragma unroll
       for (int nt = 0; nt < Cfg::NT; nt++) {
 #pragma unroll
@@ -261,7 +274,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
           if (col < cols) {  // cols % 8 == 0 and col % 4 == 0: a 4-wide group is all in or all out
             bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; e++) o[e] = (bf16_t)acc[mt][nt][g * 4 + e];
+            for (int e = 0; e < 4; e++) o[e] = (bf16_t)(Out::SCALED ? acc[mt][nt][g * 4 + e] * scale : acc[mt][nt][g * 4 + e]);
             *(bf16x4*)(crow + col) = o;
           }
         }

@@ -6,7 +6,10 @@
 #include <string.h>
 
 #include "../../include/tilelink_mi355.h"
+#include "tl_ag_producer.h"
 #include "tl_device.h"
+#include "tl_gemm_tile.h"
+#include "tl_rs_consumer.h"
 
 struct tl_ctx {
   tl_config cfg;
@@ -45,5 +48,83 @@ struct Resolved {
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r);
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+static const int kTileM[TILE_VARIANTS] = {256, 256, 128};
+static const int kTileN[TILE_VARIANTS] = {256, 224, 128};
+typedef TileCfg<256, 256, 2, 4, 32, 4> Cfg256x256;
+typedef TileCfg<256, 224, 8, 1, 32, 4> Cfg256x224;
+typedef TileCfg<128, 128, 2, 2, 32, 4> Cfg128x128;
+static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
+static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
+
+inline WaitCtl make_ctl(const tl_ctx* ctx, void* workspace) {
+  WaitCtl c;
+  c.status = (int*)workspace;
+  c.timeout = (unsigned long long)ctx->cfg.spin_timeout_us * 100ull;  // 100 MHz wall clock
+  return c;
+}
+
+// Launches a kernel that uses Cfg::LDS_BYTES of dynamic LDS.
+template <class Cfg, class P>
+inline int launch_fused(void (*kernel)(const P), const P& p, int grid, hipStream_t stream) {
+  TL_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES));
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, stream, p);
+  TL_HIP(hipGetLastError());
+  return TL_OK;
+}
+
+// Fills the AllGather side of a call (wait_target is left to the caller: it depends on the binding).
+inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const* shards, void* gathered, int ld, int Tm_p, int Tn_p,
+                             int n_ptm, int n_ptn, int rows_per_rank, int rows_per_channel, unsigned* flags, unsigned epoch,
+                             void* workspace) {
+  const tl_config& cfg = ctx->cfg;
+  for (int q = 0; q < cfg.world_size; q++) p->shards[q] = (const bf16_t*)shards[q];
+  p->gathered = (bf16_t*)gathered;
+  p->ld = ld;
+  p->R = cfg.world_size;
+  p->rank = cfg.rank;
+  p->Tm_p = Tm_p; p->Tn_p = Tn_p; p->n_ptm = n_ptm; p->n_ptn = n_ptn;
+  p->rows_per_rank = rows_per_rank;
+  p->rows_per_channel = rows_per_channel;
+  p->local_in_place = (const bf16_t*)shards[cfg.rank] == (const bf16_t*)gathered + (size_t)cfg.rank * rows_per_rank * ld;
+  p->flags = flags;
+  p->ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
+  p->ticket_end = epoch * (unsigned)(n_ptm * n_ptn);
+  p->ctl = make_ctl(ctx, workspace);
+}
+
+// Fills the ReduceScatter side of a call.  Flags: ready[ncm*ncn] | arrived[R*tiles_per_seg] | pushed[R*tiles_per_seg].
+inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void* const* peer_recv, void* const* peer_push, void* out,
+                         int M, int N, int tile_m, int tile_n, int Tm_r, int Tn_r, unsigned* flags, unsigned epoch, void* workspace) {
+  const tl_config& cfg = ctx->cfg;
+  const int R = cfg.world_size;
+  p->partial = (bf16_t*)partial;
+  p->out = (bf16_t*)out;
+  for (int q = 0; q < R; q++) {
+    p->peer_recv[q] = (const bf16_t*)peer_recv[q];
+    p->peer_push[q] = (bf16_t*)peer_push[q];
+  }
+  p->M = M; p->N = N; p->R = R; p->rank = cfg.rank;
+  p->tile_m = tile_m; p->tile_n = tile_n;
+  p->Tm_r = Tm_r; p->Tn_r = Tn_r; p->ncm = M / Tm_r; p->ncn = N / Tn_r;
+  p->seg_rows = M / R;
+  p->tiles_per_seg = (p->seg_rows / Tm_r) * p->ncn;
+  p->rs_first_block = 0;
+  p->do_wait = 1;
+  p->epoch = epoch;
+  p->ready = flags;
+  p->arrived = flags + (size_t)p->ncm * p->ncn;
+  p->pushed = p->arrived + (size_t)R * p->tiles_per_seg;
+  p->ctl = make_ctl(ctx, workspace);
+}
+
+int launch_peers_arrive(const RsSide& rs, hipStream_t s);
+
+inline int check_ctx(const tl_ctx* ctx) {
+  if (!ctx) return fail(TL_ERR_INVALID_ARG, "context is null");
+  return TL_OK;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace tl

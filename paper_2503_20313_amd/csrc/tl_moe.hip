@@ -1,0 +1,550 @@
+// MoE halves of the tensor-parallel FFN: routing -> dynamic mapping tables, AllGather + gather +
+// grouped GEMM, grouped GEMM + scatter + top-k reduce + ReduceScatter.  gfx950 only.
+//
+// Dynamic mapping (paper, "Tile-Centric Mapping": lookup tables f_S_low, f_S_high, f_R, f_C filled at run
+// time by the routing): one table row of 8 ints per grouped-GEMM row tile,
+//   (f_S_low, f_S_high, expert, chan_mask_lo, chan_mask_hi, f_R_lo, f_R_hi, 0),
+// over the routed rows sorted by expert (stable: ascending row id = token*topk + slot inside an expert).
+#include "tl_ag_producer.h"
+#include "tl_gemm_tile.h"
+#include "tl_host.h"
+#include "tl_rs_consumer.h"
+
+namespace tl {
+
+constexpr int kMaxExperts = 64;
+constexpr int kMaxTopk = 8;
+constexpr int kRouteThreads = 1024;
+
+// ======================================================================================
+// Routing, step 1: per token, the k largest gate logits (ties -> lower expert index, listed by
+// descending logit) and their softmax weights (over all E experts, renormalised over the k
+// selected if asked).  One thread per token.
+// ======================================================================================
+__global__ void moe_topk_kernel(const float* __restrict__ logits, int T, int E, int topk, int renormalize, int* __restrict__ topk_ids,
+                                float* __restrict__ topk_w) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float* row = logits + (long)t * E;
+  float mx = row[0];
+  for (int e = 1; e < E; e++) mx = fmaxf(mx, row[e]);
+  float denom = 0.f;
+  for (int e = 0; e < E; e++) denom += expf(row[e] - mx);
+  unsigned long long taken = 0;
+  float w[kMaxTopk];
+  float wsum = 0.f;
+  for (int j = 0; j < topk; j++) {
+    int best = -1;
+    float bv = 0.f;
+    for (int e = 0; e < E; e++) {
+      if ((taken >> e) & 1) continue;
+      float v = row[e];
+      if (best < 0 || v > bv) { best = e; bv = v; }  // strict >: the lower index wins a tie
+    }
+    taken |= 1ull << best;
+    topk_ids[(long)t * topk + j] = best;
+    w[j] = expf(bv - mx) / denom;
+    wsum += w[j];
+  }
+  for (int j = 0; j < topk; j++) topk_w[(long)t * topk + j] = renormalize ? w[j] / wsum : w[j];
+}
+
+// ======================================================================================
+// Routing, step 2 (one workgroup): stable counting sort of the routed rows by expert, expert offsets,
+// and the tile tables.  Thread i owns a contiguous run of rows, so "rows of expert e owned by lower
+// threads" (an exclusive scan over threads) plus the rank inside the own run gives the stable position.
+// ======================================================================================
+__device__ __forceinline__ int block_exclusive_scan(int v, int tid, int* s_wave, int* total) {
+  // inclusive scan inside the wave
+  int lane = tid & 63, wave = tid >> 6;
+  int x = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
+  }
+  if (lane == 63) s_wave[wave] = x;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int i = 0; i < kRouteThreads / 64; i++) {
+    int c = s_wave[i];
+    if (i < wave) base += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + x - v;
+}
+
+__global__ void __launch_bounds__(kRouteThreads) moe_sort_kernel(const int* __restrict__ topk_ids, int n_rows, int E, int topk, int T, int R, int C,
+                                                                 int Tm, int* __restrict__ expert_offsets, int* __restrict__ sorted_row,
+                                                                 int* __restrict__ tile_tables, int* __restrict__ n_tiles) {
+  __shared__ int s_wave[kRouteThreads / 64];
+  __shared__ int s_off[kMaxExperts + 1], s_tbase[kMaxExperts + 1];
+  const int tid = threadIdx.x;
+  const int per = (n_rows + kRouteThreads - 1) / kRouteThreads;
+  const int lo = min(tid * per, n_rows), hi = min(lo + per, n_rows);
+  int offset = 0;
+  for (int e = 0; e < E; e++) {
+    int c = 0;
+    for (int r = lo; r < hi; r++) c += (topk_ids[r] == e);
+    int total;
+    int before = block_exclusive_scan(c, tid, s_wave, &total);
+    int pos = offset + before;
+    for (int r = lo; r < hi; r++)
+      if (topk_ids[r] == e) sorted_row[pos++] = r;
+    if (tid == 0) s_off[e] = offset;
+    offset += total;
+  }
+  if (tid == 0) {
+    s_off[E] = offset;
+    int tb = 0;
+    for (int e = 0; e < E; e++) {
+      s_tbase[e] = tb;
+      tb += (s_off[e + 1] - s_off[e] + Tm - 1) / Tm;
+    }
+    s_tbase[E] = tb;
+    *n_tiles = tb;
+  }
+  __threadfence();
+  __syncthreads();
+  for (int e = tid; e <= E; e += kRouteThreads) expert_offsets[e] = s_off[e];
+  const int nt = s_tbase[E];
+  const int tokens_per_rank = T / R, tokens_per_channel = tokens_per_rank / C;
+  for (int tau = tid; tau < nt; tau += kRouteThreads) {
+    int e = 0;
+    while (s_tbase[e + 1] <= tau) e++;
+    int f_lo = s_off[e] + (tau - s_tbase[e]) * Tm;
+    int f_hi = min(f_lo + Tm, s_off[e + 1]);
+    unsigned long long mask = 0;
+    int rmin = R, rmax = -1;
+    for (int s = f_lo; s < f_hi; s++) {
+      // written by other threads of this workgroup a moment ago: read past the vector cache
+      int token = __hip_atomic_load(sorted_row + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) / topk;
+      mask |= 1ull << (token / tokens_per_channel);
+      int q = token / tokens_per_rank;
+      rmin = min(rmin, q);
+      rmax = max(rmax, q);
+    }
+    int* rec = tile_tables + (long)tau * 8;
+    rec[0] = f_lo; rec[1] = f_hi; rec[2] = e;
+    rec[3] = (int)(unsigned)(mask & 0xffffffffull); rec[4] = (int)(unsigned)(mask >> 32);
+    rec[5] = rmin; rec[6] = rmax; rec[7] = 0;
+  }
+}
+
+// ======================================================================================
+// Part 1: AllGather + gather + grouped GEMM.  Output tile = (row tile tau of the sorted rows) x
+// (column block of I); its A rows are token rows picked through sorted_row, its B is the expert's W1.
+// ======================================================================================
+struct MoeP1Params {
+  AgProducer prod;          // token shards -> gathered tokens [T,H]
+  const bf16_t* w1;         // [E,H,I]
+  bf16_t* y1;               // [T*topk, I] in sorted row order
+  const int* sorted_row;
+  const int* tile_tables;
+  const int* n_row_tiles;   // device: number of row tiles (from the routing)
+  int H, I, topk;
+  int nbn, G, group_m, swizzle;
+  int n_comm, do_compute, do_wait;
+};
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const MoeP1Params p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int s_ticket;
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x < p.n_comm) {
+    ag_producer(p.prod, tid, Cfg::NTHREADS, &s_ticket);
+    return;
+  }
+  if (!p.do_compute) return;
+  const int w = blockIdx.x - p.n_comm;
+  Sched sc;
+  sc.nbm = *p.n_row_tiles;
+  sc.nbn = p.nbn;
+  sc.n_tiles = sc.nbm * sc.nbn;
+  sc.G = p.G;
+  sc.first_block = 0;
+  sc.swizzle = p.swizzle;
+  sc.group_m = p.group_m;
+  for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
+    int tile = sched_tile(sc, pos);
+    int bm = tile / sc.nbn, bn = tile - bm * sc.nbn;
+    const int* rec = p.tile_tables + (long)bm * 8;
+    const int f_lo = rec[0], f_hi = rec[1], e = rec[2];
+    const unsigned long long mask = (unsigned long long)(unsigned)rec[3] | ((unsigned long long)(unsigned)rec[4] << 32);
+    const int col_lo = bn * Cfg::BN;
+    const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.I - col_lo);
+    if (p.do_wait) consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
+    gemm_tile<Cfg>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                   DenseRows{p.y1 + (long)f_lo * p.I + col_lo, p.I}, rows, cols, p.H, smem);
+  }
+}
+
+// ======================================================================================
+// Part 2: grouped GEMM + scatter (+ gate weight) -> top-k reduce -> ReduceScatter.
+//   stage A (GEMM tiles): Z[s,:] = w[row(s)] * (X2[s,:] . W2[e]) stored at scatter[row(s),:], row(s) = sorted_row[s];
+//                         notifies counter (token block, column block) once per row it delivered there
+//   stage B (top-k reduce tiles): waits for Tt*topk rows, partial[t,:] = sum_j scatter[t*topk+j,:], notifies the RS tile
+//   stage C (RS tiles): the shared ReduceScatter consumer on `partial`
+// ======================================================================================
+struct ScatterRows {
+  static constexpr bool SCALED = true;
+  bf16_t* scatter;        // [T*topk, H] at the tile's first column
+  long ld;
+  const int* rows;        // sorted_row + f_lo
+  const float* w;         // routing weights, flat [T*topk]
+  __device__ __forceinline__ bf16_t* row(int r, float& scale) const {
+    int rid = rows[r];
+    scale = w[rid];
+    return scatter + (long)rid * ld;
+  }
+};
+
+struct MoeP2Params {
+  const bf16_t* x2;         // [T*topk, I] sorted row order
+  const bf16_t* w2;         // [E,I,H]
+  bf16_t* scatter;          // [T*topk, H]
+  const int* sorted_row;
+  const int* tile_tables;
+  const int* n_row_tiles;
+  const float* topk_w;
+  int T, H, I, topk;
+  int nbn, G, swizzle;
+  int Tt;                   // tokens per top-k reduce tile (= RS reduce tile rows)
+  unsigned epoch;
+  unsigned* rows_ready;     // [T/Tt * nbn] rows delivered per (token block, column block)
+  RsSide rs;                // on partial [T,H]; rs.ready is raised by stage B
+  int n_topk, n_rs;         // workgroups of stage B and C (in front of the grid when fused)
+  int do_compute, do_notify, do_wait;
+};
+
+__device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int nthreads) {
+  const int ntb = p.T / p.Tt;
+  const int n_tiles = ntb * p.nbn;
+  const int BN = p.rs.Tn_r;
+  for (int i = wg; i < n_tiles; i += n_wg) {
+    // column block slowest, like the GEMM stage that feeds it
+    int bn = i / ntb, tb = i - bn * ntb;
+    const int t_lo = tb * p.Tt, col_lo = bn * BN;
+    const int cols = min(BN, p.H - col_lo);
+    if (p.do_wait) {
+      if (tid == 0) tile_wait(p.rows_ready + tb * p.nbn + bn, p.epoch * (unsigned)(p.Tt * p.topk), p.rs.ctl, tb * p.nbn + bn);
+      __syncthreads();
+    }
+    const int cpr = cols >> 3, total = p.Tt * cpr;
+    for (int idx = tid; idx < total; idx += nthreads) {
+      int r = idx / cpr, c = idx - r * cpr;
+      const bf16_t* src = p.scatter + (long)(t_lo + r) * p.topk * p.H + col_lo + c * 8;
+      float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < p.topk; j++) acc_bf16x8(s, *(const u32x4*)(src + (long)j * p.H));
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
+      *(bf16x8*)(p.rs.partial + (long)(t_lo + r) * p.H + col_lo + c * 8) = v;
+    }
+    __syncthreads();
+    if (tid == 0) tile_notify(p.rs.ready + tb * p.rs.ncn + bn);
+  }
+}
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const MoeP2Params p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x < p.n_topk) {
+    topk_reduce(p, blockIdx.x, p.n_topk, tid, Cfg::NTHREADS);
+    return;
+  }
+  if ((int)blockIdx.x < p.n_topk + p.n_rs) {
+    rs_consumer(p.rs, blockIdx.x - p.n_topk, p.n_rs, tid, Cfg::NTHREADS);
+    return;
+  }
+  if (!p.do_compute) return;
+  const int w = blockIdx.x - p.n_topk - p.n_rs;
+  Sched sc;
+  sc.nbm = *p.n_row_tiles;
+  sc.nbn = p.nbn;
+  sc.n_tiles = sc.nbm * sc.nbn;
+  sc.G = p.G;
+  sc.first_block = 0;
+  sc.swizzle = p.swizzle;
+  sc.group_m = sc.nbm > 0 ? sc.nbm : 1;  // column block slowest: a column block of every token is complete early
+  for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
+    int tile = sched_tile(sc, pos);
+    int bm = tile / sc.nbn, bn = tile - bm * sc.nbn;
+    const int* rec = p.tile_tables + (long)bm * 8;
+    const int f_lo = rec[0], f_hi = rec[1], e = rec[2];
+    const int col_lo = bn * Cfg::BN;
+    const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.H - col_lo);
+    gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
+                   ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
+    if (p.do_notify) {
+      // producer_tile_notify with a count: the rows of this tile are token-ascending, so each token block
+      // receives one run of them; the first row of a run adds the run's length to the block's counter
+      __syncthreads();
+      for (int r = tid; r < rows; r += Cfg::NTHREADS) {
+        int tb = (p.sorted_row[f_lo + r] / p.topk) / p.Tt;
+        if (r == 0 || (p.sorted_row[f_lo + r - 1] / p.topk) / p.Tt != tb) {
+          int n = 1;
+          while (r + n < rows && (p.sorted_row[f_lo + r + n] / p.topk) / p.Tt == tb) n++;
+          tile_notify(p.rows_ready + tb * p.nbn + bn, (unsigned)n);
+        }
+      }
+    }
+  }
+}
+
+// stages B and C as a kernel of their own (side-kernel binding)
+__global__ void __launch_bounds__(256) moe_reduce_kernel(const MoeP2Params p) {
+  if ((int)blockIdx.x < p.n_topk) topk_reduce(p, blockIdx.x, p.n_topk, threadIdx.x, 256);
+  else rs_consumer(p.rs, blockIdx.x - p.n_topk, p.n_rs, threadIdx.x, 256);
+}
+
+__global__ void __launch_bounds__(256) moe_ag_producer_kernel(const AgProducer p) {
+  __shared__ int s_ticket;
+  ag_producer(p, threadIdx.x, 256, &s_ticket);
+}
+
+// ======================================================================================
+// Host side
+// ======================================================================================
+struct MoeResolved {
+  int variant, tile_m, tile_n, nbn, max_row_tiles;
+  int G, n_comm;
+  int Tm_p, Tn_p, n_ptm, n_ptn, rows_per_rank, rows_per_channel, expected;  // AllGather of the tokens (part 1)
+  int Tt;                                                                     // top-k reduce / RS tile rows (part 2)
+};
+
+static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk, MoeResolved* r) {
+  const tl_config& c = ctx->cfg;
+  const int R = c.world_size;
+  if (T <= 0 || H <= 0 || I <= 0 || E <= 0 || topk <= 0) return fail(TL_ERR_INVALID_ARG, "T, H, I, E, topk must be positive");
+  if (E > kMaxExperts) return fail(TL_ERR_UNSUPPORTED_SHAPE, "at most %d experts (got %d)", kMaxExperts, E);
+  if (topk > kMaxTopk || topk > E) return fail(TL_ERR_UNSUPPORTED_SHAPE, "topk=%d must be <= %d and <= E", topk, kMaxTopk);
+  if (T % R) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d must divide T=%d", R, T);
+  if ((T / R) % c.channels_per_rank) return fail(TL_ERR_UNSUPPORTED_SHAPE, "channels per rank %d must divide T/R=%d", c.channels_per_rank, T / R);
+  if (R * c.channels_per_rank > 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "at most 64 AllGather channels (R*C=%d)", R * c.channels_per_rank);
+  if (H % 64 || I % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "H=%d and I=%d must be multiples of 64", H, I);
+  memset(r, 0, sizeof *r);
+  const int N = (op == TL_OP_MOE_AG_GATHER_GEMM) ? I : H;
+  int v = -1;
+  if (c.tile_m || c.tile_n) {
+    for (int i = 0; i < TILE_VARIANTS; i++)
+      if (kTileM[i] == c.tile_m && kTileN[i] == c.tile_n) v = i;
+    if (v < 0) return fail(TL_ERR_UNSUPPORTED_SHAPE, "compute tile %dx%d is not one of 256x256, 256x224, 128x128", c.tile_m, c.tile_n);
+  } else if ((long)T * topk * N <= 1024L * 1024L) {
+    v = TILE_128x128;
+  } else {
+    // 256x256 unless the 224-wide tile divides N and fills the last round of workgroups better; the number of
+    // row tiles is data dependent: estimated as the routed rows over the tile height plus half a tile per expert
+    auto fill = [&](int tn) {
+      long tiles = ((long)T * topk / 256 + E / 2) * ceil_div(N, tn), G = ctx->num_cus;
+      return (double)tiles * tn / (double)((tiles + G - 1) / G * G);
+    };
+    v = (N % 224 == 0 && (N % 256 != 0 || fill(224) > fill(256) + 1e-9)) ? TILE_256x224 : TILE_256x256;
+  }
+  r->variant = v;
+  r->tile_m = kTileM[v];
+  r->tile_n = kTileN[v];
+  r->nbn = ceil_div(N, r->tile_n);
+  r->max_row_tiles = ceil_div(T * topk, r->tile_m) + E;
+  r->G = c.compute_workgroups > 0 ? c.compute_workgroups : ctx->num_cus;
+  r->n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : 128);
+  if (c.comm_mode == TL_COMM_NONE) r->n_comm = 0;
+  r->rows_per_rank = T / R;
+  r->rows_per_channel = r->rows_per_rank / c.channels_per_rank;
+  int Tm_p = c.comm_tile_m;
+  if (op == TL_OP_MOE_AG_GATHER_GEMM) {
+    if (Tm_p == 0) {
+      Tm_p = r->rows_per_channel;
+      while (Tm_p > 32 && Tm_p % 2 == 0) Tm_p /= 2;
+    }
+    if (Tm_p <= 0 || r->rows_per_channel % Tm_p) return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer row tile %d must divide T/(R*C)=%d", Tm_p, r->rows_per_channel);
+    int Tn_p = c.comm_tile_n ? c.comm_tile_n : H;
+    if (Tn_p <= 0 || H % Tn_p || Tn_p % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer column tile %d must divide H=%d and be a multiple of 8", Tn_p, H);
+    r->Tm_p = Tm_p; r->Tn_p = Tn_p; r->n_ptm = T / Tm_p; r->n_ptn = H / Tn_p;
+    r->expected = (r->rows_per_channel / Tm_p) * r->n_ptn;
+  } else {
+    int Tt = c.comm_tile_m ? c.comm_tile_m : (r->rows_per_rank >= 128 ? 128 : r->rows_per_rank);
+    if (Tt <= 0 || r->rows_per_rank % Tt) return fail(TL_ERR_UNSUPPORTED_SHAPE, "top-k reduce tile of %d tokens must divide T/R=%d", Tt, r->rows_per_rank);
+    if (H % r->tile_n) return fail(TL_ERR_UNSUPPORTED_SHAPE, "H=%d must be a multiple of the column tile %d", H, r->tile_n);
+    r->Tt = Tt;
+  }
+  return TL_OK;
+}
+
+template <class P>
+static int launch_moe(int variant, void (*k0)(const P), void (*k1)(const P), void (*k2)(const P), const P& p, int grid, hipStream_t s) {
+  switch (variant) {
+    case TILE_256x256: return launch_fused<Cfg256x256>(k0, p, grid, s);
+    case TILE_256x224: return launch_fused<Cfg256x224>(k1, p, grid, s);
+    default: return launch_fused<Cfg128x128>(k2, p, grid, s);
+  }
+}
+
+}  // namespace tl
+
+using namespace tl;
+
+extern "C" {
+
+int tl_moe_query(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk, int* info) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!info) return fail(TL_ERR_INVALID_ARG, "info must not be null");
+  if (op != TL_OP_MOE_AG_GATHER_GEMM && op != TL_OP_MOE_GEMM_SCATTER_RS) return fail(TL_ERR_INVALID_ARG, "tl_moe_query: operator %d is not a MoE half", op);
+  MoeResolved r;
+  if (int e = resolve_moe(ctx, op, T, H, I, E, topk, &r)) return e;
+  const int R = ctx->cfg.world_size;
+  int n_flags;
+  if (op == TL_OP_MOE_AG_GATHER_GEMM) n_flags = R * ctx->cfg.channels_per_rank;
+  else {
+    int ntb = T / r.Tt, tps = (T / R / r.Tt) * r.nbn;
+    n_flags = ntb * r.nbn /*rows_ready*/ + ntb * r.nbn /*rs ready*/ + 2 * R * tps;
+  }
+  int v[8] = {r.tile_m, r.tile_n, r.max_row_tiles, n_flags, 256, r.expected, r.Tt, r.nbn};
+  memcpy(info, v, sizeof v);
+  return TL_OK;
+}
+
+int tl_moe_route(tl_ctx* ctx, const float* gate_logits, int T, int E, int topk, int renormalize, int tile_m, int* topk_ids, float* topk_w,
+                 int* expert_offsets, int* sorted_row, int* tile_tables, int* n_tiles, void* stream) {
+  if (int e = check_ctx(ctx)) return e;
+  if (!gate_logits || !topk_ids || !topk_w || !expert_offsets || !sorted_row || !tile_tables || !n_tiles) return fail(TL_ERR_INVALID_ARG, "tl_moe_route: null pointer argument");
+  const tl_config& c = ctx->cfg;
+  if (T <= 0 || E <= 0 || topk <= 0 || tile_m <= 0) return fail(TL_ERR_INVALID_ARG, "tl_moe_route: T, E, topk, tile_m must be positive");
+  if (E > kMaxExperts || topk > kMaxTopk || topk > E) return fail(TL_ERR_UNSUPPORTED_SHAPE, "tl_moe_route: E <= %d, topk <= %d and topk <= E required", kMaxExperts, kMaxTopk);
+  if (T % c.world_size || (T / c.world_size) % c.channels_per_rank) return fail(TL_ERR_UNSUPPORTED_SHAPE, "tl_moe_route: R must divide T and C must divide T/R");
+  if (c.world_size * c.channels_per_rank > 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "tl_moe_route: at most 64 AllGather channels");
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(moe_topk_kernel, dim3((T + 255) / 256), dim3(256), 0, s, gate_logits, T, E, topk, renormalize, topk_ids, topk_w);
+  TL_HIP(hipGetLastError());
+  hipLaunchKernelGGL(moe_sort_kernel, dim3(1), dim3(kRouteThreads), 0, s, topk_ids, T * topk, E, topk, T, c.world_size, c.channels_per_rank,
+                     tile_m, expert_offsets, sorted_row, tile_tables, n_tiles);
+  TL_HIP(hipGetLastError());
+  return TL_OK;
+}
+
+int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1, const int* sorted_row,
+                          const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E, int topk, unsigned* flags,
+                          unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (int e = check_ctx(ctx)) return e;
+  const tl_config& cfg = ctx->cfg;
+  if (!x_shards || !x_gathered || !w1 || !sorted_row || !tile_tables || !n_tiles || !y1 || !flags || !workspace)
+    return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: null pointer argument");
+  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: epoch starts at 1");
+  MoeResolved r;
+  if (int e = resolve_moe(ctx, TL_OP_MOE_AG_GATHER_GEMM, T, H, I, E, topk, &r)) return e;
+  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_moe_ag_gather_gemm: workspace of %zu bytes, 256 needed", ws_bytes);
+  for (int q = 0; q < cfg.world_size; q++)
+    if (!x_shards[q] || !aligned16(x_shards[q])) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: x_shards[%d] is null or misaligned", q);
+  if (!aligned16(x_gathered) || !aligned16(w1) || !aligned16(y1)) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: device pointers must be 16-byte aligned");
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+    return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: comm_mode must be NONE, WAVES or SIDE_KERNEL");
+
+  MoeP1Params p;
+  memset(&p, 0, sizeof p);
+  fill_ag_producer(ctx, &p.prod, x_shards, x_gathered, H, r.Tm_p, r.Tn_p, r.n_ptm, r.n_ptn, r.rows_per_rank, r.rows_per_channel, flags,
+                   epoch, workspace);
+  p.prod.wait_target = epoch * (unsigned)r.expected;
+  p.w1 = (const bf16_t*)w1;
+  p.y1 = (bf16_t*)y1;
+  p.sorted_row = sorted_row;
+  p.tile_tables = tile_tables;
+  p.n_row_tiles = n_tiles;
+  p.H = H; p.I = I; p.topk = topk;
+  p.nbn = r.nbn; p.G = r.G; p.swizzle = cfg.xcd_swizzle;
+  p.group_m = cfg.group_m > 0 ? cfg.group_m : 4;
+  hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
+  const bool alone = cfg.comm_alone != 0;
+  p.do_compute = alone ? 0 : 1;
+  auto launch = [&](int grid) {
+    return launch_moe<MoeP1Params>(r.variant, moe_ag_gather_gemm_kernel<Cfg256x256>, moe_ag_gather_gemm_kernel<Cfg256x224>,
+                                   moe_ag_gather_gemm_kernel<Cfg128x128>, p, grid, cs);
+  };
+  switch (cfg.comm_mode) {
+    case TL_COMM_NONE:
+      if (alone) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: comm_alone needs a producer");
+      p.n_comm = 0; p.do_wait = 0;
+      return launch(r.G);
+    case TL_COMM_WAVES:
+      p.n_comm = r.n_comm; p.do_wait = 1;
+      return launch(alone ? r.n_comm : r.G + r.n_comm);
+    case TL_COMM_SIDE_KERNEL:
+      p.n_comm = 0; p.do_wait = 1;
+      hipLaunchKernelGGL(moe_ag_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.prod);
+      TL_HIP(hipGetLastError());
+      return alone ? TL_OK : launch(r.G);
+  }
+  return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: unknown comm_mode");
+}
+
+int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const int* sorted_row, const int* tile_tables, const int* n_tiles,
+                           const float* topk_w, void* scatter_buf, void* partial, const void* const* peer_recv, void* const* peer_push,
+                           void* out, int T, int H, int I, int E, int topk, unsigned* flags, unsigned epoch, void* workspace,
+                           size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (int e = check_ctx(ctx)) return e;
+  const tl_config& cfg = ctx->cfg;
+  if (!x2 || !w2 || !sorted_row || !tile_tables || !n_tiles || !topk_w || !scatter_buf || !partial || !peer_recv || !peer_push || !out || !flags || !workspace)
+    return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: null pointer argument");
+  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: epoch starts at 1");
+  MoeResolved r;
+  if (int e = resolve_moe(ctx, TL_OP_MOE_GEMM_SCATTER_RS, T, H, I, E, topk, &r)) return e;
+  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_moe_gemm_scatter_rs: workspace of %zu bytes, 256 needed", ws_bytes);
+  const int R = cfg.world_size;
+  if (!aligned16(x2) || !aligned16(w2) || !aligned16(scatter_buf) || !aligned16(partial) || !aligned16(out))
+    return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: device pointers must be 16-byte aligned");
+  for (int q = 0; q < R; q++)
+    if (q != cfg.rank && (!peer_recv[q] || !peer_push[q] || !aligned16(peer_recv[q]) || !aligned16(peer_push[q])))
+      return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: peer_recv[%d] or peer_push[%d] is null or misaligned", q, q);
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+    return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: comm_mode must be NONE, WAVES or SIDE_KERNEL");
+
+  MoeP2Params p;
+  memset(&p, 0, sizeof p);
+  p.x2 = (const bf16_t*)x2; p.w2 = (const bf16_t*)w2; p.scatter = (bf16_t*)scatter_buf;
+  p.sorted_row = sorted_row; p.tile_tables = tile_tables; p.n_row_tiles = n_tiles; p.topk_w = topk_w;
+  p.T = T; p.H = H; p.I = I; p.topk = topk;
+  p.nbn = r.nbn; p.G = r.G; p.swizzle = cfg.xcd_swizzle;
+  p.Tt = r.Tt;
+  p.epoch = epoch;
+  const int ntb = T / r.Tt;
+  p.rows_ready = flags;
+  // stage B raises one notification per reduce tile: for the RS consumer the "producer tile" is the reduce tile itself
+  fill_rs_side(ctx, &p.rs, partial, peer_recv, peer_push, out, T, H, r.Tt, r.tile_n, r.Tt, r.tile_n, flags + (size_t)ntb * r.nbn, epoch, workspace);
+  if (cfg.tile_order != TL_ORDER_NATURAL) {
+    int first = cfg.tile_order == TL_ORDER_OWN_FIRST ? cfg.rank : (cfg.rank + 1) % R;
+    p.rs.rs_first_block = first * (T / R / r.Tt);
+  }
+  hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
+  const bool alone = cfg.comm_alone != 0;
+  p.do_compute = alone ? 0 : 1;
+  auto launch = [&](int grid) {
+    return launch_moe<MoeP2Params>(r.variant, moe_gemm_scatter_kernel<Cfg256x256>, moe_gemm_scatter_kernel<Cfg256x224>,
+                                   moe_gemm_scatter_kernel<Cfg128x128>, p, grid, cs);
+  };
+  const int n_topk = (r.n_comm + 1) / 2, n_rs = r.n_comm - n_topk > 0 ? r.n_comm - n_topk : 1;
+  switch (cfg.comm_mode) {
+    case TL_COMM_NONE:
+      if (alone) return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: comm_alone needs a comm_mode with a reduce side");
+      p.n_topk = 0; p.n_rs = 0; p.do_notify = 0;
+      return launch(r.G);
+    case TL_COMM_WAVES:
+      if (int e = launch_peers_arrive(p.rs, alone ? cs : ms)) return e;
+      p.n_topk = n_topk; p.n_rs = n_rs; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      return launch(alone ? n_topk + n_rs : r.G + n_topk + n_rs);
+    case TL_COMM_SIDE_KERNEL:
+      p.n_topk = 0; p.n_rs = 0; p.do_notify = alone ? 0 : 1; p.do_wait = alone ? 0 : 1;
+      if (!alone)
+        if (int e = launch(r.G)) return e;
+      if (int e = launch_peers_arrive(p.rs, ms)) return e;
+      p.n_topk = n_topk; p.n_rs = n_rs;
+      hipLaunchKernelGGL(moe_reduce_kernel, dim3(n_topk + n_rs), dim3(256), 0, ms, p);
+      TL_HIP(hipGetLastError());
+      return TL_OK;
+  }
+  return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: unknown comm_mode");
+}
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+// ReduceScatter side shared by GEMM+RS and the MoE second half: reduce tiles of a partial result,
+// their ready / peer counters, and the consumer that reduces the own segment and pushes the others.
+#pragma once
+#include "tl_device.h"
+
+namespace tl {
+
+struct RsSide {
+  bf16_t* partial;                  // [M,N] local partial result (written by the producer stage)
+  const bf16_t* peer_recv[kMaxWorld];
+  bf16_t* peer_push[kMaxWorld];
+  bf16_t* out;                      // [M/R,N]
+  int M, N, R, rank;
+  int tile_m, tile_n;               // tile of the producer stage (decides how many notifications a reduce tile expects)
+  int Tm_r, Tn_r, ncm, ncn;         // reduce tiles
+  int seg_rows, tiles_per_seg;
+  int rs_first_block;               // rotation of reduce row-blocks
+  int do_wait;                      // wait for the producer stage's notifications
+  unsigned epoch;
+  unsigned* ready;                  // [ncm*ncn]
+  unsigned* arrived;                // [R*tiles_per_seg]
+  unsigned* pushed;                 // [R*tiles_per_seg]
+  WaitCtl ctl;
+};
+
+// ======================================================================================
+// ReduceScatter consumer: reduce tiles of the partial product.  Own segment: wait for every
+// peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
+// landing zone and notify it.
+// ======================================================================================
+__device__ __forceinline__ void acc_bf16x8(float (&s)[8], u32x4 v) {
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    s[2 * e] += __uint_as_float(v[e] << 16);
+    s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+  }
+}
+
+__device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthreads) {
+  const int n_rt = p.ncm * p.ncn;
+  const int cm_per_seg = p.seg_rows / p.Tm_r;
+  for (int i = wg; i < n_rt; i += n_wg) {
+    int cmi = i / p.ncn, cn = i - cmi * p.ncn;
+    int cm = cmi + p.rs_first_block;
+    if (cm >= p.ncm) cm -= p.ncm;
+    const int t = cm * p.ncn + cn;
+    const int row_lo = cm * p.Tm_r, col_lo = cn * p.Tn_r;
+    const int rows = min(p.Tm_r, p.M - row_lo), cols = min(p.Tn_r, p.N - col_lo);
+    const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
+    const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
+    const int seg_row = row_lo - dest * p.seg_rows;
+    if (tid == 0) {
+      if (p.do_wait) {
+        // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
+        unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
+        unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
+        tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);
+      }
+      if (dest == p.rank) {
+        // peer_tile_wait: every peer's contribution to this tile has landed
+        for (int q = 0; q < p.R; q++)
+          if (q != p.rank) tile_wait(p.arrived + q * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + q * p.tiles_per_seg + local);
+      }
+    }
+    __syncthreads();
+    const bf16_t* mine = p.partial + (long)row_lo * p.N + col_lo;
+    const int cpr = cols >> 3, total = rows * cpr;
+    if (dest == p.rank) {
+      bf16_t* o = p.out + (long)seg_row * p.N + col_lo;
+      for (int idx = tid; idx < total; idx += nthreads) {
+        int r = idx / cpr, c = idx - r * cpr;
+        long off = (long)r * p.N + c * 8;
+        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < p.R; q++) {
+          const bf16_t* src = (q == p.rank) ? mine : p.peer_recv[q] + (long)seg_row * p.N + col_lo;
+          acc_bf16x8(s, *(const u32x4*)(src + off));
+        }
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
+        *(bf16x8*)(o + off) = v;
+      }
+    } else {
+      // tile_push_data to the owner's landing zone, then peer_tile_notify
+      copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
+      __syncthreads();
+      if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);
+    }
+  }
+}
+
+
+// Simulated peers: peer q's push of every tile of this rank's segment "arrives".
+__global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R, int rank);
+
+}  // namespace tl

@@ -1,0 +1,182 @@
+"""GPU parity of the MoE entry points (routing tables, AG+gather+grouped GEMM, grouped GEMM+scatter+top-k reduce+RS)
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_20313_amd as tl
+import tl_workloads as wl
+from oracle import ops
+from oracle.bf16 import round_to_bf16, widen
+from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
+
+pytestmark = pytest.mark.gpu
+MODES = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL}
+
+
+def route_on_gpu(ctx, logits, T, E, k, tile_m, max_tiles, renorm=True):
+    d = dev()
+    lg = torch.from_numpy(logits).to(d)
+    ids = torch.full((T, k), -1, dtype=torch.int32, device=d)
+    w = torch.zeros((T, k), dtype=torch.float32, device=d)
+    off = torch.full((E + 1,), -1, dtype=torch.int32, device=d)
+    srow = torch.full((T * k,), -1, dtype=torch.int32, device=d)
+    tab = torch.full((max_tiles, 8), -7, dtype=torch.int32, device=d)
+    nt = torch.zeros(1, dtype=torch.int32, device=d)
+    tl.tl_moe_route(ctx, lg, T, E, k, renorm, tile_m, ids, w, off, srow, tab, nt)
+    torch.cuda.synchronize()
+    return ids, w, off, srow, tab, nt
+
+
+def check_routing(w_in, R, C, tile_m, got, renorm=True):
+    T, E, k = w_in["T"], w_in["E"], w_in["topk"]
+    ids, w, off, srow, tab, nt = got
+    ids_ref, w_ref = ops.moe_route(w_in["logits"], k, renorm)
+    _, off_ref, srow_ref = ops.moe_sort_rows(ids_ref, E)
+    tab_ref = ops.moe_tile_tables(off_ref, srow_ref, T, k, R, C, tile_m)
+    assert np.array_equal(ids.cpu().numpy(), ids_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=2e-6, atol=1e-7)
+    assert np.array_equal(off.cpu().numpy(), off_ref)
+    assert np.array_equal(srow.cpu().numpy(), srow_ref)
+    n = int(nt.item())
+    assert n == len(tab_ref)
+    assert np.array_equal(tab.cpu().numpy()[:n], tab_ref)
+    return ids_ref, w_ref, off_ref, srow_ref
+
+
+@pytest.mark.parametrize("T,E,k,R,C,tile_m,renorm", [(64, 4, 2, 2, 2, 16, True), (256, 8, 3, 4, 1, 128, False), (8192, 32, 2, 8, 4, 256, True), (1000, 5, 5, 5, 2, 128, True)])
+def test_route_tables_bit_exact(T, E, k, R, C, tile_m, renorm):
+    logits = wl.normal_f32((T, E), 1.0, 41, 0)
+    # plant ties: equal logits inside some rows must go to the lower expert index
+    logits[::7, 1] = logits[::7, 0]
+    if E > 3:
+        logits[::5, 3] = logits[::5, 2]
+    ctx = make_ctx(world_size=R, rank=0, channels_per_rank=C)
+    got = route_on_gpu(ctx, logits, T, E, k, tile_m, -(-T * k // tile_m) + E, renorm)
+    check_routing(dict(T=T, E=E, topk=k, logits=logits), R, C, tile_m, got, renorm)
+    tl.tl_ctx_destroy(ctx)
+
+
+def run_part1(w, rank, C, mode, epochs=1, **cfg):
+    T, H, I, E, k, R = w["T"], w["H"], w["I"], w["E"], w["topk"], w["world"]
+    ctx = make_ctx(world_size=R, rank=rank, channels_per_rank=C, comm_mode=mode, **cfg)
+    q = tl.tl_moe_query(ctx, tl.TL_OP_MOE_AG_GATHER_GEMM, T, H, I, E, k)
+    got = route_on_gpu(ctx, w["logits"], T, E, k, q["tile_m"], q["max_row_tiles"])
+    ids_ref, w_ref, off_ref, srow_ref = check_routing(w, R, C, q["tile_m"], got)
+    ids, tw, off, srow, tab, nt = got
+    shards = [up(s) for s in w["x_shards"]]
+    xg = poison((T, H))
+    w1 = up(w["w1"].reshape(E * H, I))
+    y1 = poison((T * k, I))
+    flags = torch.zeros(q["n_flags"], dtype=torch.int32, device=dev())
+    wsp = torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev())
+    comm = torch.cuda.Stream()
+    host_shards = [s.copy() for s in w["x_shards"]]
+    for epoch in range(1, epochs + 1):
+        if epoch > 1:
+            for r_ in range(R):
+                host_shards[r_] = wl.normal_bf16(host_shards[r_].shape, 1.0, 79, epoch, r_)
+                shards[r_].copy_(up(host_shards[r_]))
+            y1.copy_(poison((T * k, I)))
+        torch.cuda.synchronize()
+        tl.tl_moe_ag_gather_gemm(ctx, shards, xg, w1, srow, tab, nt, y1, T, H, I, E, k, flags, epoch, wsp, q["ws_bytes"], torch.cuda.current_stream(), comm)
+        torch.cuda.synchronize()
+        tl.tl_check_status(ctx, wsp)
+    x_ref, _, y_ref = ops.moe_ag_gather_gemm(host_shards, w["w1"], srow_ref, off_ref, k)
+    if mode != tl.TL_COMM_NONE:
+        assert np.array_equal(down(xg), x_ref)
+        assert flags.cpu().numpy().tolist() == [epochs * q["expected_per_channel"]] * (R * C)
+    tl.tl_ctx_destroy(ctx)
+    return assert_close_bf16(down(y1), y_ref, "MoE part 1"), q
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+def test_part1_small(mode):
+    w = wl.moe_inputs(256, 128, 192, 4, 2, 2, 0, config_id=42)
+    run_part1(w, 1, 2, MODES[mode], epochs=2, comm_workgroups=2)
+
+
+def test_part1_ragged_tiles_and_many_channels():
+    # 5 ranks, 5 experts, top-3, I = 320 (ragged for every tile width), explicit 128x128 tile -> short last tiles per expert
+    w = wl.moe_inputs(640, 192, 320, 5, 3, 5, 2, config_id=43)
+    run_part1(w, 2, 4, tl.TL_COMM_WAVES, epochs=2, comm_workgroups=3, tile_m=128, tile_n=128, comm_tile_m=8, comm_tile_n=64)
+    run_part1(w, 2, 4, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=3, tile_m=256, tile_n=224)
+
+
+def run_part2(w, mode, epochs=1, **cfg):
+    T, H, I, E, k, R, rank = w["T"], w["H"], w["I"], w["E"], w["topk"], w["world"], w["rank"]
+    ctx = make_ctx(world_size=R, rank=rank, comm_mode=mode, **cfg)
+    q = tl.tl_moe_query(ctx, tl.TL_OP_MOE_GEMM_SCATTER_RS, T, H, I, E, k)
+    got = route_on_gpu(ctx, w["logits"], T, E, k, q["tile_m"], q["max_row_tiles"])
+    ids_ref, w_ref, off_ref, srow_ref = check_routing(w, R, 1, q["tile_m"], got)
+    ids, tw, off, srow, tab, nt = got
+    seg = T // R
+    x2 = up(w["x2"])
+    w2 = up(w["w2"].reshape(E * I, H))
+    scatter = poison((T * k, H))
+    partial = poison((T, H))
+    recv = [0 if q_ == rank else up(w["peer_segments"][q_]) for q_ in range(R)]
+    push_t = [None if q_ == rank else poison((seg, H)) for q_ in range(R)]
+    out = poison((seg, H))
+    flags = torch.zeros(q["n_flags"], dtype=torch.int32, device=dev())
+    wsp = torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev())
+    comm = torch.cuda.Stream()
+    host_x2 = w["x2"]
+    for epoch in range(1, epochs + 1):
+        if epoch > 1:
+            host_x2 = wl.normal_bf16(host_x2.shape, 1.0, 80, epoch)
+            x2.copy_(up(host_x2))
+            out.copy_(poison((seg, H)))
+        torch.cuda.synchronize()
+        tl.tl_moe_gemm_scatter_rs(ctx, x2, w2, srow, tab, nt, tw, scatter, partial, recv, [0 if t is None else t for t in push_t], out,
+                                  T, H, I, E, k, flags, epoch, wsp, q["ws_bytes"], torch.cuda.current_stream(), comm)
+        torch.cuda.synchronize()
+        tl.tl_check_status(ctx, wsp)
+    tl.tl_ctx_destroy(ctx)
+    s_ref, p_ref, _, out_ref = ops.moe_gemm_scatter_rs(host_x2, w["w2"], srow_ref, off_ref, w_ref, w["peer_segments"], rank)
+    assert_close_bf16(down(scatter), s_ref, "MoE part 2 scatter")
+    if mode == tl.TL_COMM_NONE:
+        return q
+    assert_close_bf16(down(partial), p_ref, "MoE part 2 partial")
+    # the GPU's own top-k reduce and ReduceScatter, recomputed by the oracle from the GPU's intermediate tensors (tight)
+    sc = down(scatter)
+    p_exact = round_to_bf16(widen(sc).reshape(T, k, H).sum(axis=1))
+    pg = down(partial)
+    assert np.mean(pg != p_exact) < 0.02 and np.all(np.abs(widen(pg) - widen(p_exact)) <= np.abs(widen(p_exact)) * 2.0 ** -7 + 1e-30)
+    for q_ in range(R):
+        if q_ != rank:
+            assert np.array_equal(down(push_t[q_]), pg[q_ * seg:(q_ + 1) * seg]), f"push to peer {q_}"
+    red = round_to_bf16(ops.reduce_scatter_segment(pg[rank * seg:(rank + 1) * seg], w["peer_segments"], rank))
+    og = down(out)
+    assert np.mean(og != red) < 0.02 and np.all(np.abs(widen(og) - widen(red)) <= np.abs(widen(red)) * 2.0 ** -7 + 1e-30)
+    assert_close_bf16(og, out_ref, "MoE part 2 out")
+    # counters: every (token block, column block) received Tt*topk rows per call; every reduce tile one notification
+    ntb, nbn, Tt = T // q["tokens_per_reduce_tile"], q["col_blocks"], q["tokens_per_reduce_tile"]
+    f = flags.cpu().numpy()
+    assert f[:ntb * nbn].tolist() == [epochs * Tt * k] * (ntb * nbn)
+    assert f[ntb * nbn:2 * ntb * nbn].tolist() == [epochs] * (ntb * nbn)
+    return q
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("rank", [0, 1])
+def test_part2_small(mode, rank):
+    w = wl.moe_inputs(256, 256, 128, 4, 2, 2, rank, config_id=44)
+    run_part2(w, MODES[mode], epochs=2, comm_workgroups=4)
+
+
+def test_part2_gemm_stage_only_and_other_shapes():
+    w = wl.moe_inputs(640, 512, 192, 5, 3, 5, 3, config_id=45)
+    run_part2(w, tl.TL_COMM_NONE)
+    run_part2(w, tl.TL_COMM_WAVES, epochs=2, comm_workgroups=5, comm_tile_m=64, tile_m=256, tile_n=256)
+    run_part2(w, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=6, tile_m=128, tile_n=128, tile_order=tl.TL_ORDER_OWN_FIRST)
+
+
+@pytest.mark.parametrize("mode", ["side"])
+def test_full_size_tp8_share(mode):
+    """BASELINE configuration 4: 8192 tokens, hidden 4096, 32 experts top-2, per-rank expert FFN slice 4096 -> 1792."""
+    w = wl.moe_inputs(8192, 4096, 1792, 32, 2, 8, 0, config_id=4)
+    (rel, mx), q1 = run_part1(w, 0, 4, MODES[mode])
+    print(f"cfg4 part1 {mode}: tile {q1['tile_m']}x{q1['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")
+    q2 = run_part2(w, MODES[mode], tile_order=tl.TL_ORDER_OWN_FIRST)
+    print(f"cfg4 part2 {mode}: tile {q2['tile_m']}x{q2['tile_n']}")
