@@ -211,6 +211,33 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
                            size_t ws_bytes, void* compute_stream, void* comm_stream);
 
 /*
+ * Sequence-parallel attention: AllGather of K and V overlapped with flash attention of the local queries
+ * (paper: "Kernel Design", AG KV + self-attention; evaluation, sequence-parallel self-attention).
+ *   O[i,hd,:] = bf16( sum_j softmax_j( scale * Q[i,hd,:] . K[j,hd,:] ) V[j,hd,:] ),  fp32 scores, statistics and accumulation,
+ *   probabilities rounded to bf16 before they multiply V.  K = AllGather of the key shards along the sequence, V likewise.
+ *   Local query row i sits at sequence position rank*S/R + i; with causal != 0 it attends to positions <= its own, and only
+ *   the shards 0..rank are gathered and waited for (the remaining rows of k_gathered / v_gathered are not written).
+ * An attention workgroup owns (head, 256 local queries) and walks the keys in blocks of 64 from position 0; the first block
+ * of every AllGather channel is preceded by consumer_tile_wait on that channel's K flag and V flag.
+ *   q dev [S/R, heads, head_dim] bf16;  k_shards / v_shards host arrays of R dev pointers, each [S/R, heads, head_dim] bf16
+ *   k_gathered / v_gathered dev [S, heads, head_dim] bf16 (written);  o dev [S/R, heads, head_dim] bf16 (written)
+ *   flags dev unsigned[2*R*C]: K channels, then V channels; channel c covers positions [c*S/(R*C), (c+1)*S/(R*C)).
+ *   Zeroed once by the caller; after call number `epoch` (1, 2, ...) a gathered channel holds epoch * info[4] of tl_attn_query.
+ *   workspace dev, 256 bytes, zeroed once (word 0 status, words 1 and 2 the K and V producer queues).
+ *   Requirements: head_dim == 128, R | S, S/(R*C) % 64 == 0, R*C <= 64, 16-byte aligned pointers.
+ *   comm_mode: NONE (k_gathered / v_gathered are taken as complete), WAVES or SIDE_KERNEL.
+ * Returns TL_OK or a negative error; waits are bounded as in tl_ag_gemm (tl_check_status).
+ */
+int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards /*host array of dev*/,
+                       const void* const* v_shards /*host array of dev*/, void* k_gathered, void* v_gathered, void* o, int S,
+                       int heads, int head_dim, int causal, float scale, unsigned* flags /*dev*/, unsigned epoch,
+                       void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/* Geometry tl_sp_ag_attention resolves (host call).  info[0..7] = queries per workgroup, keys per block, n_flags, ws_bytes,
+ * expected_per_channel, shards gathered, attention workgroups, communication workgroups. */
+int tl_attn_query(const tl_ctx* ctx, int S, int heads, int head_dim, int causal, int* info /*host, 8 ints*/);
+
+/*
  * Schedule dump for bit-exact checks (host call, no GPU work).  Writes int records in schedule order
  * (position p is taken by persistent workgroup p % G in its round p / G):
  *   TL_OP_AG_GEMM : 8 ints per consumer tile: tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0

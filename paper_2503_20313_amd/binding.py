@@ -55,6 +55,11 @@ _lib.tl_moe_route.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, 
 _lib.tl_moe_ag_gather_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_moe_gemm_scatter_rs.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp,
                                         _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_sp_ag_attention.restype = _i
+_lib.tl_sp_ag_attention.argtypes = [_vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _vp, _u, _vp, _sz,
+                                    _vp, _vp]
+_lib.tl_attn_query.restype = _i
+_lib.tl_attn_query.argtypes = [_vp, _i, _i, _i, _i, ctypes.POINTER(_i)]
 
 
 def _ptr(x):
@@ -170,3 +175,17 @@ def tl_moe_gemm_scatter_rs(ctx, x2, w2, sorted_row, tile_tables, n_tiles, topk_w
     _check(_lib.tl_moe_gemm_scatter_rs(ctx, _ptr(x2), _ptr(w2), _ptr(sorted_row), _ptr(tile_tables), _ptr(n_tiles), _ptr(topk_w), _ptr(scatter_buf),
                                        _ptr(partial), _ptr_array(peer_recv), _ptr_array(peer_push), _ptr(out), T, H, I, E, topk, _ptr(flags), epoch,
                                        _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_attn_query(ctx, S, heads, head_dim, causal):
+    info = (_i * 8)()
+    _check(_lib.tl_attn_query(ctx, S, heads, head_dim, int(causal), info))
+    keys = ("block_q", "block_kv", "n_flags", "ws_bytes", "expected_per_channel", "shards_gathered", "attention_workgroups", "comm_workgroups")
+    return dict(zip(keys, list(info)))
+
+
+def tl_sp_ag_attention(ctx, q, k_shards, v_shards, k_gathered, v_gathered, o, S, heads, head_dim, causal, scale, flags, epoch, workspace, ws_bytes,
+                       compute_stream=None, comm_stream=None):
+    _check(_lib.tl_sp_ag_attention(ctx, _ptr(q), _ptr_array(k_shards), _ptr_array(v_shards), _ptr(k_gathered), _ptr(v_gathered), _ptr(o), S, heads,
+                                   head_dim, int(causal), float(scale), _ptr(flags), epoch, _ptr(workspace), ws_bytes, _stream(compute_stream),
+                                   _stream(comm_stream)))

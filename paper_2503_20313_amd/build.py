@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libtilelink_mi355.so")
-SOURCES = ["tl_dense.hip", "tl_moe.hip"]
+SOURCES = ["tl_dense.hip", "tl_moe.hip", "tl_attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          # packed fp32 VALU forms are kept out of all device code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -10,7 +10,9 @@ struct AgProducer {
   bf16_t* gathered;                 // [R*rows_per_rank, ld]
   int ld;                           // row length in elements (K of AG+GEMM, H of the MoE token buffer)
   int R, rank;
-  int Tm_p, Tn_p, n_ptm, n_ptn;     // producer tile and the number of tiles along rows / columns
+  int first_src;                    // source rank whose tiles head the queue; the queue then follows the ring
+  int n_ptm_all;                    // row tiles of the whole gathered matrix (ring wrap-around)
+  int Tm_p, Tn_p, n_ptm, n_ptn;     // producer tile and the number of tiles in the queue along rows / columns
   int rows_per_rank, rows_per_channel;
   int local_in_place;
   unsigned wait_target;             // epoch * expected
@@ -22,8 +24,8 @@ struct AgProducer {
 
 // ======================================================================================
 // AllGather producer (pull mode).  Producer tiles form a queue that is consumed through an atomic
-// ticket counter: ticket i is producer tile (tm, tn) in ring order over source ranks (rank+1,
-// rank+2, ..., the local shard last).  Whoever holds a ticket copies that tile of the gathered
+// ticket counter: ticket i is producer tile (tm, tn) in ring order over source ranks (by default
+// rank+1, rank+2, ..., the local shard last).  Whoever holds a ticket copies that tile of the gathered
 // matrix from its owner's shard and then notifies the tile's channel.  Dedicated producer
 // workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
 // too instead of idling, so a consumer can never wait for a producer that is not resident.
@@ -43,8 +45,8 @@ __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out)
 __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid, int wave, int nthreads) {
   const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
   int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
-  int tm = tmi + (p.rank + 1) * ptm_per_rank;  // ring order over source ranks: rank+1, rank+2, ..., rank
-  if (tm >= p.n_ptm) tm -= p.n_ptm;
+  int tm = tmi + p.first_src * ptm_per_rank;  // ring order over source ranks: first_src, first_src+1, ...
+  if (tm >= p.n_ptm_all) tm -= p.n_ptm_all;
   int row_lo = tm * p.Tm_p;
   int src = tm / ptm_per_rank;                       // f_R
   int channel = tm / (p.rows_per_channel / p.Tm_p);  // f_C

@@ -84,6 +84,8 @@ inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const
   p->R = cfg.world_size;
   p->rank = cfg.rank;
   p->Tm_p = Tm_p; p->Tn_p = Tn_p; p->n_ptm = n_ptm; p->n_ptn = n_ptn;
+  p->first_src = (cfg.rank + 1) % cfg.world_size;
+  p->n_ptm_all = n_ptm;
   p->rows_per_rank = rows_per_rank;
   p->rows_per_channel = rows_per_channel;
   p->local_in_place = (const bf16_t*)shards[cfg.rank] == (const bf16_t*)gathered + (size_t)cfg.rank * rows_per_rank * ld;
