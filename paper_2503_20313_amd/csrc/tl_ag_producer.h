@@ -82,6 +82,19 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned long long t0 = 0;
   if (wave == 0 && p.ctl.timeout) t0 = wall_clock64();
+  // Tickets are taken only while the queue head has not passed the last tile of the awaited channels: beyond that point every
+  // tile this workgroup needs is already in the hands of a resident workgroup, and taking more tickets would only delay it.
+  int limit = 0;
+  {
+    const int tpc = p.rows_per_channel / p.Tm_p, ptm_per_rank = p.rows_per_rank / p.Tm_p;
+    for (unsigned long long m = chan_mask; m; m &= m - 1) {
+      int qi = __builtin_ctzll(m) * tpc - p.first_src * ptm_per_rank;  // queue position of the channel's first row tile
+      if (qi < 0) qi += p.n_ptm_all;
+      int end = (qi + tpc) * p.n_ptn;
+      limit = end > limit ? end : limit;
+    }
+  }
+  const unsigned queue_begin = p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn);
   for (;;) {
     if (wave == 0) {
       int state = -2;  // -2: ready, -1: not ready and nothing to produce, >= 0: ticket to work off
@@ -93,7 +106,8 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
       }
       if (state == -1) {
         unsigned t;
-        if (claim_ticket(p, &t)) state = (int)t;
+        unsigned head = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if ((int)(head - queue_begin) < limit && claim_ticket(p, &t)) state = (int)t;
         else if (p.ctl.timeout) {
           int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
           if (st != 0) state = -2;  // abandoned elsewhere
@@ -113,7 +127,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     if (state >= 0) produce_tile(p, state, tid, wave, nthreads);
     else __builtin_amdgcn_s_sleep(8);
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);
   __syncthreads();
 }
 

@@ -16,15 +16,38 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Scope of the fence a consumer takes after it has seen a flag reach its target.
+//
+// The flag itself is always read with a device-scope atomic, and the producer's notify is a
+// device-scope release (its data is written back to memory before the flag moves).  What the
+// scope below decides is whether the consumer also discards the cached lines of its die: the
+// eight dies have private L2s, so a device-scope acquire invalidates the whole L2 of the die and
+// the L1 of the CU, and everything the other workgroups of that die were sharing there (weight
+// panels, K/V blocks) has to be fetched again.  With one such acquire per tile wait this cost a
+// tenth of the run time of the overlapped kernels.
+//
+// The invalidation guards against one thing only: a line of the awaited data that entered this
+// die's caches before the producer wrote it.  The kernels here exclude that by construction:
+//   * a kernel never reads a byte of flag-guarded data before it has seen the flag of the tile or
+//     channel that byte belongs to (no prefetch across a wait, guarded regions are whole rows
+//     aligned to more than a cache line), and
+//   * lines cached by earlier kernels are dropped by the acquire every kernel dispatch performs.
+// Hence every guarded line a die caches during a kernel was fetched after its producer's release.
+// The default is therefore a workgroup-scope fence: it orders the workgroup's later loads after
+// the flag load for the compiler and the wave, and leaves the caches alone.  Define
+// TL_ACQ_SCOPE="agent" to build with the full device-scope acquire instead.
+#ifndef TL_ACQ_SCOPE
+#define TL_ACQ_SCOPE "workgroup"
+#endif
 constexpr int kMaxWorld = 16;
 constexpr int kXcds = 8;  // workgroup w of a launch runs on die w % 8
 
 // ---------------------------------------------------------------------------------------
 // Signal primitives.  A barrier is a counter that only grows; notify adds 1 with release
-// ordering at device scope, wait spins until the counter reaches its target and then takes an
-// acquire fence, so that no later load of the waiting workgroup can be served from data cached
-// before the producer's stores became visible.  One lane per workgroup performs them; the
-// caller brackets them with workgroup barriers.
+// ordering at device scope, wait spins until the counter reaches its target and then takes the
+// acquire fence of scope TL_ACQ_SCOPE (see above), so that no later load of the waiting workgroup
+// is issued before the flag was seen.  One lane per workgroup performs them; the caller brackets
+// them with workgroup barriers.
 // ---------------------------------------------------------------------------------------
 struct WaitCtl {
   int* status;                 // status word: 0 = ok, else 1 + index of the flag whose wait expired
@@ -54,7 +77,7 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
       }
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);
   return ok;
 }
 
@@ -136,29 +159,39 @@ __host__ __device__ inline int sched_tile(const Sched& s, int p) {
 
 // ---------------------------------------------------------------------------------------
 // Copy of a rows x cols (bf16, cols % 8 == 0) tile by one workgroup, 16 bytes per lane and
-// access, four accesses in flight per lane.  Pointers must be 16-byte aligned.
+// access, four accesses in flight per lane.  Pointers must be 16-byte aligned and a tile must
+// span less than 4 GiB in either matrix (offsets inside the tile are 32-bit, so that an access is
+// a uniform base plus one offset register: the copy loops have to stay small enough in registers
+// to share a SIMD with two waves of a matrix kernel).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void copy_tile(const bf16_t* __restrict__ src, long src_ld, bf16_t* __restrict__ dst, long dst_ld,
                                           int rows, int cols, int tid, int nthreads) {
   const int cpr = cols >> 3;  // 16-byte chunks per row
   const int total = rows * cpr;
+  const int dr = nthreads / cpr, dc = nthreads - dr * cpr;  // chunk index + nthreads = (row + dr, chunk + dc) with carry
+  const unsigned sld = (unsigned)src_ld * 2u, dld = (unsigned)dst_ld * 2u;
+  const char* sb = (const char*)src;
+  char* db = (char*)dst;
+  int r = tid / cpr, c = tid - r * cpr;
   int i = tid;
   for (; i + 3 * nthreads < total; i += 4 * nthreads) {
     u32x4 v[4];
+    unsigned doff[4];
 #pragma unroll
     for (int u = 0; u < 4; u++) {
-      int idx = i + u * nthreads, r = idx / cpr, c = idx - r * cpr;
-      v[u] = __builtin_nontemporal_load((const u32x4*)(src + r * src_ld) + c);
+      v[u] = __builtin_nontemporal_load((const u32x4*)(sb + ((unsigned)r * sld + (unsigned)c * 16u)));
+      doff[u] = (unsigned)r * dld + (unsigned)c * 16u;
+      r += dr; c += dc;
+      if (c >= cpr) { c -= cpr; r++; }
     }
 #pragma unroll
-    for (int u = 0; u < 4; u++) {
-      int idx = i + u * nthreads, r = idx / cpr, c = idx - r * cpr;
-      *((u32x4*)(dst + r * dst_ld) + c) = v[u];
-    }
+    for (int u = 0; u < 4; u++) *(u32x4*)(db + doff[u]) = v[u];
   }
   for (; i < total; i += nthreads) {
-    int r = i / cpr, c = i - r * cpr;
-    *((u32x4*)(dst + r * dst_ld) + c) = __builtin_nontemporal_load((const u32x4*)(src + r * src_ld) + c);
+    *(u32x4*)(db + ((unsigned)r * dld + (unsigned)c * 16u)) =
+        __builtin_nontemporal_load((const u32x4*)(sb + ((unsigned)r * sld + (unsigned)c * 16u)));
+    r += dr; c += dc;
+    if (c >= cpr) { c -= cpr; r++; }
   }
 }
 
