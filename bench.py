@@ -42,6 +42,112 @@ def cpu_baseline(np, wl, ops):
                       f"float64 numpy, {dt:.1f} s (+{t0 - t_gen:.1f} s input generation)"}
 
 
+def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup):
+    """Secondary measurements, outside the timed step: the two MoE halves (configuration 4) and sequence-parallel
+    attention (configuration 5, causal, the last rank = the one with the most keys), each fused, compute alone
+    (communication off, gathered inputs complete) and communication alone."""
+    res = {}
+    R = 8
+
+    def triple(make, call, flop, extra=None):
+        t = {}
+        for name, m, alone in (("compute_alone_ms", tl.TL_COMM_NONE, 0), ("comm_alone_ms", mode, 1), ("fused_ms", mode, 0)):
+            st = make(m, alone)
+            st["epoch"] = 0
+
+            def fn(st=st):
+                st["epoch"] += 1
+                ms.wait_stream(cs)
+                call(st)
+            t[name], _ = timed(fn, steps, warmup)
+            tl.tl_check_status(st["ctx"], st["wsp"])
+            tl.tl_ctx_destroy(st["ctx"])
+        r = {k: round(v, 4) for k, v in t.items()}
+        r["tflops"] = round(flop / t["fused_ms"] / 1e9, 1)
+        r["compute_alone_tflops"] = round(flop / t["compute_alone_ms"] / 1e9, 1)
+        r["frac_of_peak"] = round(flop / t["fused_ms"] / 1e9 / PEAK_BF16_TFLOPS, 4)
+        r["overlap_efficiency"] = round(max(t["compute_alone_ms"], t["comm_alone_ms"]) / t["fused_ms"], 4)
+        if extra:
+            r.update(extra)
+        return r
+
+    # ---------------- MoE (configuration 4), rank 0
+    c = wl.CONFIGS[4]
+    T, H, I, E, k = c["T"], c["H"], c["I"], c["E"], c["topk"]
+    w = wl.moe_inputs(T, H, I, E, k, R, 0, config_id=4)
+    x_shards = [up(x) for x in w["x_shards"]]
+    x_full = torch.cat(x_shards).clone()
+    w1, w2, x2 = up(w["w1"].reshape(E * H, I)), up(w["w2"].reshape(E * I, H)), up(w["x2"])
+    logits = torch.from_numpy(w["logits"]).to(dev)
+    y1 = torch.zeros((T * k, I), dtype=torch.int16, device=dev)
+    scatter = torch.zeros((T * k, H), dtype=torch.int16, device=dev)
+    partial = torch.zeros((T, H), dtype=torch.int16, device=dev)
+    recv = [0] + [up(w["peer_segments"][q]) for q in range(1, R)]
+    push = [0] + [torch.zeros((T // R, H), dtype=torch.int16, device=dev) for _ in range(1, R)]
+    out = torch.zeros((T // R, H), dtype=torch.int16, device=dev)
+
+    def moe_state(op, m, alone, C):
+        ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                               spin_timeout_us=10_000_000, comm_alone=alone)
+        q = tl.tl_moe_query(ctx, op, T, H, I, E, k)
+        st = dict(ctx=ctx, q=q,
+                  ids=torch.zeros((T, k), dtype=torch.int32, device=dev), tw=torch.zeros((T, k), dtype=torch.float32, device=dev),
+                  off=torch.zeros(E + 1, dtype=torch.int32, device=dev), srow=torch.zeros(T * k, dtype=torch.int32, device=dev),
+                  tab=torch.zeros((q["max_row_tiles"], 8), dtype=torch.int32, device=dev), nt=torch.zeros(1, dtype=torch.int32, device=dev),
+                  flags=torch.zeros(q["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+        with torch.cuda.stream(cs):
+            tl.tl_moe_route(ctx, logits, T, E, k, True, q["tile_m"], st["ids"], st["tw"], st["off"], st["srow"], st["tab"], st["nt"])
+        torch.cuda.synchronize()
+        return st
+
+    def p1_make(m, alone):
+        st = moe_state(tl.TL_OP_MOE_AG_GATHER_GEMM, m, alone, 4)
+        st["xg"] = x_full.clone() if m == tl.TL_COMM_NONE else torch.zeros((T, H), dtype=torch.int16, device=dev)
+        return st
+
+    def p1_call(st):
+        tl.tl_moe_ag_gather_gemm(st["ctx"], x_shards, st["xg"], w1, st["srow"], st["tab"], st["nt"], y1, T, H, I, E, k, st["flags"], st["epoch"],
+                                 st["wsp"], st["q"]["ws_bytes"], cs, ms)
+
+    def p2_call(st):
+        tl.tl_moe_gemm_scatter_rs(st["ctx"], x2, w2, st["srow"], st["tab"], st["nt"], st["tw"], scatter, partial, recv, push, out, T, H, I, E, k,
+                                  st["flags"], st["epoch"], st["wsp"], st["q"]["ws_bytes"], cs, ms)
+
+    flop_moe = 2.0 * T * k * H * I
+    res["moe_ag_gather_gemm"] = triple(p1_make, p1_call, flop_moe, {"workload": f"T={T} H={H} I={I} E={E} top{k}, TP=8 share, rank 0"})
+    res["moe_gemm_scatter_rs"] = triple(lambda m, alone: moe_state(tl.TL_OP_MOE_GEMM_SCATTER_RS, m, alone, 1), p2_call, flop_moe,
+                                        {"workload": f"T={T} H={H} I={I} E={E} top{k}, TP=8 share, rank 0; compute alone = grouped GEMM + scatter only"})
+    del x_shards, x_full, w1, w2, x2, y1, scatter, partial, recv, push, out
+
+    # ---------------- sequence-parallel attention (configuration 5), causal, rank 7
+    c = wl.CONFIGS[5]
+    S, Hd, D, rank = c["S"], c["heads"], c["head_dim"], R - 1
+    w = wl.sp_attention_inputs(S, Hd, D, R)
+    S_loc = S // R
+    q_dev = up(w["q_shards"][rank])
+    ks, vs = [up(x) for x in w["k_shards"]], [up(x) for x in w["v_shards"]]
+    k_full, v_full = torch.cat(ks).clone(), torch.cat(vs).clone()
+    o = torch.zeros((S_loc, Hd, D), dtype=torch.int16, device=dev)
+
+    def at_make(m, alone):
+        ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=1, comm_mode=m, spin_timeout_us=10_000_000, comm_alone=alone)
+        info = tl.tl_attn_query(ctx, S, Hd, D, True)
+        full = m == tl.TL_COMM_NONE
+        return dict(ctx=ctx, info=info, kg=k_full if full else torch.zeros_like(k_full), vg=v_full if full else torch.zeros_like(v_full),
+                    flags=torch.zeros(info["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+
+    def at_call(st):
+        tl.tl_sp_ag_attention(st["ctx"], q_dev, ks, vs, st["kg"], st["vg"], o, S, Hd, D, True, D ** -0.5, st["flags"], st["epoch"], st["wsp"],
+                              st["info"]["ws_bytes"], cs, ms)
+
+    g = rank * S_loc + np.arange(S_loc, dtype=np.float64)
+    flop_attn = 4.0 * D * Hd * float((g + 1).sum())     # QK^T and PV over the keys a causal query sees
+    res["sp_ag_attention"] = triple(at_make, at_call, flop_attn,
+                                    {"workload": f"S={S} heads={Hd} head_dim={D} causal, TP=8 share, rank {rank} (keys 0..{S - 1})",
+                                     "flop_count": "4*D*heads*sum_i(position_i+1): masked pairs are not counted"})
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +157,8 @@ def main():
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the secondary measurements (MoE halves, sequence-parallel attention); they are outside the timed step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (5 times): the known-size kernel against which the FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
@@ -189,6 +297,9 @@ def main():
                      "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)"},
         "host_wall_ms_per_step": round(wall_step, 4),
     }
+    if not args.no_extras:
+        out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
+                               args.steps, args.warmup)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops
         out["cpu_baseline"] = cpu_baseline(np, wl, oracle_ops)

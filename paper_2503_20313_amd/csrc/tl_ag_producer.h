@@ -42,6 +42,8 @@ __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out)
 }
 
 // All threads of the workgroup call this with the same ticket index; `wave` is the wave-uniform wave index.
+// DEPTH = loads in flight per lane of the copy.
+template <int DEPTH>
 __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid, int wave, int nthreads) {
   const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
   int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
@@ -53,7 +55,7 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
   if (!(src == p.rank && p.local_in_place)) {
     const bf16_t* s = p.shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.ld + (long)tn * p.Tn_p;
     bf16_t* d = p.gathered + (long)row_lo * p.ld + (long)tn * p.Tn_p;
-    copy_tile(s, p.ld, d, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
+    copy_tile<DEPTH>(s, p.ld, d, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
   }
   __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
   if (wave == 0) wave_tile_notify(p.flags + channel);
@@ -72,7 +74,7 @@ __device__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_t
     int i = __builtin_amdgcn_readfirstlane(*s_ticket);
     __syncthreads();
     if (i < 0) break;
-    produce_tile(p, i, tid, wave, nthreads);
+    produce_tile<8>(p, i, tid, wave, nthreads);
   }
 }
 
@@ -124,7 +126,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     int state = __builtin_amdgcn_readfirstlane(*s_ticket);
     __syncthreads();
     if (state == -2) break;
-    if (state >= 0) produce_tile(p, state, tid, wave, nthreads);
+    if (state >= 0) produce_tile<2>(p, state, tid, wave, nthreads);  // shallow: this path shares its registers with the caller's matrix tile
     else __builtin_amdgcn_s_sleep(8);
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);

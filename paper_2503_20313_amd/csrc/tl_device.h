@@ -5,6 +5,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace tl {
 
@@ -158,18 +159,95 @@ __host__ __device__ inline int sched_tile(const Sched& s, int p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Copy of a rows x cols (bf16, cols % 8 == 0) tile by one workgroup, 16 bytes per lane and
-// access, four accesses in flight per lane.  Pointers must be 16-byte aligned and a tile must
-// span less than 4 GiB in either matrix (offsets inside the tile are 32-bit, so that an access is
-// a uniform base plus one offset register: the copy loops have to stay small enough in registers
-// to share a SIMD with two waves of a matrix kernel).
+// Tile movers of the communication side: copy_tile (tile_push_data / tile_pull_data / rank_copy_data)
+// and sum_tile (reduction of several source tiles).  A tile is rows x cols bf16 with cols % 8 == 0,
+// 16-byte aligned, and spans less than 2 GiB in every matrix it lives in.
+//
+// These loops run beside two waves of a matrix kernel on every SIMD, which leaves them 48 vector
+// registers, and a copy is bound by the bytes it keeps in flight: so all accesses of a lane use
+// buffer addressing -- one resource descriptor per matrix in scalar registers, ONE lane-offset
+// register, and a scalar offset that moves from step to step -- and eight 16-byte loads per lane
+// are in flight at a time.  A "step" is one pass of the workgroup over nthreads consecutive
+// 16-byte chunks; the tile shapes in use make a step either a block of whole rows (chunks per row
+// divides nthreads) or a piece of one row (nthreads divides chunks per row), and in both cases a
+// lane's chunk in step s is its chunk in step 0 shifted by a lane-independent offset.  Other shapes
+// fall back to per-lane index arithmetic with four loads in flight.  The hardware range-checks a
+// buffer access against the extent of the tile, so a wrong offset can return zeros but cannot fault.
 // ---------------------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t tile_rsrc(const void* base, long ld, int rows, int cols) {
+  unsigned bytes = (unsigned)(((long)(rows - 1) * ld + cols) * 2);
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+// Walk of the steps of a tile: for step s, off(ld_bytes) is the lane-independent byte offset of the step.
+struct TileSteps {
+  bool rows_mode;   // a step is dr whole rows; else a row takes spr steps
+  int dr, spr, n_full, n_steps, nthreads;
+  int lane_r, lane_c;  // the lane's chunk in step 0
+  bool ok;
+  __device__ __forceinline__ unsigned off(int s, unsigned ld_bytes) const {
+    if (rows_mode) return (unsigned)(s * dr) * ld_bytes;
+    int row = s / spr, sub = s - row * spr;
+    return (unsigned)row * ld_bytes + (unsigned)(sub * nthreads) * 16u;
+  }
+};
+
+__device__ __forceinline__ TileSteps tile_steps(int rows, int cpr, int tid, int nthreads) {
+  TileSteps t;
+  t.nthreads = nthreads;
+  t.ok = true;
+  t.rows_mode = cpr <= nthreads;
+  if (t.rows_mode) {
+    t.dr = nthreads / cpr; t.spr = 1;
+    t.ok = t.dr * cpr == nthreads;
+    t.lane_r = tid / cpr; t.lane_c = tid - t.lane_r * cpr;
+    t.n_full = rows / t.dr; t.n_steps = (rows + t.dr - 1) / t.dr;
+  } else {
+    t.dr = 0; t.spr = cpr / nthreads;
+    t.ok = t.spr * nthreads == cpr;
+    t.lane_r = 0; t.lane_c = tid;
+    t.n_full = t.n_steps = rows * t.spr;
+  }
+  return t;
+}
+
+__device__ __forceinline__ u32x4 buf_load16(rsrc_t r, unsigned lane_off, unsigned step_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)step_off, 2 /* streaming */);
+}
+__device__ __forceinline__ void buf_store16(u32x4 v, rsrc_t r, unsigned lane_off, unsigned step_off) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, (int)step_off, 0);
+}
+
+template <int DEPTH = 8>  // loads in flight per lane
 __device__ __forceinline__ void copy_tile(const bf16_t* __restrict__ src, long src_ld, bf16_t* __restrict__ dst, long dst_ld,
                                           int rows, int cols, int tid, int nthreads) {
   const int cpr = cols >> 3;  // 16-byte chunks per row
+  const unsigned sld = (unsigned)src_ld * 2u, dld = (unsigned)dst_ld * 2u;
+  const TileSteps ts = tile_steps(rows, cpr, tid, nthreads);
+  if (ts.ok) {
+    const rsrc_t rs = tile_rsrc(src, src_ld, rows, cols), rd = tile_rsrc(dst, dst_ld, rows, cols);
+    const unsigned so = (unsigned)ts.lane_r * sld + (unsigned)ts.lane_c * 16u, dof = (unsigned)ts.lane_r * dld + (unsigned)ts.lane_c * 16u;
+    int st = 0;
+    for (; st + DEPTH <= ts.n_full; st += DEPTH) {
+      u32x4 v[DEPTH];
+#pragma unroll
+      for (int u = 0; u < DEPTH; u++) v[u] = buf_load16(rs, so, ts.off(st + u, sld));
+#pragma unroll
+      for (int u = 0; u < DEPTH; u++) buf_store16(v[u], rd, dof, ts.off(st + u, dld));
+    }
+    for (; st + 2 <= ts.n_full; st += 2) {
+      u32x4 v0 = buf_load16(rs, so, ts.off(st, sld)), v1 = buf_load16(rs, so, ts.off(st + 1, sld));
+      buf_store16(v0, rd, dof, ts.off(st, dld));
+      buf_store16(v1, rd, dof, ts.off(st + 1, dld));
+    }
+    for (; st < ts.n_steps; st++)   // at most one full step, then the partial one (rows mode): predicated per lane
+      if (st < ts.n_full || st * ts.dr + ts.lane_r < rows) buf_store16(buf_load16(rs, so, ts.off(st, sld)), rd, dof, ts.off(st, dld));
+    return;
+  }
   const int total = rows * cpr;
   const int dr = nthreads / cpr, dc = nthreads - dr * cpr;  // chunk index + nthreads = (row + dr, chunk + dc) with carry
-  const unsigned sld = (unsigned)src_ld * 2u, dld = (unsigned)dst_ld * 2u;
   const char* sb = (const char*)src;
   char* db = (char*)dst;
   int r = tid / cpr, c = tid - r * cpr;
@@ -190,6 +268,79 @@ __device__ __forceinline__ void copy_tile(const bf16_t* __restrict__ src, long s
   for (; i < total; i += nthreads) {
     *(u32x4*)(db + ((unsigned)r * dld + (unsigned)c * 16u)) =
         __builtin_nontemporal_load((const u32x4*)(sb + ((unsigned)r * sld + (unsigned)c * 16u)));
+    r += dr; c += dc;
+    if (c >= cpr) { c -= cpr; r++; }
+  }
+}
+
+// dst tile = bf16( sum over n_src source tiles, fp32, in source order ).  src(q) returns the uniform base pointer of
+// source q's tile; all sources share the row pitch src_ld.  Up to DEPTH sources of one chunk are in flight.
+__device__ __forceinline__ void acc_bf16x8(float (&s)[8], u32x4 v) {
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    s[2 * e] += __uint_as_float(v[e] << 16);
+    s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+  }
+}
+
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&s)[8]) {
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
+  return __builtin_bit_cast(u32x4, v);
+}
+
+template <int DEPTH = 4, int POS = 1, class SrcFn>  // DEPTH sources of POS chunks in flight per lane
+__device__ __forceinline__ void sum_tile(SrcFn src, int n_src, bf16_t* dst, long src_ld, long dst_ld, int rows, int cols, int tid,
+                                         int nthreads) {
+  const int cpr = cols >> 3;
+  const unsigned sld = (unsigned)src_ld * 2u, dld = (unsigned)dst_ld * 2u;
+  const TileSteps ts = tile_steps(rows, cpr, tid, nthreads);
+  if (ts.ok) {
+    const rsrc_t rd = tile_rsrc(dst, dst_ld, rows, cols);
+    const unsigned so = (unsigned)ts.lane_r * sld + (unsigned)ts.lane_c * 16u, dof = (unsigned)ts.lane_r * dld + (unsigned)ts.lane_c * 16u;
+    // NP chunks (steps st .. st+NP-1) of this lane: sum their sources, store
+    auto group = [&](auto np_c, int st) {
+      constexpr int NP = decltype(np_c)::value;
+      float s[NP][8];
+#pragma unroll
+      for (int w = 0; w < NP; w++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) s[w][e] = 0.f;
+      for (int q0 = 0; q0 < n_src; q0 += DEPTH) {
+        u32x4 v[NP][DEPTH];
+#pragma unroll
+        for (int u = 0; u < DEPTH; u++)
+          if (q0 + u < n_src) {  // uniform condition
+            const rsrc_t rq = tile_rsrc(src(q0 + u), src_ld, rows, cols);
+#pragma unroll
+            for (int w = 0; w < NP; w++) v[w][u] = buf_load16(rq, so, ts.off(st + w, sld));
+          }
+#pragma unroll
+        for (int u = 0; u < DEPTH; u++)
+          if (q0 + u < n_src) {
+#pragma unroll
+            for (int w = 0; w < NP; w++) acc_bf16x8(s[w], v[w][u]);
+          }
+      }
+#pragma unroll
+      for (int w = 0; w < NP; w++) buf_store16(pack_bf16x8(s[w]), rd, dof, ts.off(st + w, dld));
+    };
+    int st = 0;
+    for (; st + POS <= ts.n_full; st += POS) group(std::integral_constant<int, POS>{}, st);
+    for (; st < ts.n_steps; st++)   // fewer than POS full steps, then the partial one (rows mode): predicated per lane
+      if (st < ts.n_full || st * ts.dr + ts.lane_r < rows) group(std::integral_constant<int, 1>{}, st);
+    return;
+  }
+  const int total = rows * cpr;
+  const int dr = nthreads / cpr, dc = nthreads - dr * cpr;
+  char* db = (char*)dst;
+  int r = tid / cpr, c = tid - r * cpr;
+  for (int i = tid; i < total; i += nthreads) {
+    const unsigned so = (unsigned)r * sld + (unsigned)c * 16u;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < n_src; q++) acc_bf16x8(s, __builtin_nontemporal_load((const u32x4*)((const char*)src(q) + so)));
+    *(u32x4*)(db + ((unsigned)r * dld + (unsigned)c * 16u)) = pack_bf16x8(s);
     r += dr; c += dc;
     if (c >= cpr) { c -= cpr; r++; }
   }

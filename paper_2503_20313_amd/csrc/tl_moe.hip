@@ -233,17 +233,10 @@ __device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int
       if (tid == 0) tile_wait(p.rows_ready + tb * p.nbn + bn, p.epoch * (unsigned)(p.Tt * p.topk), p.rs.ctl, tb * p.nbn + bn);
       __syncthreads();
     }
-    const int cpr = cols >> 3, total = p.Tt * cpr;
-    for (int idx = tid; idx < total; idx += nthreads) {
-      int r = idx / cpr, c = idx - r * cpr;
-      const bf16_t* src = p.scatter + (long)(t_lo + r) * p.topk * p.H + col_lo + c * 8;
-      float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int j = 0; j < p.topk; j++) acc_bf16x8(s, *(const u32x4*)(src + (long)j * p.H));
-      bf16x8 v;
-#pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
-      *(bf16x8*)(p.rs.partial + (long)(t_lo + r) * p.H + col_lo + c * 8) = v;
-    }
+    // token t's routed rows are rows t*topk .. t*topk+topk-1 of the scatter buffer: source j = the buffer shifted by j rows, pitch topk*H
+    const bf16_t* src0 = p.scatter + (long)t_lo * p.topk * p.H + col_lo;
+    sum_tile<2, 2>([&](int j) { return src0 + (long)j * p.H; }, p.topk, p.rs.partial + (long)t_lo * p.H + col_lo, (long)p.topk * p.H, p.H, p.Tt, cols,
+             tid, nthreads);
     __syncthreads();
     if (tid == 0) tile_notify(p.rs.ready + tb * p.rs.ncn + bn);
   }
@@ -281,17 +274,26 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
     gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
                    ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
     if (p.do_notify) {
-      // producer_tile_notify with a count: the rows of this tile are token-ascending, so each token block
-      // receives one run of them; the first row of a run adds the run's length to the block's counter
+      // producer_tile_notify with a count: the rows of this tile are token-ascending, so each token block receives
+      // one run of them; the first row of a run adds the run's length to the block's counter.  The token block of
+      // every row goes through LDS (free once the tile is stored) so that finding the runs costs no global loads;
+      // one wave issues a single device-scope release for the whole tile, then relaxed adds.
+      __syncthreads();  // every wave's stores of the tile have completed
+      int* s_tb = (int*)smem;
+      for (int r = tid; r < rows; r += Cfg::NTHREADS) s_tb[r] = (p.sorted_row[f_lo + r] / p.topk) / p.Tt;
       __syncthreads();
-      for (int r = tid; r < rows; r += Cfg::NTHREADS) {
-        int tb = (p.sorted_row[f_lo + r] / p.topk) / p.Tt;
-        if (r == 0 || (p.sorted_row[f_lo + r - 1] / p.topk) / p.Tt != tb) {
-          int n = 1;
-          while (r + n < rows && (p.sorted_row[f_lo + r + n] / p.topk) / p.Tt == tb) n++;
-          tile_notify(p.rows_ready + tb * p.nbn + bn, (unsigned)n);
+      if (__builtin_amdgcn_readfirstlane(tid >> 6) == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        for (int r = tid; r < rows; r += 64) {
+          int tb = s_tb[r];
+          if (r == 0 || s_tb[r - 1] != tb) {
+            int n = 1;
+            while (r + n < rows && s_tb[r + n] == tb) n++;
+            __hip_atomic_fetch_add(p.rows_ready + tb * p.nbn + bn, (unsigned)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
         }
       }
+      __syncthreads();  // the next tile's loads overwrite s_tb
     }
   }
 }

@@ -28,14 +28,6 @@ struct RsSide {
 // peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
 // landing zone and notify it.
 // ======================================================================================
-__device__ __forceinline__ void acc_bf16x8(float (&s)[8], u32x4 v) {
-#pragma unroll
-  for (int e = 0; e < 4; e++) {
-    s[2 * e] += __uint_as_float(v[e] << 16);
-    s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
-  }
-}
-
 __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthreads) {
   const int n_rt = p.ncm * p.ncn;
   const int cm_per_seg = p.seg_rows / p.Tm_r;
@@ -64,22 +56,10 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
     }
     __syncthreads();
     const bf16_t* mine = p.partial + (long)row_lo * p.N + col_lo;
-    const int cpr = cols >> 3, total = rows * cpr;
     if (dest == p.rank) {
-      bf16_t* o = p.out + (long)seg_row * p.N + col_lo;
-      for (int idx = tid; idx < total; idx += nthreads) {
-        int r = idx / cpr, c = idx - r * cpr;
-        long off = (long)r * p.N + c * 8;
-        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int q = 0; q < p.R; q++) {
-          const bf16_t* src = (q == p.rank) ? mine : p.peer_recv[q] + (long)seg_row * p.N + col_lo;
-          acc_bf16x8(s, *(const u32x4*)(src + off));
-        }
-        bf16x8 v;
-#pragma unroll
-        for (int e = 0; e < 8; e++) v[e] = (bf16_t)s[e];
-        *(bf16x8*)(o + off) = v;
-      }
+      const long seg_off = (long)seg_row * p.N + col_lo;
+      sum_tile<4>([&](int q) { return q == p.rank ? mine : p.peer_recv[q] + seg_off; }, p.R, p.out + seg_off, p.N, p.N, rows, cols, tid,
+               nthreads);
     } else {
       // tile_push_data to the owner's landing zone, then peer_tile_notify
       copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
