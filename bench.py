@@ -42,7 +42,7 @@ def cpu_baseline(np, wl, ops):
                       f"float64 numpy, {dt:.1f} s (+{t0 - t_gen:.1f} s input generation)"}
 
 
-def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup):
+def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push):
     """Secondary measurements, outside the timed step: the two MoE halves (configuration 4) and sequence-parallel
     attention (configuration 5, causal, the last rank = the one with the most keys), each fused, compute alone
     (communication off, gathered inputs complete) and communication alone."""
@@ -88,7 +88,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup):
 
     def moe_state(op, m, alone, C):
         ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
-                               spin_timeout_us=10_000_000, comm_alone=alone)
+                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push)
         q = tl.tl_moe_query(ctx, op, T, H, I, E, k)
         st = dict(ctx=ctx, q=q,
                   ids=torch.zeros((T, k), dtype=torch.int32, device=dev), tw=torch.zeros((T, k), dtype=torch.float32, device=dev),
@@ -156,6 +156,9 @@ def main():
     ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream"])
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
+    ap.add_argument("--no-direct-push", action="store_true",
+                    help="GEMM+RS: store every partial row locally and let the communication side copy the other ranks' rows "
+                         "(default: the GEMM epilogue stores them straight into the peers' landing zones)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (MoE halves, sequence-parallel attention); they are outside the timed step")
@@ -212,7 +215,7 @@ def main():
         def __init__(self, op, dims, comm_mode, comm_alone=0):
             self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode,
                                         comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
-                                        spin_timeout_us=10_000_000, comm_alone=comm_alone)
+                                        spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else 1)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
             self.flags = torch.zeros(n_flags, dtype=torch.int32, device=dev)
@@ -288,7 +291,8 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "MLP-5 TP=8 share: AG+GEMM 8x[1024,8192]->[8192,8192]x[8192,3584] then GEMM+RS [8192,3584]x[3584,8192]->[1024,8192]",
-                   "world_size": R, "rank": rank, "comm_mode": args.comm_mode, "channels_per_rank": args.channels},
+                   "world_size": R, "rank": rank, "comm_mode": args.comm_mode, "channels_per_rank": args.channels,
+                   "rs_direct_push": 0 if args.no_direct_push else 1},
         "overlap_efficiency": round(min(res["ag_gemm"]["overlap_efficiency"], res["gemm_rs"]["overlap_efficiency"]), 4),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "ops": res,
@@ -299,7 +303,7 @@ def main():
     }
     if not args.no_extras:
         out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
-                               args.steps, args.warmup)
+                               args.steps, args.warmup, 0 if args.no_direct_push else 1)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops
         out["cpu_baseline"] = cpu_baseline(np, wl, oracle_ops)

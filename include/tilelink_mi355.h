@@ -85,6 +85,11 @@ typedef struct tl_config {
   unsigned spin_timeout_us;/* bound on every flag wait; 0 = unbounded */
   int comm_alone;          /* 1: run only the communication side of comm_mode (no GEMM tiles; producer-consumer waits
                               skipped, the GEMM's output is taken as already complete): for timing */
+  int rs_direct_push;      /* ReduceScatter operators: 1 = the stage that produces the partial result stores the rows of
+                              other ranks' segments straight into peer_push[] (tile_push_data from the producer's
+                              epilogue) and only the rows of the own segment into `partial`; the communication side then
+                              just forwards the notification for those tiles instead of copying them.  The flags keep
+                              their meaning; the rows of `partial` outside the own segment are not written. */
 } tl_config;
 
 typedef struct tl_ctx tl_ctx;
@@ -143,6 +148,8 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards /*host array of dev*/, v
  *              peer-arrival counters (peer-major; entry for peer q counts q's pushes into this rank, raised by
  *              the library's simulated peers), then the same number of pushed counters (this rank's pushes
  *              into peer q).  Each grows by its expected count per call.
+ *   With tl_config.rs_direct_push the GEMM epilogue stores each output row at its final place (own segment: `partial`,
+ *   segment q: peer_push[q]) and the reduce side only forwards the notifications of the pushed tiles.
  *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 64 == 0, N % 8 == 0.
  */
 int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv /*host array of dev*/,
@@ -201,6 +208,8 @@ int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards /*host array 
  *   scatter_buf dev [T*topk,H] bf16 (written); partial dev [T,H] bf16 (written)
  *   peer_recv / peer_push host arrays of R dev pointers, each [T/R,H] bf16; out dev [T/R,H] bf16 (written)
  *   flags dev unsigned[info[3] of tl_moe_query]: row counters | reduce-tile ready | peer arrived | pushed
+ *   With tl_config.rs_direct_push stage B stores the token blocks of another rank's segment straight into peer_push[]
+ *   (and those of the own segment into `partial`), and stage C only forwards their notifications.
  *   Requirements: those of tl_moe_route, H % tile_n == 0, tokens per reduce tile | T/R.  comm_mode: NONE (stage A only),
  *   WAVES or SIDE_KERNEL.
  */

@@ -29,7 +29,8 @@ class tl_config(ctypes.Structure):
                 ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("comm_tile_m", ctypes.c_int),
                 ("comm_tile_n", ctypes.c_int), ("comm_mode", ctypes.c_int), ("comm_workgroups", ctypes.c_int),
                 ("compute_workgroups", ctypes.c_int), ("tile_order", ctypes.c_int), ("xcd_swizzle", ctypes.c_int),
-                ("group_m", ctypes.c_int), ("spin_timeout_us", ctypes.c_uint), ("comm_alone", ctypes.c_int)]
+                ("group_m", ctypes.c_int), ("spin_timeout_us", ctypes.c_uint), ("comm_alone", ctypes.c_int),
+                ("rs_direct_push", ctypes.c_int)]
 
 
 if not os.path.exists(LIB_PATH):

@@ -92,8 +92,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
     int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
     int rows = min(Cfg::BM, rs.M - row_lo), cols = min(Cfg::BN, rs.N - col_lo);
-    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N,
-                   DenseRows{rs.partial + (long)row_lo * rs.N + col_lo, rs.N}, rows, cols, p.K, smem);
+    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRows{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
     if (p.do_notify) {
       // producer_tile_notify: one release-add per reduce tile this GEMM tile overlaps
       __syncthreads();

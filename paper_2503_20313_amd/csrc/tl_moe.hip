@@ -235,8 +235,12 @@ __device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int
     }
     // token t's routed rows are rows t*topk .. t*topk+topk-1 of the scatter buffer: source j = the buffer shifted by j rows, pitch topk*H
     const bf16_t* src0 = p.scatter + (long)t_lo * p.topk * p.H + col_lo;
-    sum_tile<2, 2>([&](int j) { return src0 + (long)j * p.H; }, p.topk, p.rs.partial + (long)t_lo * p.H + col_lo, (long)p.topk * p.H, p.H, p.Tt, cols,
-             tid, nthreads);
+    // a token block lies inside one rank's segment (Tt divides T/R): with direct push the reduced rows of another
+    // rank's segment go straight to that rank's landing zone
+    const int dest = t_lo / p.rs.seg_rows;
+    bf16_t* dst = (!p.rs.direct || dest == p.rs.rank) ? p.rs.partial + (long)t_lo * p.H + col_lo
+                                                      : p.rs.peer_push[dest] + (long)(t_lo - dest * p.rs.seg_rows) * p.H + col_lo;
+    sum_tile<2, 2>([&](int j) { return src0 + (long)j * p.H; }, p.topk, dst, (long)p.topk * p.H, p.H, p.Tt, cols, tid, nthreads);
     __syncthreads();
     if (tid == 0) tile_notify(p.rs.ready + tb * p.rs.ncn + bn);
   }

@@ -16,6 +16,7 @@ struct RsSide {
   int seg_rows, tiles_per_seg;
   int rs_first_block;               // rotation of reduce row-blocks
   int do_wait;                      // wait for the producer stage's notifications
+  int direct;                       // the producer stage stored the other segments' rows into peer_push itself
   unsigned epoch;
   unsigned* ready;                  // [ncm*ncn]
   unsigned* arrived;                // [R*tiles_per_seg]
@@ -61,14 +62,29 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
       sum_tile<4>([&](int q) { return q == p.rank ? mine : p.peer_recv[q] + seg_off; }, p.R, p.out + seg_off, p.N, p.N, rows, cols, tid,
                nthreads);
     } else {
-      // tile_push_data to the owner's landing zone, then peer_tile_notify
-      copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
+      // tile_push_data to the owner's landing zone (unless the producer stage has put the rows there itself), then
+      // peer_tile_notify
+      if (!p.direct) copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
       __syncthreads();
       if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);
     }
   }
 }
 
+
+// Where the rows of a [M,N] partial result go (output functor of the matrix tile): row g of the own segment to
+// partial[g,:], and with direct push row g of segment q to peer_push[q][g - q*seg_rows,:]; else all rows to partial.
+struct PushRows {
+  static constexpr bool SCALED = false;
+  const RsSide* rs;
+  int row_lo, col_lo;
+  __device__ __forceinline__ bf16_t* row(int r, float& scale) const {
+    const int g = row_lo + r;
+    const int dest = g / rs->seg_rows;
+    if (!rs->direct || dest == rs->rank) return rs->partial + (long)g * rs->N + col_lo;
+    return rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo;
+  }
+};
 
 // Simulated peers: peer q's push of every tile of this rank's segment "arrives".
 __global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R, int rank);

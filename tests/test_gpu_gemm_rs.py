@@ -43,15 +43,23 @@ def run_gemm_rs(w, mode, epochs=1, **cfg):
     return host_a, down(partial), [None if t is None else down(t) for t in push], down(out), flags.cpu().numpy(), info
 
 
-def check(w, host_a, partial, push, out, what):
+def check(w, host_a, partial, push, out, what, direct=False):
     R, rank = w["world"], w["rank"]
     seg = w["M"] // R
     p_ref, _, out_ref = ops.gemm_rs(host_a, w["b"], w["peer_segments"], rank)
-    assert_close_bf16(partial, p_ref, what + " partial")
-    for q in range(R):
-        if q != rank:
-            # what was pushed to peer q is exactly this rank's partial rows of segment q
-            assert np.array_equal(push[q], partial[q * seg:(q + 1) * seg]), f"{what}: push to peer {q}"
+    if direct:
+        # the GEMM epilogue stored segment q's rows straight into peer q's landing zone; `partial` holds the own segment only
+        assert_close_bf16(partial[rank * seg:(rank + 1) * seg], p_ref[rank * seg:(rank + 1) * seg], what + " partial (own segment)")
+        for q in range(R):
+            if q != rank:
+                assert (partial[q * seg:(q + 1) * seg] == 0x7FC0).all(), f"{what}: partial rows of segment {q} were written"
+                assert_close_bf16(push[q], p_ref[q * seg:(q + 1) * seg], f"{what}: push to peer {q}")
+    else:
+        assert_close_bf16(partial, p_ref, what + " partial")
+        for q in range(R):
+            if q != rank:
+                # what was pushed to peer q is exactly this rank's partial rows of segment q
+                assert np.array_equal(push[q], partial[q * seg:(q + 1) * seg]), f"{what}: push to peer {q}"
     # the reduction of the GPU's own partial with the peers' rows, recomputed by the oracle: tight check of the reducer
     own = partial[rank * seg:(rank + 1) * seg]
     red = ops.reduce_scatter_segment(own, w["peer_segments"], rank)
@@ -63,12 +71,13 @@ def check(w, host_a, partial, push, out, what):
     return assert_close_bf16(out, out_ref, what + " out")
 
 
+@pytest.mark.parametrize("direct", [0, 1])
 @pytest.mark.parametrize("mode", list(MODES))
 @pytest.mark.parametrize("rank", [0, 1])
-def test_small(mode, rank):
+def test_small(mode, rank, direct):
     w = wl.gemm_rs_inputs(256, 512, 512, 2, rank, config_id=21)
-    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=3, comm_workgroups=2)
-    check(w, ha, partial, push, out, f"small {mode} r={rank}")
+    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=3, comm_workgroups=2, rs_direct_push=direct)
+    check(w, ha, partial, push, out, f"small {mode} r={rank} direct={direct}", direct=bool(direct))
     n_rt = info["n_comm_tiles"]
     tps = n_rt // 2
     ready, arrived, pushed = flags[:n_rt], flags[n_rt:n_rt + 2 * tps], flags[n_rt + 2 * tps:]
@@ -78,13 +87,15 @@ def test_small(mode, rank):
     assert pushed[other * tps:(other + 1) * tps].tolist() == [3] * tps and pushed[rank * tps:(rank + 1) * tps].tolist() == [0] * tps
 
 
+@pytest.mark.parametrize("direct", [0, 1])
 @pytest.mark.parametrize("tile,rt", [((256, 256), (56, 152)), ((256, 224), (140, 456)), ((128, 128), (280, 8)), ((128, 128), (20, 152))])
-def test_ragged_and_mismatched_reduce_tiles(tile, rt):
-    # 4 segments of 280 rows, N = 456: ragged for every GEMM tile; reduce tiles smaller and larger than GEMM tiles
+def test_ragged_and_mismatched_reduce_tiles(tile, rt, direct):
+    # 4 segments of 280 rows, N = 456: ragged for every GEMM tile (a 256-row tile straddles two segments, so with
+    # direct push its rows go to two different places); reduce tiles smaller and larger than GEMM tiles
     w = wl.gemm_rs_inputs(1120, 456, 192, 4, 1, config_id=22)
     ha, partial, push, out, flags, info = run_gemm_rs(w, tl.TL_COMM_WAVES, epochs=2, tile_m=tile[0], tile_n=tile[1],
-                                                      comm_tile_m=rt[0], comm_tile_n=rt[1], comm_workgroups=3)
-    check(w, ha, partial, push, out, f"ragged tile={tile} reduce={rt}")
+                                                      comm_tile_m=rt[0], comm_tile_n=rt[1], comm_workgroups=3, rs_direct_push=direct)
+    check(w, ha, partial, push, out, f"ragged tile={tile} reduce={rt} direct={direct}", direct=bool(direct))
     table = omap.rs_tile_table(1120, 456, 4, 1, tile[0], tile[1], rt[0], rt[1])
     assert flags[:len(table)].tolist() == [2 * e[7] for e in table]
 
@@ -108,11 +119,11 @@ def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("mode,order", [("waves", tl.TL_ORDER_RING), ("side", tl.TL_ORDER_OWN_FIRST)])
-def test_full_size_tp8_share(mode, order):
+@pytest.mark.parametrize("mode,order,direct", [("waves", tl.TL_ORDER_RING, 0), ("side", tl.TL_ORDER_OWN_FIRST, 0), ("side", tl.TL_ORDER_OWN_FIRST, 1)])
+def test_full_size_tp8_share(mode, order, direct):
     """BASELINE configuration 3: A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]; the side-kernel /
     own-first combination is the launch configuration bench.py times."""
     w = wl.gemm_rs_inputs(8192, 8192, 3584, 8, 0, config_id=3)
-    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=2, tile_order=order)
-    rel, mx = check(w, ha, partial, push, out, f"cfg3 {mode}")
+    ha, partial, push, out, flags, info = run_gemm_rs(w, MODES[mode], epochs=2, tile_order=order, rs_direct_push=direct)
+    rel, mx = check(w, ha, partial, push, out, f"cfg3 {mode} direct={direct}", direct=bool(direct))
     print(f"cfg3 {mode}: tile {info['tile_m']}x{info['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")

@@ -137,11 +137,17 @@ def run_part2(w, mode, epochs=1, **cfg):
     assert_close_bf16(down(scatter), s_ref, "MoE part 2 scatter")
     if mode == tl.TL_COMM_NONE:
         return q
-    assert_close_bf16(down(partial), p_ref, "MoE part 2 partial")
+    pg = down(partial)
+    if cfg.get("rs_direct_push"):
+        # stage B stored the other segments' token blocks straight into the peers' landing zones: reassemble
+        for q_ in range(R):
+            if q_ != rank:
+                assert (pg[q_ * seg:(q_ + 1) * seg] == 0x7FC0).all(), f"partial rows of segment {q_} were written"
+                pg[q_ * seg:(q_ + 1) * seg] = down(push_t[q_])
+    assert_close_bf16(pg, p_ref, "MoE part 2 partial")
     # the GPU's own top-k reduce and ReduceScatter, recomputed by the oracle from the GPU's intermediate tensors (tight)
     sc = down(scatter)
     p_exact = round_to_bf16(widen(sc).reshape(T, k, H).sum(axis=1))
-    pg = down(partial)
     assert np.mean(pg != p_exact) < 0.02 and np.all(np.abs(widen(pg) - widen(p_exact)) <= np.abs(widen(p_exact)) * 2.0 ** -7 + 1e-30)
     for q_ in range(R):
         if q_ != rank:
@@ -158,11 +164,12 @@ def run_part2(w, mode, epochs=1, **cfg):
     return q
 
 
+@pytest.mark.parametrize("direct", [0, 1])
 @pytest.mark.parametrize("mode", list(MODES))
 @pytest.mark.parametrize("rank", [0, 1])
-def test_part2_small(mode, rank):
+def test_part2_small(mode, rank, direct):
     w = wl.moe_inputs(256, 256, 128, 4, 2, 2, rank, config_id=44)
-    run_part2(w, MODES[mode], epochs=2, comm_workgroups=4)
+    run_part2(w, MODES[mode], epochs=2, comm_workgroups=4, rs_direct_push=direct)
 
 
 def test_part2_gemm_stage_only_and_other_shapes():
@@ -170,6 +177,7 @@ def test_part2_gemm_stage_only_and_other_shapes():
     run_part2(w, tl.TL_COMM_NONE)
     run_part2(w, tl.TL_COMM_WAVES, epochs=2, comm_workgroups=5, comm_tile_m=64, tile_m=256, tile_n=256)
     run_part2(w, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=6, tile_m=128, tile_n=128, tile_order=tl.TL_ORDER_OWN_FIRST)
+    run_part2(w, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=6, tile_m=256, tile_n=256, tile_order=tl.TL_ORDER_OWN_FIRST, rs_direct_push=1)
 
 
 @pytest.mark.parametrize("mode", ["side"])
@@ -180,3 +188,4 @@ def test_full_size_tp8_share(mode):
     print(f"cfg4 part1 {mode}: tile {q1['tile_m']}x{q1['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")
     q2 = run_part2(w, MODES[mode], tile_order=tl.TL_ORDER_OWN_FIRST)
     print(f"cfg4 part2 {mode}: tile {q2['tile_m']}x{q2['tile_n']}")
+    run_part2(w, MODES[mode], tile_order=tl.TL_ORDER_OWN_FIRST, rs_direct_push=1)
