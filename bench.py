@@ -16,9 +16,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk x 2.4 GHz (dense bf16 MFMA)
 # HBM/fabric bytes per fused GEMM launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md (scaled by the plain-copy calibration): mean of AG+GEMM (832 + 187 MiB)
-# and GEMM+RS (672 + 194 MiB).  A measured constant, not recomputed by this script.
-HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (832 + 187 + 672 + 194) * 2 ** 20)
+# profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md (scaled by the plain-copy calibration): mean of AG+GEMM (833 + 187 MiB)
+# and GEMM+RS with direct push (672 + 151 MiB).  A measured constant, not recomputed by this script.
+HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (833 + 187 + 672 + 151) * 2 ** 20)
 
 
 def cpu_baseline(np, wl, ops):
@@ -133,8 +133,10 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
         ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=1, comm_mode=m, spin_timeout_us=10_000_000, comm_alone=alone)
         info = tl.tl_attn_query(ctx, S, Hd, D, True)
         full = m == tl.TL_COMM_NONE
-        return dict(ctx=ctx, info=info, kg=k_full if full else torch.zeros_like(k_full), vg=v_full if full else torch.zeros_like(v_full),
-                    flags=torch.zeros(info["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+        st = dict(ctx=ctx, info=info, kg=k_full if full else torch.zeros_like(k_full), vg=v_full if full else torch.zeros_like(v_full),
+                  flags=torch.zeros(info["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+        torch.cuda.synchronize()    # the fills ran on the default stream, the calls use cs and ms
+        return st
 
     def at_call(st):
         tl.tl_sp_ag_attention(st["ctx"], q_dev, ks, vs, st["kg"], st["vg"], o, S, Hd, D, True, D ** -0.5, st["flags"], st["epoch"], st["wsp"],
@@ -222,6 +224,7 @@ def main():
             self.wsp = torch.zeros(self.ws_bytes // 4, dtype=torch.int32, device=dev)
             self.epoch = 0
             self.info = tl.tl_resolve(self.ctx, op, dims)
+            torch.cuda.synchronize()    # the zero fills ran on the default stream, the calls use cs and ms
 
         def __call__(self):
             self.epoch += 1

@@ -32,12 +32,16 @@ struct AgProducer {
 // ======================================================================================
 // Called by every lane of one wave; the result is wave-uniform.
 __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out) {
+  const unsigned count = (unsigned)(p.n_ptm * p.n_ptn);
   unsigned t = lane0_fetch_add(p.ticket, 1u);
-  if ((int)(t - p.ticket_end) >= 0) {  // queue of this call is empty: give the ticket back
+  unsigned idx = t - (p.ticket_end - count);
+  // outside this call's range: the queue is empty (or the counter does not belong to this epoch, e.g. a workspace that
+  // was not zeroed): give the ticket back; an index outside [0, count) is never handed out
+  if (idx >= count) {
     lane0_add(p.ticket, 0xffffffffu);
     return false;
   }
-  *out = t - (p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn));
+  *out = idx;
   return true;
 }
 

@@ -89,7 +89,8 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
 // across the loop's back edge, after which the waves of a workgroup no longer meet the same
 // barrier in the same iteration.  These helpers are called by every lane of a wave; the atomic
 // itself is issued for lane 0 only by narrowing EXEC inside one asm statement, and the result is
-// returned as a wave-uniform value.  Device scope; ordering comes from the fences around them.
+// returned as a wave-uniform value.  Device scope (sc1: performed where all eight dies see it, as the compiler
+// does for an agent-scope atomic); ordering comes from the fences around them.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned lane0_fetch_add(unsigned* ptr, unsigned v) {
   unsigned r;
@@ -97,7 +98,7 @@ __device__ __forceinline__ unsigned lane0_fetch_add(unsigned* ptr, unsigned v) {
   asm volatile(
       "s_mov_b64 %1, exec\n\t"
       "s_mov_b64 exec, 1\n\t"
-      "global_atomic_add %0, %2, %3, off sc0\n\t"
+      "global_atomic_add %0, %2, %3, off sc0 sc1\n\t"
       "s_waitcnt vmcnt(0)\n\t"
       "s_mov_b64 exec, %1"
       : "=&v"(r), "=&s"(saved)
@@ -111,7 +112,7 @@ __device__ __forceinline__ void lane0_add(unsigned* ptr, unsigned v) {
   asm volatile(
       "s_mov_b64 %0, exec\n\t"
       "s_mov_b64 exec, 1\n\t"
-      "global_atomic_add %1, %2, off\n\t"
+      "global_atomic_add %1, %2, off sc1\n\t"
       "s_mov_b64 exec, %0"
       : "=&s"(saved)
       : "v"(ptr), "v"(v)

@@ -34,6 +34,7 @@ def run_attention(w, rank, causal, mode, C=1, epochs=1, scale=None, k_std=None, 
     flags = torch.zeros(info["n_flags"], dtype=torch.int32, device=dev())
     wsp = torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev())
     comm = torch.cuda.Stream()
+    torch.cuda.synchronize()   # the zero fills above ran on the default stream; the communication stream does not order after it
     for epoch in range(1, epochs + 1):
         if epoch > 1:   # new keys and values every call: a stale flag would let old data through
             for r_ in range(R):
@@ -137,6 +138,7 @@ def test_drained_queue_times_out():
     wsp = torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev())
     wsp[1] = 1 << 20
     wsp[2] = 1 << 20
+    torch.cuda.synchronize()
     tl.tl_sp_ag_attention(ctx, q, ks, vs, kg, vg, o, S, Hd, D, True, 1.0 / math.sqrt(D), flags, 1, wsp, info["ws_bytes"],
                           torch.cuda.current_stream(), torch.cuda.Stream())
     torch.cuda.synchronize()

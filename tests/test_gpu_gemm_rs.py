@@ -28,6 +28,7 @@ def run_gemm_rs(w, mode, epochs=1, **cfg):
     flags = torch.zeros(n_flags, dtype=torch.int32, device=dev())
     wsp = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=dev())
     comm = torch.cuda.Stream()
+    torch.cuda.synchronize()   # the zero fills above ran on the default stream; the communication stream does not order after it
     host_a = w["a"]
     for epoch in range(1, epochs + 1):
         if epoch > 1:

@@ -71,6 +71,7 @@ def run_part1(w, rank, C, mode, epochs=1, **cfg):
     flags = torch.zeros(q["n_flags"], dtype=torch.int32, device=dev())
     wsp = torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev())
     comm = torch.cuda.Stream()
+    torch.cuda.synchronize()   # the zero fills above ran on the default stream; the communication stream does not order after it
     host_shards = [s.copy() for s in w["x_shards"]]
     for epoch in range(1, epochs + 1):
         if epoch > 1:
@@ -121,6 +122,7 @@ def run_part2(w, mode, epochs=1, **cfg):
     flags = torch.zeros(q["n_flags"], dtype=torch.int32, device=dev())
     wsp = torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev())
     comm = torch.cuda.Stream()
+    torch.cuda.synchronize()   # the zero fills above ran on the default stream; the communication stream does not order after it
     host_x2 = w["x2"]
     for epoch in range(1, epochs + 1):
         if epoch > 1:
