@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream"])
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
+    ap.add_argument("--ag-tile", default="", help="compute tile of AG+GEMM as MxN (default: the library's choice)")
+    ap.add_argument("--rs-tile", default="", help="compute tile of GEMM+RS as MxN (default: the library's choice)")
     ap.add_argument("--no-direct-push", action="store_true",
                     help="GEMM+RS: store every partial row locally and let the communication side copy the other ranks' rows "
                          "(default: the GEMM epilogue stores them straight into the peers' landing zones)")
@@ -215,7 +217,9 @@ def main():
 
     class Op:
         def __init__(self, op, dims, comm_mode, comm_alone=0):
-            self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode,
+            tile = (args.ag_tile if op == tl.TL_OP_AG_GEMM else args.rs_tile) or "0x0"
+            tm, tn = (int(v) for v in tile.split("x"))
+            self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
                                         comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
                                         spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else 1)
             self.op, self.dims = op, dims

@@ -164,12 +164,14 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   } else if ((long)M * N <= 1024L * 1024L) {
     v = TILE_128x128;
   } else {
-    // 256x256 unless the 224-wide tile divides N and fills the last round of workgroups better
+    // 256x256 unless the 224-wide tile divides N and fills the last round of workgroups much better: its wave tile
+    // (32x224) reads more LDS bytes per flop and the kernel takes all 256 vector registers, which keeps side-kernel
+    // waves off its compute units; measured on 8192x3584x8192, 448 tiles of 256x256 (1.75 rounds) beat 512 of 256x224
     auto fill = [&](int tm, int tn) {
       long tiles = (long)ceil_div(M, tm) * ceil_div(N, tn), G = ctx->num_cus;
       return (double)((long)M * N) / ((double)((tiles + G - 1) / G * G) * tm * tn);
     };
-    v = (N % 224 == 0 && fill(256, 224) > fill(256, 256) + 1e-9) ? TILE_256x224 : TILE_256x256;
+    v = (N % 224 == 0 && fill(256, 224) > 1.25 * fill(256, 256)) ? TILE_256x224 : TILE_256x256;
   }
   r->variant = v;
   r->tile_m = kTileM[v];

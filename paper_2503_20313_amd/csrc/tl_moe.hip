@@ -349,7 +349,7 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
       long tiles = ((long)T * topk / 256 + E / 2) * ceil_div(N, tn), G = ctx->num_cus;
       return (double)tiles * tn / (double)((tiles + G - 1) / G * G);
     };
-    v = (N % 224 == 0 && (N % 256 != 0 || fill(224) > fill(256) + 1e-9)) ? TILE_256x224 : TILE_256x256;
+    v = (N % 224 == 0 && (N % 256 != 0 || fill(224) > 1.25 * fill(256))) ? TILE_256x224 : TILE_256x256;
   }
   r->variant = v;
   r->tile_m = kTileM[v];
@@ -357,7 +357,10 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
   r->nbn = ceil_div(N, r->tile_n);
   r->max_row_tiles = ceil_div(T * topk, r->tile_m) + E;
   r->G = c.compute_workgroups > 0 ? c.compute_workgroups : ctx->num_cus;
-  r->n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : 128);
+  // side kernels: one 256-thread workgroup fits on a compute unit beside a resident GEMM workgroup, and the reduce
+  // stages of part 2 are bound by the bytes they keep in flight, so part 2 asks for one per compute unit
+  r->n_comm = c.comm_workgroups > 0 ? c.comm_workgroups
+                                    : (c.comm_mode == TL_COMM_WAVES ? 16 : (op == TL_OP_MOE_GEMM_SCATTER_RS ? 256 : 128));
   if (c.comm_mode == TL_COMM_NONE) r->n_comm = 0;
   r->rows_per_rank = T / R;
   r->rows_per_channel = r->rows_per_rank / c.channels_per_rank;
@@ -530,7 +533,11 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
     return launch_moe<MoeP2Params>(r.variant, moe_gemm_scatter_kernel<Cfg256x256>, moe_gemm_scatter_kernel<Cfg256x224>,
                                    moe_gemm_scatter_kernel<Cfg128x128>, p, grid, cs);
   };
-  const int n_topk = (r.n_comm + 1) / 2, n_rs = r.n_comm - n_topk > 0 ? r.n_comm - n_topk : 1;
+  // split of the communication workgroups between stage B (top-k reduce) and stage C (ReduceScatter): even, except that
+  // with direct push stage C only reduces the own segment (1/R of the tiles) and forwards notifications
+  int n_rs = cfg.rs_direct_push && r.n_comm >= 16 ? r.n_comm / 8 : r.n_comm / 2;
+  if (n_rs < 1) n_rs = 1;
+  const int n_topk = r.n_comm - n_rs > 0 ? r.n_comm - n_rs : 1;
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
       if (alone) return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: comm_alone needs a comm_mode with a reduce side");
