@@ -140,7 +140,8 @@ struct Sched {
   int group_m;      // >= 1
 };
 
-__host__ __device__ inline int sched_tile(const Sched& s, int p) {
+// Die swizzle alone: the logical index of schedule position p.
+__host__ __device__ inline int sched_logical(const Sched& s, int p) {
   int l = p;
   if (s.swizzle && s.G % kXcds == 0) {
     int rnd = p / s.G, w = p - rnd * s.G;
@@ -148,6 +149,24 @@ __host__ __device__ inline int sched_tile(const Sched& s, int p) {
     if (span > s.G) span = s.G;
     if (span % kXcds == 0) l = rnd * s.G + (w % kXcds) * (span / kXcds) + w / kXcds;
   }
+  return l;
+}
+
+// The other walk, for stages whose consumer needs a column block of EVERY row block before it can start (MoE part 2):
+// groups of gb column blocks slowest, inside a group the row block next and the column block fastest.  gb = 1 finishes
+// one column block of all rows at a time, but then all workgroups of the chip touch the same 512-byte slice of every
+// row at once, and with a power-of-two row pitch those slices sit on a handful of memory channels; a few column
+// blocks side by side spread the traffic while the consumer still gets complete columns early.
+__host__ __device__ inline void colgroup_tile(int l, int nbm, int nbn, int gb, int* bm, int* bn) {
+  int g = l / (nbm * gb), within = l - g * (nbm * gb);
+  int gsz = nbn - g * gb;  // the last group may be narrower
+  if (gsz > gb) gsz = gb;
+  *bm = within / gsz;
+  *bn = g * gb + (within - *bm * gsz);
+}
+
+__host__ __device__ inline int sched_tile(const Sched& s, int p) {
+  int l = sched_logical(s, p);
   int per_group = s.group_m * s.nbn;
   int g = l / per_group, within = l - g * per_group;
   int gsz = s.nbm - g * s.group_m;  // row blocks in this group (the last group may be short)
