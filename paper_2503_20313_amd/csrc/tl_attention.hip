@@ -47,6 +47,7 @@ __global__ void __launch_bounds__(kAttnThreads) sp_attention_kernel(const AttnPa
     return;
   }
   if (!p.do_compute) return;
+  __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   // workgroup -> (head, query block): the query blocks of a head run on one die (workgroup w runs on die w % 8) so
   // that they share the head's K/V in that die's L2; heavy (late, for causal) query blocks first
   const int wid = blockIdx.x - p.n_comm;

@@ -40,6 +40,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
     return;
   }
   if (!p.do_compute) return;
+  __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   const int M_per_channel = p.prod.rows_per_channel;
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
@@ -85,6 +86,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
     return;
   }
   if (!p.do_compute) return;
+  __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   const RsSide& rs = p.rs;
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {

@@ -40,6 +40,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef TL_ACQ_SCOPE
 #define TL_ACQ_SCOPE "workgroup"
 #endif
+#ifndef TL_COMPUTE_WAVE_PRIO
+#define TL_COMPUTE_WAVE_PRIO 2
+#endif
 constexpr int kMaxWorld = 16;
 constexpr int kXcds = 8;  // workgroup w of a launch runs on die w % 8
 

@@ -159,6 +159,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     return;
   }
   if (!p.do_compute) return;
+  __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   Sched sc;
   sc.nbm = *p.n_row_tiles;
@@ -261,6 +262,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
     return;
   }
   if (!p.do_compute) return;
+  __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_topk - p.n_rs;
   Sched sc;
   sc.nbm = *p.n_row_tiles;
