@@ -13,7 +13,7 @@
 //    (ds_read_b64_tr_b16: a 16-lane block reads 4 k-rows x 16 columns and hands each lane the
 //    4 k-values of its column), the MFMA "B" operand from the A tile with 16-byte reads; the
 //    product is therefore the transposed tile C^T, whose accumulator layout gives every lane
-//    4 consecutive columns of one row of C, i.e. 8-byte stores.
+//    4 consecutive columns of one row of C; the epilogue passes them through LDS to store whole lines.
 //  * v_mfma_f32_32x32x16_bf16, wave tile (BM/WM) x (BN/WN).
 #pragma once
 #include <type_traits>
@@ -44,7 +44,11 @@ struct TileCfg {
   static constexpr int B_LOADS = BK * B_CPR / 64;
   static constexpr bool B_SWZ = (B_CPR % 16) == 0;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+  // Epilogue staging: every wave passes its WTM x WTN result through an LDS region of its own, rows padded by 16 bytes.
+  static constexpr int EP_PITCH = WTN * 2 + 16;
+  static constexpr int EP_BYTES = NWAVES * WTM * EP_PITCH;
+  static constexpr int LDS_BYTES = NS * STAGE_BYTES > EP_BYTES ? NS * STAGE_BYTES : EP_BYTES;
+  static_assert((WTM * (WTN / 8)) % 64 == 0, "the epilogue hands out 16-byte chunks of the wave tile 64 at a time");
   static constexpr int A_PER_WAVE = (A_LOADS + NWAVES - 1) / NWAVES;
   static constexpr int B_PER_WAVE = (B_LOADS + NWAVES - 1) / NWAVES;
   // Direct-to-LDS loads per stage issued by every wave.  Every wave issues the same number (the vmcnt
@@ -83,7 +87,7 @@ struct DenseRows {
 // row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
 // column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED).
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
-// masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS reads complete.
+// masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
 template <class Cfg, class Out>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
@@ -255,32 +259,43 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     slot = nslot;
   }
   slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, smem, 0, false, 0);
-  __syncthreads();  // all LDS reads of this tile are complete before the next tile's loads
+  __syncthreads();  // all operand reads of this tile are complete: LDS is free for the epilogue
 
-  // ---- epilogue: accumulator register e of lane l holds C[row = l%32][col = (e/4)*8 + (l/32)*4 + e%4]
-  const int c_row = wm * Cfg::WTM + (lane & 31);
-  const int c_col = wn * Cfg::WTN + (lane >> 5) * 4;
+  // ---- epilogue.  Accumulator register e of lane l holds C[row = l%32][col = (e/4)*8 + (l/32)*4 + e%4] of its 32x32
+  // block: stored from there, every store instruction would touch 32 rows with 16 bytes each.  Instead the wave
+  // rounds its result to bf16 into an LDS region of its own and reads it back row-wise, so that a store instruction
+  // writes whole 128-byte lines (16 bytes per lane, 8 lanes per row of a 64-wide wave tile).
+  char* ep = smem + wave * (Cfg::WTM * Cfg::EP_PITCH);
 #pragma unroll
   for (int mt = 0; mt < Cfg::MT; mt++) {
-    int row = c_row + mt * 32;
-    if (row < rows) {
-      float scale = 1.f;
-      bf16_t* crow = out.row(row, scale);
+    const int row = mt * 32 + (lane & 31);
+    float scale = 1.f;
+    if (Out::SCALED && wm * Cfg::WTM + row < rows) out.row(wm * Cfg::WTM + row, scale);
 #pragma unroll
-      for (int nt = 0; nt < Cfg::NT; nt++) {
+    for (int nt = 0; nt < Cfg::NT; nt++) {
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          int col = c_col + nt * 32 + g * 8;
-          if (col < cols) {  // cols % 8 == 0 and col % 4 == 0: a 4-wide group is all in or all out
-            bf16x4 o;
+      for (int g = 0; g < 4; g++) {
+        bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; e++) o[e] = (bf16_t)(Out::SCALED ? acc[mt][nt][g * 4 + e] * scale : acc[mt][nt][g * 4 + e]);
-            *(bf16x4*)(crow + col) = o;
-          }
-        }
+        for (int e = 0; e < 4; e++) o[e] = (bf16_t)(Out::SCALED ? acc[mt][nt][g * 4 + e] * scale : acc[mt][nt][g * 4 + e]);
+        *(bf16x4*)(ep + row * Cfg::EP_PITCH + (nt * 32 + g * 8 + (lane >> 5) * 4) * 2) = o;
       }
     }
   }
+  constexpr int EP_CPR = Cfg::WTN / 8;                  // 16-byte chunks per row of the wave tile
+  constexpr int EP_ITERS = Cfg::WTM * EP_CPR / 64;
+#pragma unroll 4
+  for (int i = 0; i < EP_ITERS; i++) {
+    const int idx = i * 64 + lane;
+    const int row = idx / EP_CPR, q = idx - row * EP_CPR;
+    const int grow = wm * Cfg::WTM + row, col = wn * Cfg::WTN + q * 8;
+    if (grow < rows && col < cols) {  // cols % 8 == 0: a chunk is all in or all out
+      float unused;
+      bf16_t* crow = out.row(grow, unused);
+      *(u32x4*)(crow + col) = *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16);
+    }
+  }
+  __syncthreads();  // the next tile's loads overwrite the staging regions
 }
 
 }  // namespace tl
