@@ -9,6 +9,13 @@ from __future__ import annotations
 import ctypes
 import os
 
+try:
+    # The library must use the same HIP runtime instance as the owner of the device buffers it is given.  PyTorch ships
+    # its own copy of the runtime: loading torch first makes the dynamic loader resolve this library against that copy.
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
 
