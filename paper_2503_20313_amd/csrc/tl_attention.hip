@@ -162,10 +162,8 @@ __global__ void __launch_bounds__(kAttnThreads) sp_attention_kernel(const AttnPa
     }
     // scale, mask, online softmax.  Accumulator e of key tile t is key kv0 + t*32 + (e/4)*8 + h*4 + e%4.
     const bool need_mask = (p.causal && kv0 + kBKV - 1 > g0 + qw0) || kv0 + kBKV > p.S;
-#pragma unroll
-    for (int t = 0; t < 2; t++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) sacc[t][e] *= p.scale_log2e;
+    // the softmax scale (times log2 e) is folded into the exponent: p = exp2(s*c - m*c) is one fused multiply-add and
+    // one exp2 per score; the running maximum m is kept in units of the raw scores (c > 0)
     if (need_mask) {
 #pragma unroll
       for (int t = 0; t < 2; t++)
@@ -182,15 +180,16 @@ __global__ void __launch_bounds__(kAttnThreads) sp_attention_kernel(const AttnPa
       for (int e = 0; e < 16; e++) mloc = fmaxf(mloc, sacc[t][e]);
     mloc = fmaxf(mloc, xor32(mloc));
     const float m_new = fmaxf(m_run, mloc);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
     m_run = m_new;
+    const float mc = -m_new * p.scale_log2e;
     float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
     for (int t = 0; t < 2; t++)
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        float pv = __builtin_amdgcn_exp2f(sacc[t][e] - m_new);
+        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][e], p.scale_log2e, mc));
         psum += pv;
         pf[t * 2 + (e >> 3)][e & 7] = (bf16_t)pv;
       }
