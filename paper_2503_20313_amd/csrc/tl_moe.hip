@@ -50,87 +50,125 @@ __global__ void moe_topk_kernel(const float* __restrict__ logits, int T, int E, 
 }
 
 // ======================================================================================
-// Routing, step 2 (one workgroup): stable counting sort of the routed rows by expert, expert offsets,
-// and the tile tables.  Thread i owns a contiguous run of rows, so "rows of expert e owned by lower
-// threads" (an exclusive scan over threads) plus the rank inside the own run gives the stable position.
+// Routing, step 2 (one workgroup of 16 waves): stable counting sort of the routed rows by expert, expert
+// offsets, and the tile tables.  Wave w owns a contiguous range of rows and walks it 64 rows at a time; inside
+// a step the lanes that route to the same expert are found with one ballot per bit of the expert index, which
+// gives every row its rank among them.  Pass A counts rows per (wave, expert); a scan turns the counts into the
+// position where each wave's rows of each expert start; pass B places the rows (stable: waves, steps and lanes
+// are in row order) and ORs each row's AllGather channel into its tile's mask.
 // ======================================================================================
-__device__ __forceinline__ int block_exclusive_scan(int v, int tid, int* s_wave, int* total) {
-  // inclusive scan inside the wave
-  int lane = tid & 63, wave = tid >> 6;
-  int x = v;
+constexpr int kRouteWaves = kRouteThreads / 64;
+constexpr int kLdsTiles = 2048;  // tile tables are assembled in LDS up to this many tiles, else in global memory
+
+__device__ __forceinline__ unsigned long long same_expert_lanes(int e, bool valid) {
+  unsigned long long same = __builtin_amdgcn_ballot_w64(valid);
 #pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int y = __shfl_up(x, d, 64);
-    if (lane >= d) x += y;
+  for (int b = 0; b < 6; b++) {  // kMaxExperts = 64
+    unsigned long long bal = __builtin_amdgcn_ballot_w64(valid && ((e >> b) & 1));
+    same &= ((e >> b) & 1) ? bal : ~bal;
   }
-  if (lane == 63) s_wave[wave] = x;
-  __syncthreads();
-  int base = 0, tot = 0;
-  for (int i = 0; i < kRouteThreads / 64; i++) {
-    int c = s_wave[i];
-    if (i < wave) base += c;
-    tot += c;
-  }
-  __syncthreads();
-  *total = tot;
-  return base + x - v;
+  return same;
 }
 
 __global__ void __launch_bounds__(kRouteThreads) moe_sort_kernel(const int* __restrict__ topk_ids, int n_rows, int E, int topk, int T, int R, int C,
                                                                  int Tm, int* __restrict__ expert_offsets, int* __restrict__ sorted_row,
                                                                  int* __restrict__ tile_tables, int* __restrict__ n_tiles) {
-  __shared__ int s_wave[kRouteThreads / 64];
+  __shared__ int s_cnt[kRouteWaves][kMaxExperts];
   __shared__ int s_off[kMaxExperts + 1], s_tbase[kMaxExperts + 1];
-  const int tid = threadIdx.x;
-  const int per = (n_rows + kRouteThreads - 1) / kRouteThreads;
-  const int lo = min(tid * per, n_rows), hi = min(lo + per, n_rows);
-  int offset = 0;
-  for (int e = 0; e < E; e++) {
-    int c = 0;
-    for (int r = lo; r < hi; r++) c += (topk_ids[r] == e);
-    int total;
-    int before = block_exclusive_scan(c, tid, s_wave, &total);
-    int pos = offset + before;
-    for (int r = lo; r < hi; r++)
-      if (topk_ids[r] == e) sorted_row[pos++] = r;
-    if (tid == 0) s_off[e] = offset;
-    offset += total;
+  __shared__ unsigned s_mlo[kLdsTiles], s_mhi[kLdsTiles];
+  __shared__ int s_rmin[kLdsTiles], s_rmax[kLdsTiles];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = ((n_rows + kRouteWaves - 1) / kRouteWaves + 63) / 64 * 64;
+  const int lo = min(wave * chunk, n_rows), hi = min(lo + chunk, n_rows);
+  const unsigned long long below = (1ull << lane) - 1;
+  for (int i = tid; i < kRouteWaves * kMaxExperts; i += kRouteThreads) (&s_cnt[0][0])[i] = 0;
+  __syncthreads();
+  // ---- pass A: rows per (wave, expert)
+  for (int base = lo; base < hi; base += 64) {
+    const int r = base + lane;
+    const bool valid = r < hi;
+    const int e = valid ? topk_ids[r] : 0;
+    const unsigned long long same = same_expert_lanes(e, valid);
+    if (valid && (same & below) == 0) s_cnt[wave][e] += __builtin_popcountll(same);  // the group's first lane
   }
+  __syncthreads();
+  // ---- offsets, tile bases, start position of every (wave, expert)
+  if (tid < E) {
+    int tot = 0;
+    for (int w = 0; w < kRouteWaves; w++) tot += s_cnt[w][tid];
+    s_off[tid + 1] = tot;
+  }
+  __syncthreads();
   if (tid == 0) {
-    s_off[E] = offset;
-    int tb = 0;
+    int run = 0, tb = 0;
     for (int e = 0; e < E; e++) {
+      int c = s_off[e + 1];
+      s_off[e] = run;
       s_tbase[e] = tb;
-      tb += (s_off[e + 1] - s_off[e] + Tm - 1) / Tm;
+      run += c;
+      tb += (c + Tm - 1) / Tm;
     }
+    s_off[E] = run;
     s_tbase[E] = tb;
     *n_tiles = tb;
   }
-  __threadfence();
   __syncthreads();
-  for (int e = tid; e <= E; e += kRouteThreads) expert_offsets[e] = s_off[e];
+  if (tid < E) {
+    int run = s_off[tid];
+    for (int w = 0; w < kRouteWaves; w++) {
+      int c = s_cnt[w][tid];
+      s_cnt[w][tid] = run;
+      run += c;
+    }
+  }
   const int nt = s_tbase[E];
-  const int tokens_per_rank = T / R, tokens_per_channel = tokens_per_rank / C;
+  const bool in_lds = nt <= kLdsTiles;
+  // ---- tile records: range and expert now, masks and rank span start empty
   for (int tau = tid; tau < nt; tau += kRouteThreads) {
     int e = 0;
     while (s_tbase[e + 1] <= tau) e++;
     int f_lo = s_off[e] + (tau - s_tbase[e]) * Tm;
-    int f_hi = min(f_lo + Tm, s_off[e + 1]);
-    unsigned long long mask = 0;
-    int rmin = R, rmax = -1;
-    for (int s = f_lo; s < f_hi; s++) {
-      // written by other threads of this workgroup a moment ago: read past the vector cache
-      int token = __hip_atomic_load(sorted_row + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) / topk;
-      mask |= 1ull << (token / tokens_per_channel);
-      int q = token / tokens_per_rank;
-      rmin = min(rmin, q);
-      rmax = max(rmax, q);
-    }
     int* rec = tile_tables + (long)tau * 8;
-    rec[0] = f_lo; rec[1] = f_hi; rec[2] = e;
-    rec[3] = (int)(unsigned)(mask & 0xffffffffull); rec[4] = (int)(unsigned)(mask >> 32);
-    rec[5] = rmin; rec[6] = rmax; rec[7] = 0;
+    rec[0] = f_lo; rec[1] = min(f_lo + Tm, s_off[e + 1]); rec[2] = e; rec[7] = 0;
+    if (in_lds) { s_mlo[tau] = 0; s_mhi[tau] = 0; s_rmin[tau] = R; s_rmax[tau] = -1; }
+    else { rec[3] = 0; rec[4] = 0; rec[5] = R; rec[6] = -1; }
   }
+  __threadfence();
+  __syncthreads();
+  // ---- pass B: place the rows, collect each tile's channels and source ranks
+  const int tokens_per_rank = T / R, tokens_per_channel = tokens_per_rank / C;
+  for (int base = lo; base < hi; base += 64) {
+    const int r = base + lane;
+    const bool valid = r < hi;
+    const int e = valid ? topk_ids[r] : 0;
+    const unsigned long long same = same_expert_lanes(e, valid);
+    int start = 0;
+    if (valid) start = s_cnt[wave][e];
+    if (valid && (same & below) == 0) s_cnt[wave][e] = start + __builtin_popcountll(same);
+    if (valid) {
+      const int pos = start + __builtin_popcountll(same & below);
+      sorted_row[pos] = r;
+      const int tau = s_tbase[e] + (pos - s_off[e]) / Tm;
+      const int token = r / topk, ch = token / tokens_per_channel, q = token / tokens_per_rank;
+      if (in_lds) {
+        if (ch < 32) atomicOr(&s_mlo[tau], 1u << ch); else atomicOr(&s_mhi[tau], 1u << (ch - 32));
+        atomicMin(&s_rmin[tau], q);
+        atomicMax(&s_rmax[tau], q);
+      } else {
+        int* rec = tile_tables + (long)tau * 8;
+        if (ch < 32) atomicOr((unsigned*)rec + 3, 1u << ch); else atomicOr((unsigned*)rec + 4, 1u << (ch - 32));
+        atomicMin(rec + 5, q);
+        atomicMax(rec + 6, q);
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e <= E; e += kRouteThreads) expert_offsets[e] = s_off[e];
+  if (in_lds)
+    for (int tau = tid; tau < nt; tau += kRouteThreads) {
+      int* rec = tile_tables + (long)tau * 8;
+      rec[3] = (int)s_mlo[tau]; rec[4] = (int)s_mhi[tau]; rec[5] = s_rmin[tau]; rec[6] = s_rmax[tau];
+    }
 }
 
 // ======================================================================================

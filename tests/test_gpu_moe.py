@@ -44,7 +44,9 @@ def check_routing(w_in, R, C, tile_m, got, renorm=True):
     return ids_ref, w_ref, off_ref, srow_ref
 
 
-@pytest.mark.parametrize("T,E,k,R,C,tile_m,renorm", [(64, 4, 2, 2, 2, 16, True), (256, 8, 3, 4, 1, 128, False), (8192, 32, 2, 8, 4, 256, True), (1000, 5, 5, 5, 2, 128, True)])
+@pytest.mark.parametrize("T,E,k,R,C,tile_m,renorm", [(64, 4, 2, 2, 2, 16, True), (256, 8, 3, 4, 1, 128, False), (8192, 32, 2, 8, 4, 256, True), (1000, 5, 5, 5, 2, 128, True),
+                                                    (8192, 32, 2, 8, 8, 4, True),      # > 2048 tiles: tables assembled in global memory; 64 channels
+                                                    (4096, 64, 8, 4, 2, 64, True)])    # the largest expert count and top-k
 def test_route_tables_bit_exact(T, E, k, R, C, tile_m, renorm):
     logits = wl.normal_f32((T, E), 1.0, 41, 0)
     # plant ties: equal logits inside some rows must go to the lower expert index
