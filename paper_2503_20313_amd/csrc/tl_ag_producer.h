@@ -133,7 +133,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     if (state >= 0) produce_tile<2>(p, state, tid, wave, nthreads);  // shallow: this path shares its registers with the caller's matrix tile
     else __builtin_amdgcn_s_sleep(8);
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);
+  acquire_after_wait(p.ctl);
   __syncthreads();
 }
 

@@ -28,15 +28,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // tenth of the run time of the overlapped kernels.
 //
 // The invalidation guards against one thing only: a line of the awaited data that entered this
-// die's caches before the producer wrote it.  The kernels here exclude that by construction:
+// die's caches before the producer wrote it.  The kernels here exclude that by construction when
 //   * a kernel never reads a byte of flag-guarded data before it has seen the flag of the tile or
-//     channel that byte belongs to (no prefetch across a wait, guarded regions are whole rows
-//     aligned to more than a cache line), and
+//     channel that byte belongs to (no prefetch across a wait),
+//   * no cache line holds bytes of two differently guarded regions (else reading one region would
+//     cache not-yet-written bytes of its neighbour): guarded regions start and end on 128-byte
+//     boundaries.  Whole rows of the gathered matrices always do (their pitch is a multiple of 128
+//     bytes); the column-split tiles of the ReduceScatter side do only for some shapes, so the host
+//     decides per call and sets WaitCtl::strict where the condition fails, and
 //   * lines cached by earlier kernels are dropped by the acquire every kernel dispatch performs.
-// Hence every guarded line a die caches during a kernel was fetched after its producer's release.
-// The default is therefore a workgroup-scope fence: it orders the workgroup's later loads after
-// the flag load for the compiler and the wave, and leaves the caches alone.  Define
-// TL_ACQ_SCOPE="agent" to build with the full device-scope acquire instead.
+// Then every guarded line a die caches during a kernel was fetched after its producer's release,
+// and the fence after a wait only has to order the workgroup's later loads after the flag load for
+// the compiler and the wave (workgroup scope), leaving the caches alone.  With WaitCtl::strict, or
+// when built with TL_ACQ_SCOPE="agent", the full device-scope acquire is taken instead.
 #ifndef TL_ACQ_SCOPE
 #define TL_ACQ_SCOPE "workgroup"
 #endif
@@ -56,7 +60,13 @@ constexpr int kXcds = 8;  // workgroup w of a launch runs on die w % 8
 struct WaitCtl {
   int* status;                 // status word: 0 = ok, else 1 + index of the flag whose wait expired
   unsigned long long timeout;  // in ticks of the 100 MHz wall clock; 0 = unbounded
+  int strict;                  // 1: device-scope acquire after every wait (guarded regions share cache lines)
 };
+
+__device__ __forceinline__ void acquire_after_wait(const WaitCtl& ctl) {
+  if (ctl.strict) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);
+}
 
 __device__ __forceinline__ void tile_notify(unsigned* flag, unsigned inc = 1u) {
   __hip_atomic_fetch_add(flag, inc, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -81,7 +91,7 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
       }
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, TL_ACQ_SCOPE);
+  acquire_after_wait(ctl);
   return ok;
 }
 

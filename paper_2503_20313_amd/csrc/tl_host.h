@@ -57,10 +57,13 @@ typedef TileCfg<128, 128, 2, 2, 32, 4> Cfg128x128;
 static const int kThreads[TILE_VARIANTS] = {Cfg256x256::NTHREADS, Cfg256x224::NTHREADS, Cfg128x128::NTHREADS};
 static const int kLds[TILE_VARIANTS] = {Cfg256x256::LDS_BYTES, Cfg256x224::LDS_BYTES, Cfg128x128::LDS_BYTES};
 
+inline bool aligned128(const void* p) { return ((uintptr_t)p & 127) == 0; }
+
 inline WaitCtl make_ctl(const tl_ctx* ctx, void* workspace) {
   WaitCtl c;
   c.status = (int*)workspace;
   c.timeout = (unsigned long long)ctx->cfg.spin_timeout_us * 100ull;  // 100 MHz wall clock
+  c.strict = 0;
   return c;
 }
 
@@ -93,6 +96,8 @@ inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const
   p->ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
   p->ticket_end = epoch * (unsigned)(n_ptm * n_ptn);
   p->ctl = make_ctl(ctx, workspace);
+  // a channel is a block of whole rows: its edges fall on 128-byte lines if the pitch and the base do
+  p->ctl.strict = (ld % 64 == 0 && aligned128(gathered)) ? 0 : 1;
 }
 
 // Fills the ReduceScatter side of a call.  Flags: ready[ncm*ncn] | arrived[R*tiles_per_seg] | pushed[R*tiles_per_seg].
@@ -119,6 +124,11 @@ inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void
   p->arrived = flags + (size_t)p->ncm * p->ncn;
   p->pushed = p->arrived + (size_t)R * p->tiles_per_seg;
   p->ctl = make_ctl(ctx, workspace);
+  // reduce tiles whose edges do not fall on 128-byte lines share cache lines with their neighbours
+  bool aligned = N % 64 == 0 && Tn_r % 64 == 0 && aligned128(partial);
+  for (int q = 0; q < R; q++)
+    if (q != cfg.rank && !aligned128(peer_recv[q])) aligned = false;
+  p->ctl.strict = aligned ? 0 : 1;
 }
 
 int launch_peers_arrive(const RsSide& rs, hipStream_t s);

@@ -573,6 +573,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
     int first = cfg.tile_order == TL_ORDER_OWN_FIRST ? cfg.rank : (cfg.rank + 1) % R;
     p.rs.rs_first_block = first * (T / R / r.Tt);
   }
+  if (!aligned128(scatter_buf)) p.rs.ctl.strict = 1;  // stage B's guarded regions are column blocks of the scatter buffer
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
   const bool alone = cfg.comm_alone != 0;
   p.do_compute = alone ? 0 : 1;
