@@ -158,6 +158,7 @@ def main():
     ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream"])
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
+    ap.add_argument("--ag-comm-tile-m", type=int, default=0, help="rows of an AllGather producer tile (default: the library's choice)")
     ap.add_argument("--ag-tile", default="", help="compute tile of AG+GEMM as MxN (default: the library's choice)")
     ap.add_argument("--rs-tile", default="", help="compute tile of GEMM+RS as MxN (default: the library's choice)")
     ap.add_argument("--no-direct-push", action="store_true",
@@ -223,6 +224,7 @@ def main():
             tile = (args.ag_tile if op == tl.TL_OP_AG_GEMM else args.rs_tile) or "0x0"
             tm, tn = (int(v) for v in tile.split("x"))
             self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
+                                        comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
                                         comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
                                         spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else 1)
             self.op, self.dims = op, dims
