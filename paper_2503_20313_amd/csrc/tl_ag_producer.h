@@ -84,6 +84,9 @@ __device__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_t
 
 // consumer_tile_wait for the channels set in chan_mask (bit = global channel index) by a whole workgroup: while a channel is short of its target
 // the workgroup works off producer tickets; with the queue empty it sleeps and polls (bounded by ctl.timeout).
+// DEPTH = loads in flight per lane when this workgroup copies a producer tile itself: deep where the caller's registers allow
+// (a ticket then takes a quarter of the time), shallow where they are full.
+template <int DEPTH = 2>
 __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, unsigned long long chan_mask, int tid, int nthreads, int* s_ticket) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned long long t0 = 0;
@@ -130,7 +133,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     int state = __builtin_amdgcn_readfirstlane(*s_ticket);
     __syncthreads();
     if (state == -2) break;
-    if (state >= 0) produce_tile<2>(p, state, tid, wave, nthreads);  // shallow: this path shares its registers with the caller's matrix tile
+    if (state >= 0) produce_tile<DEPTH>(p, state, tid, wave, nthreads);
     else __builtin_amdgcn_s_sleep(8);
   }
   acquire_after_wait(p.ctl);

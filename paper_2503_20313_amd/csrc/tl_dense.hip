@@ -52,7 +52,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
     const int clo = row_lo / M_per_channel, chi = (row_lo + rows - 1) / M_per_channel;
     if (p.do_wait == 1) {
       unsigned long long mask = ((chi - clo + 1 >= 64) ? ~0ull : ((1ull << (chi - clo + 1)) - 1)) << clo;
-      consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
+      consumer_wait_or_produce<8>(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
     } else if (p.do_wait == 2) {
       // flags raised by somebody else (no ticket queue): plain wait
       if (tid == 0)
@@ -334,6 +334,20 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t*
       size_t tiles_per_seg = (size_t)(r.rows_per_rank / r.Tm_p) * r.n_ptn;
       *n_flags = (size_t)r.n_ptm * r.n_ptn + 2 * (size_t)ctx->cfg.world_size * tiles_per_seg;
     }
+    return TL_OK;
+  }
+  if (op == TL_OP_MOE_AG_GATHER_GEMM || op == TL_OP_MOE_GEMM_SCATTER_RS) {
+    int info[8];
+    if (int e = tl_moe_query(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], (int)dims[3], (int)dims[4], info)) return e;
+    *n_flags = (size_t)info[3];
+    *ws_bytes = (size_t)info[4];
+    return TL_OK;
+  }
+  if (op == TL_OP_SP_AG_ATTENTION) {
+    int info[8];
+    if (int e = tl_attn_query(ctx, (int)dims[0], (int)dims[1], (int)dims[2], 1, info)) return e;
+    *n_flags = (size_t)info[2];
+    *ws_bytes = (size_t)info[3];
     return TL_OK;
   }
   return fail(TL_ERR_INVALID_ARG, "unknown operator %d", op);

@@ -73,3 +73,17 @@ def test_moe_one_expert_top1_is_the_dense_operator():
     _, _, _, out_moe = ops.moe_gemm_scatter_rs(w["x2"], w["w2"], srow, off, tw, w["peer_segments"], rank)
     _, _, out_dense = ops.gemm_rs(w["x2"], w["w2"][0], w["peer_segments"], rank)
     assert np.array_equal(out_moe, out_dense)
+
+
+def test_query_workspace_covers_every_operator():
+    """tl_query_workspace agrees with the operator-specific queries for the MoE halves and attention."""
+    from tests.gpu_util import make_ctx
+    ctx = make_ctx(world_size=8, rank=3, channels_per_rank=2, comm_mode=tl.TL_COMM_SIDE_KERNEL)
+    for op in (tl.TL_OP_MOE_AG_GATHER_GEMM, tl.TL_OP_MOE_GEMM_SCATTER_RS):
+        q = tl.tl_moe_query(ctx, op, 8192, 4096, 1792, 32, 2)
+        assert tl.tl_query_workspace(ctx, op, [8192, 4096, 1792, 32, 2]) == (q["ws_bytes"], q["n_flags"])
+    a = tl.tl_attn_query(ctx, 32768, 32, 128, True)
+    assert tl.tl_query_workspace(ctx, tl.TL_OP_SP_AG_ATTENTION, [32768, 32, 128]) == (a["ws_bytes"], a["n_flags"])
+    with pytest.raises(tl.TileLinkError):
+        tl.tl_query_workspace(ctx, 17, [1, 2, 3])
+    tl.tl_ctx_destroy(ctx)
