@@ -89,7 +89,10 @@ typedef struct tl_config {
                               other ranks' segments straight into peer_push[] (tile_push_data from the producer's
                               epilogue) and only the rows of the own segment into `partial`; the communication side then
                               just forwards the notification for those tiles instead of copying them.  The flags keep
-                              their meaning; the rows of `partial` outside the own segment are not written. */
+                              their meaning; the rows of `partial` outside the own segment are not written.
+                              2 (tl_gemm_rs only; 1 elsewhere) = in addition the GEMM epilogue reduces the rows of the own
+                              segment itself: it waits for the peers' contributions (peer_tile_wait) before such a tile and
+                              writes `out` together with the own rows of `partial`; same arithmetic, same bits as 1. */
 } tl_config;
 
 typedef struct tl_ctx tl_ctx;

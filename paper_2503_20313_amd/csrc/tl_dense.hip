@@ -94,6 +94,21 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
     int row_lo = bm * Cfg::BM, col_lo = bn * Cfg::BN;
     int rows = min(Cfg::BM, rs.M - row_lo), cols = min(Cfg::BN, rs.N - col_lo);
+    if (rs.direct == 2 && p.do_notify && row_lo < (rs.rank + 1) * rs.seg_rows && row_lo + rows > rs.rank * rs.seg_rows) {
+      // the tile holds rows of the own segment, which its epilogue reduces: peer_tile_wait for every peer's
+      // contribution to the reduce tiles of the own segment it covers
+      if (tid == 0) {
+        const int own_lo = max(row_lo, rs.rank * rs.seg_rows), own_hi = min(row_lo + rows, (rs.rank + 1) * rs.seg_rows);
+        const int cm_per_seg = rs.seg_rows / rs.Tm_r;
+        for (int cm = own_lo / rs.Tm_r; cm <= (own_hi - 1) / rs.Tm_r; cm++)
+          for (int cn = col_lo / rs.Tn_r; cn <= (col_lo + cols - 1) / rs.Tn_r; cn++) {
+            const int local = (cm - rs.rank * cm_per_seg) * rs.ncn + cn;
+            for (int q = 0; q < rs.R; q++)
+              if (q != rs.rank) tile_wait(rs.arrived + q * rs.tiles_per_seg + local, rs.epoch, rs.ctl, rs.ncm * rs.ncn + q * rs.tiles_per_seg + local);
+          }
+      }
+      __syncthreads();
+    }
     gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRows{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
     if (p.do_notify) {
       // producer_tile_notify: one release-add per reduce tile this GEMM tile overlaps
@@ -464,6 +479,7 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
     case TL_COMM_NONE:
       if (alone) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: comm_alone needs a comm_mode with a reduce side");
       p.n_comm = 0; p.do_notify = 0; p.rs.do_wait = 0;
+      if (p.rs.direct == 2) p.rs.direct = 1;  // no reduce side at all in this mode
       return launch_gemm_rs(r.variant, p, r.G, cs);
     case TL_COMM_WAVES:
       if (int e = peers_arrive(alone ? cs : ms)) return e;
@@ -476,9 +492,13 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
       // The GEMM kernel is enqueued before the reduce kernel that waits on it: should both streams share a
       // hardware queue, the reduce kernel then simply runs after the GEMM instead of blocking it.
       p.n_comm = 0; p.do_notify = alone ? 0 : 1; p.rs.do_wait = alone ? 0 : 1;
+      // ... and with the own segment reduced in the GEMM's epilogue the GEMM itself waits for the peers' arrival
+      if (p.rs.direct == 2)
+        if (int e = peers_arrive(ms)) return e;
       if (!alone)
         if (int e = launch_gemm_rs(r.variant, p, r.G, cs)) return e;
-      if (int e = peers_arrive(ms)) return e;
+      if (p.rs.direct != 2)
+        if (int e = peers_arrive(ms)) return e;
       hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.rs);
       TL_HIP(hipGetLastError());
       return TL_OK;

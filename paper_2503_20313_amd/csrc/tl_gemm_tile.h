@@ -80,12 +80,15 @@ struct DenseRows {
   bf16_t* c;
   long ldc;
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
+  // 8 consecutive bf16 of tile row r starting at tile column col (col % 8 == 0)
+  __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(c + (long)r * ldc + col) = v; }
 };
 
 // Computes one output tile.  `a` points at column 0 of the A rows: tile row r is A row r, or A row
 // a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index); `b` points at
 // row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
-// column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED).
+// column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED);
+// `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
 // masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
 template <class Cfg, class Out>
@@ -290,9 +293,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     const int row = idx / EP_CPR, q = idx - row * EP_CPR;
     const int grow = wm * Cfg::WTM + row, col = wn * Cfg::WTN + q * 8;
     if (grow < rows && col < cols) {  // cols % 8 == 0: a chunk is all in or all out
-      float unused;
-      bf16_t* crow = out.row(grow, unused);
-      *(u32x4*)(crow + col) = *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16);
+      out.store(grow, col, *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16));
     }
   }
   __syncthreads();  // the next tile's loads overwrite the staging regions

@@ -114,7 +114,7 @@ inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void
   p->M = M; p->N = N; p->R = R; p->rank = cfg.rank;
   p->tile_m = tile_m; p->tile_n = tile_n;
   p->Tm_r = Tm_r; p->Tn_r = Tn_r; p->ncm = M / Tm_r; p->ncn = N / Tn_r;
-  p->direct = cfg.rs_direct_push ? 1 : 0;
+  p->direct = cfg.rs_direct_push == 2 ? 2 : (cfg.rs_direct_push ? 1 : 0);
   p->seg_rows = M / R;
   p->tiles_per_seg = (p->seg_rows / Tm_r) * p->ncn;
   p->rs_first_block = 0;

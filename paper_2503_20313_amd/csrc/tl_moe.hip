@@ -239,6 +239,7 @@ struct ScatterRows {
     scale = w[rid];
     return scatter + (long)rid * ld;
   }
+  __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(scatter + (long)rows[r] * ld + col) = v; }
 };
 
 struct MoeP2Params {
@@ -573,6 +574,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
     int first = cfg.tile_order == TL_ORDER_OWN_FIRST ? cfg.rank : (cfg.rank + 1) % R;
     p.rs.rs_first_block = first * (T / R / r.Tt);
   }
+  if (p.rs.direct == 2) p.rs.direct = 1;  // the own segment is reduced by stage C here (stage B has no peer data at hand)
   if (!aligned128(scatter_buf)) p.rs.ctl.strict = 1;  // stage B's guarded regions are column blocks of the scatter buffer
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
   const bool alone = cfg.comm_alone != 0;

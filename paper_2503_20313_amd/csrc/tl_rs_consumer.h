@@ -16,7 +16,8 @@ struct RsSide {
   int seg_rows, tiles_per_seg;
   int rs_first_block;               // rotation of reduce row-blocks
   int do_wait;                      // wait for the producer stage's notifications
-  int direct;                       // the producer stage stored the other segments' rows into peer_push itself
+  int direct;                       // 1: the producer stage stored the other segments' rows into peer_push itself;
+                                    // 2: it also reduced the own segment in its epilogue (the consumer only forwards)
   unsigned epoch;
   unsigned* ready;                  // [ncm*ncn]
   unsigned* arrived;                // [R*tiles_per_seg]
@@ -42,6 +43,7 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
     const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
     const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
     const int seg_row = row_lo - dest * p.seg_rows;
+    if (p.direct == 2 && dest == p.rank) continue;  // reduced by the producer stage's epilogue
     if (tid == 0) {
       if (p.do_wait) {
         // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
@@ -83,6 +85,30 @@ struct PushRows {
     const int dest = g / rs->seg_rows;
     if (!rs->direct || dest == rs->rank) return rs->partial + (long)g * rs->N + col_lo;
     return rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo;
+  }
+  // 8 values of tile row r at tile column col.  Mode 2, own segment: besides the bf16 partial, out = bf16(sum over
+  // ranks in rank order, fp32) with the R-1 peer values of the same place loaded together (the caller has done the
+  // peer_tile_wait): the same arithmetic as the consumer's sum, so both paths give identical bits.
+  __device__ __forceinline__ void store(int r, int col, u32x4 v) const {
+    const int g = row_lo + r;
+    const int dest = g / rs->seg_rows;
+    if (!rs->direct || dest == rs->rank) {
+      *(u32x4*)(rs->partial + (long)g * rs->N + col_lo + col) = v;
+      if (rs->direct == 2) {
+        const long off = (long)(g - dest * rs->seg_rows) * rs->N + col_lo + col;
+        u32x4 pv[kMaxWorld];
+#pragma unroll
+        for (int q = 0; q < kMaxWorld; q++)
+          if (q < rs->R && q != rs->rank) pv[q] = __builtin_nontemporal_load((const u32x4*)(rs->peer_recv[q] + off));
+        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < kMaxWorld; q++)
+          if (q < rs->R) acc_bf16x8(s, q == rs->rank ? v : pv[q]);
+        *(u32x4*)(rs->out + off) = pack_bf16x8(s);
+      }
+    } else {
+      *(u32x4*)(rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo + col) = v;
+    }
   }
 };
 

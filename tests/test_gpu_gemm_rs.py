@@ -72,7 +72,7 @@ def check(w, host_a, partial, push, out, what, direct=False):
     return assert_close_bf16(out, out_ref, what + " out")
 
 
-@pytest.mark.parametrize("direct", [0, 1])
+@pytest.mark.parametrize("direct", [0, 1, 2])
 @pytest.mark.parametrize("mode", list(MODES))
 @pytest.mark.parametrize("rank", [0, 1])
 def test_small(mode, rank, direct):
@@ -88,7 +88,7 @@ def test_small(mode, rank, direct):
     assert pushed[other * tps:(other + 1) * tps].tolist() == [3] * tps and pushed[rank * tps:(rank + 1) * tps].tolist() == [0] * tps
 
 
-@pytest.mark.parametrize("direct", [0, 1])
+@pytest.mark.parametrize("direct", [0, 1, 2])
 @pytest.mark.parametrize("tile,rt", [((256, 256), (56, 152)), ((256, 224), (140, 456)), ((128, 128), (280, 8)), ((128, 128), (20, 152))])
 def test_ragged_and_mismatched_reduce_tiles(tile, rt, direct):
     # 4 segments of 280 rows, N = 456: ragged for every GEMM tile (a 256-row tile straddles two segments, so with
@@ -120,7 +120,8 @@ def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("mode,order,direct", [("waves", tl.TL_ORDER_RING, 0), ("side", tl.TL_ORDER_OWN_FIRST, 0), ("side", tl.TL_ORDER_OWN_FIRST, 1)])
+@pytest.mark.parametrize("mode,order,direct", [("waves", tl.TL_ORDER_RING, 0), ("side", tl.TL_ORDER_OWN_FIRST, 0), ("side", tl.TL_ORDER_OWN_FIRST, 1), ("side", tl.TL_ORDER_OWN_FIRST, 2),
+                                               ("waves", tl.TL_ORDER_RING, 2)])
 def test_full_size_tp8_share(mode, order, direct):
     """BASELINE configuration 3: A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]; the side-kernel /
     own-first combination is the launch configuration bench.py times."""
