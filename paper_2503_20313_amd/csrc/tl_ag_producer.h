@@ -66,7 +66,7 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
 }
 
 // Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
-__device__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_ticket) {
+__device__ __forceinline__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_ticket) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   for (;;) {
     if (wave == 0) {

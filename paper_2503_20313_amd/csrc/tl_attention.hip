@@ -2,25 +2,33 @@
 // query shard (paper: "Kernel Design", AG KV + self-attention; background: sequence-parallel attention).
 // gfx950 only, head_dim 128.
 //
-// One workgroup = one (head, block of 256 local queries); 8 waves, 32 queries each.  K/V blocks of 64 keys
-// go through two LDS stages filled by direct-to-LDS loads.  Per wave and K/V block:
+// One workgroup = one (head, block of 256 local queries); a wave owns QT tiles of 32 queries (QT = 2: 4 waves, one
+// per SIMD with the whole register file; QT = 1: 8 waves).  K/V blocks of 64 keys go through three LDS stages
+// filled by direct-to-LDS loads.  Per wave, query tile and K/V block:
 //   S^T[keys, q] = K . Q^T            (MFMA 32x32x16; K fragments from LDS, Q fragments live in registers)
 //   online softmax down the key axis  (a lane owns one query column: the reduction over keys is over its own
 //                                      registers plus one exchange with the lane 32 apart)
 //   O^T[d, q]  += V^T . P^T           (P^T comes straight from the S^T accumulators: the key order inside an
 //                                      MFMA's reduction is free, so V^T fragments are fetched in the order the
 //                                      accumulators hold the keys, with transposing LDS reads)
-// The first K/V block of every AllGather channel is preceded by consumer_tile_wait on that channel's K and V
-// flags; a waiting workgroup works off producer tickets instead of idling.
+// Every K or V fragment read from LDS feeds QT matrix instructions.  The first K/V block of every AllGather
+// channel is preceded by consumer_tile_wait on that channel's K and V flags; a waiting workgroup works off
+// producer tickets instead of idling.
 #include "tl_ag_producer.h"
 #include "tl_gemm_tile.h"
 #include "tl_host.h"
 
 namespace tl {
 
-constexpr int kBQ = 256, kBKV = 64, kD = 128, kAttnWaves = 8, kAttnThreads = kAttnWaves * 64;
+#ifndef TL_ATTN_QT
+#define TL_ATTN_QT 1
+#endif
+#ifndef TL_ATTN_AHEAD
+#define TL_ATTN_AHEAD 2
+#endif
+constexpr int kBQ = 256, kBKV = 64, kD = 128;
 constexpr int kKvTileBytes = kBKV * kD * 2;            // 16 KiB
-constexpr int kAttnLds = 2 * 2 * kKvTileBytes;         // two stages of (K tile, V tile)
+constexpr int kAttnLds = 3 * 2 * kKvTileBytes;         // three stages of (K tile, V tile)
 
 struct AttnParams {
   AgProducer kprod, vprod;  // gathered K and V, each [S, heads*D]
@@ -35,15 +43,18 @@ struct AttnParams {
 
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
-__global__ void __launch_bounds__(kAttnThreads) sp_attention_kernel(const AttnParams p) {
+template <int QT>
+__global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams p) {
+  constexpr int NW = 8 / QT, NT = NW * 64;         // waves, threads
+  constexpr int WQ = 32 * QT;                      // queries per wave
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_ticket;
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform for the compiler too: the K/V loop holds barriers
   if ((int)blockIdx.x < p.n_comm) {
     // K and V producers share the communication workgroups: even ones start with K, odd ones with V
-    if (blockIdx.x & 1) { ag_producer(p.vprod, tid, kAttnThreads, &s_ticket); ag_producer(p.kprod, tid, kAttnThreads, &s_ticket); }
-    else { ag_producer(p.kprod, tid, kAttnThreads, &s_ticket); ag_producer(p.vprod, tid, kAttnThreads, &s_ticket); }
+    if (blockIdx.x & 1) { ag_producer(p.vprod, tid, NT, &s_ticket); ag_producer(p.kprod, tid, NT, &s_ticket); }
+    else { ag_producer(p.kprod, tid, NT, &s_ticket); ag_producer(p.vprod, tid, NT, &s_ticket); }
     return;
   }
   if (!p.do_compute) return;
@@ -61,178 +72,243 @@ __global__ void __launch_bounds__(kAttnThreads) sp_attention_kernel(const AttnPa
     qb = p.n_qblocks - 1 - wid / p.heads;
   }
   const int q0 = qb * kBQ;                       // first local query row of the workgroup
-  const int qw0 = q0 + wave * 32;                // first local query row of the wave
+  const int qw0 = q0 + wave * WQ;                // first local query row of the wave
   const int g0 = p.rank * p.S_loc;               // global position of local row 0
   const long ldq = (long)p.heads * kD;           // row pitch of q/k/v/o in elements
 
-  // ---- Q fragments (MFMA B operand): lane = query column l32, 8 consecutive d per 16-wide step
-  bf16x8 qf[8];
-  {
-    int row = min(qw0 + l32, p.S_loc - 1);
+  // ---- Q fragments (MFMA B operand): lane = query column l32 of tile u, 8 consecutive d per 16-wide step
+  bf16x8 qf[QT][8];
+#pragma unroll
+  for (int u = 0; u < QT; u++) {
+    int row = min(qw0 + u * 32 + l32, p.S_loc - 1);
     const bf16_t* qrow = p.q + (long)row * ldq + (long)head * kD + h * 8;
 #pragma unroll
-    for (int st = 0; st < 8; st++) qf[st] = *(const bf16x8*)(qrow + st * 16);
+    for (int st = 0; st < 8; st++) qf[u][st] = *(const bf16x8*)(qrow + st * 16);
   }
 
-  // ---- K/V stage loads: a tile is 64 rows x 256 bytes = 16 wave-wide loads of 1 KiB; wave w issues loads w and w+8
+  // ---- K/V stage loads: a tile is 64 rows x 256 bytes = 16 wave-wide loads of 1 KiB; wave w issues loads w, w+NW, ..
   // of the K tile and of the V tile.  LDS slot (row, pc) holds logical 16-byte chunk pc ^ f(row):
   //   K: f = row % 16   (fragment reads take one chunk from 16 consecutive rows)
   //   V: f = (row % 4) << 2 (transposing reads take 32 bytes from 4 consecutive rows)
+  constexpr int LPW = 16 / NW;                                    // loads per wave and tile
   const int wg_q_hi = min(q0 + kBQ, p.S_loc) - 1;                 // last valid local query row of the workgroup
   const int n_kv = p.causal ? (g0 + wg_q_hi) / kBKV + 1 : (p.S + kBKV - 1) / kBKV;
   const char* kbase = (const char*)(p.kprod.gathered + (long)head * kD);
   const char* vbase = (const char*)(p.vprod.gathered + (long)head * kD);
-  int ld_row[2], ld_kc[2], ld_vc[2];
+  int ld_row[LPW], ld_kc[LPW], ld_vc[LPW];
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    int j = wave + i * kAttnWaves;
+  for (int i = 0; i < LPW; i++) {
+    int j = wave + i * NW;
     int row = j * 4 + (lane >> 4), pc = lane & 15;
     ld_row[i] = row;
     ld_kc[i] = (pc ^ (row & 15)) * 16;
     ld_vc[i] = (pc ^ ((row & 3) << 2)) * 16;
   }
-  auto issue_block = [&](int blk, int stage) {
+  auto issue_block = [&](int blk, int stage) __attribute__((always_inline)) {
     char* sk = smem + stage * 2 * kKvTileBytes;
     char* sv = sk + kKvTileBytes;
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      int j = wave + i * kAttnWaves;
+    for (int i = 0; i < LPW; i++) {
+      int j = wave + i * NW;
       long row = min(blk * kBKV + ld_row[i], p.S - 1);
       lds_load16(kbase + row * ldq * 2 + ld_kc[i], sk + j * 1024);
       lds_load16(vbase + row * ldq * 2 + ld_vc[i], sv + j * 1024);
     }
   };
   // consumer_tile_wait on the K and V flags of the channel block `blk` starts, if it starts one
-  auto wait_for_block = [&](int blk) {
+  auto wait_for_block = [&](int blk) __attribute__((always_inline)) {
     if (!p.do_wait) return;
     int row = blk * kBKV;
     if (row % p.rows_per_channel != 0) return;
     unsigned long long m = 1ull << (row / p.rows_per_channel);
-    consumer_wait_or_produce(p.kprod, m, tid, kAttnThreads, &s_ticket);
-    consumer_wait_or_produce(p.vprod, m, tid, kAttnThreads, &s_ticket);
+    consumer_wait_or_produce(p.kprod, m, tid, NT, &s_ticket);
+    consumer_wait_or_produce(p.vprod, m, tid, NT, &s_ticket);
   };
 
   // ---- per-lane LDS read offsets
-  const int k_row_off = l32 * 256;                 // + t*32*256
-  const int k_sw = l32 & 15;                       // (row % 16) is the same for both key tiles
+  // K fragment i (k-step i/2, key tile i%2) of the K tile at byte offset kb = stage offset + this lane's row and
+  // swizzle term: the chunk index (2*st + h) ^ (row % 16) only touches the low 8 address bits, so it is one XOR
+  typedef short short8_t __attribute__((ext_vector_type(8)));
+  const int k_lane_off = l32 * 256 + ((h ^ (l32 & 15)) << 4);
+  auto kread = [&](int kb, int i) __attribute__((always_inline)) -> bf16x8 {
+    return *(const bf16x8*)(smem + (i & 1) * 32 * 256 + (kb ^ ((i >> 1) << 5)));
+  };
+  // V^T fragment j (key group j/4 of 16 keys, d-tile j%4).  MFMA reduction slot (h, r) of group g is key
+  // g*16 + (r/4)*8 + 4h + r%4, the order in which pf[.][g] holds the probabilities: two transposing reads at key
+  // rows g*16 + 4h and g*16 + 8 + 4h.
   const int v_r = (lane & 15) >> 2;                // row inside the 4-row group a transposing read covers
   int v_off[4];                                    // per d-tile: address for (row v_r of a group, this lane's 4 columns)
 #pragma unroll
   for (int dt = 0; dt < 4; dt++) {
     int col = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
     int c = (col >> 3) ^ (v_r << 2);
-    v_off[dt] = v_r * 256 + c * 16 + (col & 4) * 2;
+    v_off[dt] = (v_r + 4 * h) * 256 + c * 16 + (col & 4) * 2;
+  }
+  auto vread = [&](const char* sv, int j) __attribute__((always_inline)) -> bf16x8 {
+    const char* pv = sv + (j >> 2) * 16 * 256 + v_off[j & 3];
+    short4_t lo = lds_read_tr(pv);
+    short4_t hi = lds_read_tr(pv + 8 * 256);
+    return __builtin_bit_cast(bf16x8, (short8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  floatx16 zero16;
+#pragma unroll
+  for (int e = 0; e < 16; e++) zero16[e] = 0.f;
+
+  floatx16 oacc[QT][4];
+#pragma unroll
+  for (int u = 0; u < QT; u++)
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) oacc[u][dt] = zero16;
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int u = 0; u < QT; u++) { m_run[u] = -1e30f; l_run[u] = 0.f; }
+  const int q_glob = g0 + qw0 + l32;               // this lane's query position in tile 0; tile u is 32u further
+  const int qw_glob_hi = g0 + min(qw0 + WQ - 1, p.S_loc - 1);
+
+  int st_cur = 0, st_nxt = 1, st_ld = 2;   // LDS stages of blocks blk, blk+1, blk+2
+
+  // One block of the software-pipelined loop: the scores of block blk are in c[u][key tile]; the scores of block
+  // blk+1 go to n[u][key tile].  Iteration blk computes S(blk+1) while it takes block blk through the softmax, so
+  // that the matrix pipe and the vector ALU of a SIMD work at the same time (all waves of the workgroup meet at a
+  // barrier per block and would otherwise run the same phase side by side).  A K/V stage is live for three
+  // iterations: filled during blk-2, K read during blk-1, V read during blk.
+  auto block = [&](int blk, floatx16 (&c)[QT][2], floatx16 (&n)[QT][2]) __attribute__((always_inline)) {
+    wait_vmcnt<0>();
+    __syncthreads();  // block blk+1 has landed for every wave; nobody reads the stage of block blk-1 any more
+    if (blk + 2 < n_kv) {
+      wait_for_block(blk + 2);
+      issue_block(blk + 2, st_ld);
+    }
+    const int kv0 = blk * kBKV;
+    // a block whose keys all lie after every query of this wave is skipped, and so are all later ones
+    if (!(p.causal && kv0 > qw_glob_hi)) {
+      // mask.  Accumulator e of key tile t is key kv0 + t*32 + (e/4)*8 + h*4 + e%4.  A query tile whose keys are all
+      // masked keeps its running maximum (finite from block 0 on) and gets probabilities exp2(-inf) = 0.
+      const bool need_mask = (p.causal && kv0 + kBKV - 1 > g0 + qw0) || kv0 + kBKV > p.S;
+      if (need_mask) {
+#pragma unroll
+        for (int u = 0; u < QT; u++)
+#pragma unroll
+          for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+              int key = kv0 + t * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+              if ((p.causal && key > q_glob + u * 32) || key >= p.S) c[u][t][e] = -INFINITY;
+            }
+      }
+      // online softmax, part 1: running maximum and the rescaling of O.  The softmax scale (times log2 e) is folded
+      // into the exponent: p = exp2(s*c - m*c) is one fused multiply-add and one exp2 per score; the running
+      // maximum m is kept in units of the raw scores (c > 0)
+      float alpha[QT], mc[QT];
+      bool rescale = false;
+#pragma unroll
+      for (int u = 0; u < QT; u++) {
+        float mloc = -1e30f;
+#pragma unroll
+        for (int e = 0; e < 16; e++) mloc = fmaxf(mloc, fmaxf(c[u][0][e], c[u][1][e]));
+        mloc = fmaxf(mloc, xor32(mloc));
+        const float m_new = fmaxf(m_run[u], mloc);
+        alpha[u] = __builtin_amdgcn_exp2f((m_run[u] - m_new) * p.scale_log2e);
+        m_run[u] = m_new;
+        mc[u] = -m_new * p.scale_log2e;
+        rescale |= alpha[u] != 1.f;
+      }
+      if (__builtin_amdgcn_ballot_w64(rescale)) {
+#pragma unroll
+        for (int u = 0; u < QT; u++)
+#pragma unroll
+          for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) oacc[u][dt][e] *= alpha[u];
+      }
+      // ---- 32 fragments in a fixed issue order, each feeding QT matrix instructions: 16 of S(blk+1) = K.Q^T (past
+      // the last block: of whatever the stage holds; the result is dropped), then 16 of O^T += V^T.P^T.  Fragments
+      // are read from LDS two ahead, and each instruction slot carries a slice of part 2 of the softmax
+      // (p = exp2(s*c - m*c), row sum, conversion to the bf16 operand).  The scores are taken key group by key
+      // group (16 keys), query tile by query tile; score y of that order is done in slot y*7/8, so that the
+      // probabilities of key group g are complete before the first slot that multiplies them, (16 + 4g)*QT.
+      const int kb = st_nxt * 2 * kKvTileBytes + k_lane_off;
+      const char* sv = smem + st_cur * 2 * kKvTileBytes + kKvTileBytes;
+      constexpr int RD = TL_ATTN_AHEAD, RN = RD + 1;   // fragments read ahead, ring size
+      bf16x8 fr[RN];
+      bf16x8 pf[QT][4];
+      float psum[QT];
+#pragma unroll
+      for (int u = 0; u < QT; u++) psum[u] = 0.f;
+#pragma unroll
+      for (int i = 0; i < RD; i++) fr[i] = kread(kb, i);
+      static_for<0, 32 * QT>([&](auto s_c) {
+        constexpr int sl = decltype(s_c)::value, f = sl / QT, u = sl % QT;
+        if constexpr (u == 0) {
+          if constexpr (f + RD < 16) fr[(f + RD) % RN] = kread(kb, f + RD);
+          else if constexpr (f + RD < 32) fr[(f + RD) % RN] = vread(sv, f + RD - 16);
+        }
+        if constexpr (f < 16) {
+          floatx16& acc = n[u][f & 1];
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % RN], qf[u][f >> 1], f < 2 ? zero16 : acc, 0, 0, 0);
+        } else {
+          constexpr int j = f - 16;
+          oacc[u][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % RN], pf[u][j >> 2], oacc[u][j & 3], 0, 0, 0);
+        }
+        static_for<0, 32 * QT>([&](auto y_c) {
+          constexpr int y = decltype(y_c)::value;
+          if constexpr (y * 7 / 8 == sl) {
+            constexpr int g = y / (8 * QT), uu = (y / 8) % QT, i = y % 8;
+            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(c[uu][g >> 1][(g & 1) * 8 + i], p.scale_log2e, mc[uu]));
+            psum[uu] += pv;
+            pf[uu][g][i] = (bf16_t)pv;
+          }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+#pragma unroll
+      for (int u = 0; u < QT; u++) l_run[u] = l_run[u] * alpha[u] + psum[u];
+    }
+    const int st_free = st_cur;
+    st_cur = st_nxt; st_nxt = st_ld; st_ld = st_free;
+  };
+
+  for (int b = 0; b < 2 && b < n_kv; b++) {
+    wait_for_block(b);
+    issue_block(b, b);
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+  floatx16 sa[QT][2], sb[QT][2];   // scores of even blocks / of odd blocks
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    bf16x8 kf = kread(k_lane_off, i);
+#pragma unroll
+    for (int u = 0; u < QT; u++)
+      sa[u][i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][i >> 1], i < 2 ? zero16 : sa[u][i & 1], 0, 0, 0);
+  }
+  for (int blk = 0; blk < n_kv; blk += 2) {
+    block(blk, sa, sb);
+    if (blk + 1 < n_kv) block(blk + 1, sb, sa);
   }
 
-  floatx16 oacc[4];
+  // ---- normalise and store: accumulator e of d-tile dt is d = dt*32 + (e/4)*8 + h*4 + e%4 of query l32 of tile u
 #pragma unroll
-  for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-    for (int e = 0; e < 16; e++) oacc[dt][e] = 0.f;
-  float m_run = -1e30f, l_run = 0.f;
-  const int q_glob = g0 + qw0 + l32;               // this lane's query position
-  const int qw_glob_hi = g0 + min(qw0 + 31, p.S_loc - 1);
-
-  for (int blk = -1; blk < n_kv; blk++) {
-    wait_vmcnt<0>();
-    __syncthreads();  // block blk has landed for every wave; nobody reads the other stage any more
-    if (blk + 1 < n_kv) {
-      wait_for_block(blk + 1);
-      issue_block(blk + 1, (blk + 1) & 1);
-    }
-    if (blk < 0) continue;
-    const int kv0 = blk * kBKV;
-    if (p.causal && kv0 > qw_glob_hi) continue;    // every key of the block lies after every query of this wave
-    const char* sk = smem + (blk & 1) * 2 * kKvTileBytes;
-    const char* sv = sk + kKvTileBytes;
-
-    // S^T = K . Q^T
-    floatx16 sacc[2];
-#pragma unroll
-    for (int t = 0; t < 2; t++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) sacc[t][e] = 0.f;
-#pragma unroll
-    for (int st = 0; st < 8; st++) {
-#pragma unroll
-      for (int t = 0; t < 2; t++) {
-        bf16x8 kf = *(const bf16x8*)(sk + t * 32 * 256 + k_row_off + (((2 * st + h) ^ k_sw) << 4));
-        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc[t], 0, 0, 0);
-      }
-    }
-    // scale, mask, online softmax.  Accumulator e of key tile t is key kv0 + t*32 + (e/4)*8 + h*4 + e%4.
-    const bool need_mask = (p.causal && kv0 + kBKV - 1 > g0 + qw0) || kv0 + kBKV > p.S;
-    // the softmax scale (times log2 e) is folded into the exponent: p = exp2(s*c - m*c) is one fused multiply-add and
-    // one exp2 per score; the running maximum m is kept in units of the raw scores (c > 0)
-    if (need_mask) {
-#pragma unroll
-      for (int t = 0; t < 2; t++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          int key = kv0 + t * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-          if ((p.causal && key > q_glob) || key >= p.S) sacc[t][e] = -INFINITY;
-        }
-    }
-    float mloc = -1e30f;
-#pragma unroll
-    for (int t = 0; t < 2; t++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) mloc = fmaxf(mloc, sacc[t][e]);
-    mloc = fmaxf(mloc, xor32(mloc));
-    const float m_new = fmaxf(m_run, mloc);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
-    m_run = m_new;
-    const float mc = -m_new * p.scale_log2e;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int t = 0; t < 2; t++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][e], p.scale_log2e, mc));
-        psum += pv;
-        pf[t * 2 + (e >> 3)][e & 7] = (bf16_t)pv;
-      }
-    l_run = l_run * alpha + psum;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+  for (int u = 0; u < QT; u++) {
+    const float l_tot = l_run[u] + xor32(l_run[u]);
+    const float inv = 1.f / l_tot;
+    const int row = qw0 + u * 32 + l32;
+    if (row < p.S_loc) {
+      bf16_t* orow = p.o + (long)row * ldq + (long)head * kD + h * 4;
 #pragma unroll
       for (int dt = 0; dt < 4; dt++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) oacc[dt][e] *= alpha;
+        for (int gq = 0; gq < 4; gq++) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = (bf16_t)(oacc[u][dt][gq * 4 + e] * inv);
+          *(bf16x4*)(orow + dt * 32 + gq * 8) = v;
+        }
     }
-    // O^T += V^T . P^T.  Group g = 16 keys; MFMA reduction slot (h, j) of group g is key g*16 + (j/4)*8 + 4h + j%4,
-    // i.e. the order in which pf[g] holds them: two transposing reads at key rows g*16 + 4h and g*16 + 8 + 4h.
-#pragma unroll
-    for (int g = 0; g < 4; g++) {
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        const char* pv = sv + (g * 16 + 4 * h) * 256 + v_off[dt];
-        short4_t lo = lds_read_tr(pv);
-        short4_t hi = lds_read_tr(pv + 8 * 256);
-        typedef short short8_t __attribute__((ext_vector_type(8)));
-        short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), pf[g], oacc[dt], 0, 0, 0);
-      }
-    }
-  }
-
-  // ---- normalise and store: accumulator e of d-tile dt is d = dt*32 + (e/4)*8 + h*4 + e%4 of query l32
-  const float l_tot = l_run + xor32(l_run);
-  const float inv = 1.f / l_tot;
-  const int row = qw0 + l32;
-  if (row < p.S_loc) {
-    bf16_t* orow = p.o + (long)row * ldq + (long)head * kD + h * 4;
-#pragma unroll
-    for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; e++) v[e] = (bf16_t)(oacc[dt][gq * 4 + e] * inv);
-        *(bf16x4*)(orow + dt * 32 + gq * 8) = v;
-      }
   }
 }
+
+constexpr int kAttnQT = TL_ATTN_QT, kAttnThreads = 512 / kAttnQT;
 
 __global__ void __launch_bounds__(256) kv_producer_kernel(const AgProducer k, const AgProducer v) {
   __shared__ int s_ticket;
@@ -331,8 +407,8 @@ int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, 
   p.do_compute = alone ? 0 : 1;
   const int n_wg = r.n_qblocks * heads;
   auto launch = [&](int grid) -> int {
-    TL_HIP(hipFuncSetAttribute((const void*)sp_attention_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLds));
-    hipLaunchKernelGGL(sp_attention_kernel, dim3(grid), dim3(kAttnThreads), kAttnLds, cs, p);
+    TL_HIP(hipFuncSetAttribute((const void*)sp_attention_kernel<kAttnQT>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLds));
+    hipLaunchKernelGGL(sp_attention_kernel<kAttnQT>, dim3(grid), dim3(kAttnThreads), kAttnLds, cs, p);
     TL_HIP(hipGetLastError());
     return TL_OK;
   };
