@@ -41,7 +41,18 @@ struct AttnParams {
   int rows_per_channel, n_channels;  // AllGather channels along the sequence (per tensor)
 };
 
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+// The two values a query column has in lanes l and l+32, in every lane (one VALU lane-half swap, no LDS round trip).
+__device__ __forceinline__ void both_halves(float v, float& lo, float& hi) {
+  const unsigned b = __builtin_bit_cast(unsigned, v);
+  auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  lo = __builtin_bit_cast(float, (unsigned)r[0]);
+  hi = __builtin_bit_cast(float, (unsigned)r[1]);
+}
+__device__ __forceinline__ float halves_max(float v) {
+  float lo, hi;
+  both_halves(v, lo, hi);
+  return __builtin_fmaxf(lo, hi);
+}
 
 template <int QT>
 __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams p) {
@@ -166,6 +177,14 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   const int qw_glob_hi = g0 + min(qw0 + WQ - 1, p.S_loc - 1);
 
   int st_cur = 0, st_nxt = 1, st_ld = 2;   // LDS stages of blocks blk, blk+1, blk+2
+  // largest raw score of a query column in one block (both key tiles, both lane halves)
+  auto block_max = [&](const floatx16 (&sc)[2]) __attribute__((always_inline)) -> float {
+    float m = -1e30f;
+#pragma unroll
+    for (int e = 0; e < 16; e++) m = fmaxf(m, fmaxf(sc[0][e], sc[1][e]));
+    return halves_max(m);
+  };
+  float m_blk[QT];   // block_max of the block the next iteration works on, computed one iteration early
 
   // One block of the software-pipelined loop: the scores of block blk are in c[u][key tile]; the scores of block
   // blk+1 go to n[u][key tile].  Iteration blk computes S(blk+1) while it takes block blk through the softmax, so
@@ -182,6 +201,14 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
     const int kv0 = blk * kBKV;
     // a block whose keys all lie after every query of this wave is skipped, and so are all later ones
     if (!(p.causal && kv0 > qw_glob_hi)) {
+      // the first K fragments of block blk+1 are on their way while part 1 of the softmax runs
+      const int kb = st_nxt * 2 * kKvTileBytes + k_lane_off;
+      const char* sv = smem + st_cur * 2 * kKvTileBytes + kKvTileBytes;
+      constexpr int RD = TL_ATTN_AHEAD, RN = RD + 1;   // fragments read ahead, ring size
+      bf16x8 fr[RN];
+#pragma unroll
+      for (int i = 0; i < RD; i++) fr[i] = kread(kb, i);
+      __builtin_amdgcn_sched_barrier(0);
       // mask.  Accumulator e of key tile t is key kv0 + t*32 + (e/4)*8 + h*4 + e%4.  A query tile whose keys are all
       // masked keeps its running maximum (finite from block 0 on) and gets probabilities exp2(-inf) = 0.
       const bool need_mask = (p.causal && kv0 + kBKV - 1 > g0 + qw0) || kv0 + kBKV > p.S;
@@ -201,13 +228,13 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
       // maximum m is kept in units of the raw scores (c > 0)
       float alpha[QT], mc[QT];
       bool rescale = false;
+      if (need_mask) {
+#pragma unroll
+        for (int u = 0; u < QT; u++) m_blk[u] = block_max(c[u]);
+      }
 #pragma unroll
       for (int u = 0; u < QT; u++) {
-        float mloc = -1e30f;
-#pragma unroll
-        for (int e = 0; e < 16; e++) mloc = fmaxf(mloc, fmaxf(c[u][0][e], c[u][1][e]));
-        mloc = fmaxf(mloc, xor32(mloc));
-        const float m_new = fmaxf(m_run[u], mloc);
+        const float m_new = fmaxf(m_run[u], m_blk[u]);
         alpha[u] = __builtin_amdgcn_exp2f((m_run[u] - m_new) * p.scale_log2e);
         m_run[u] = m_new;
         mc[u] = -m_new * p.scale_log2e;
@@ -227,16 +254,10 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
       // (p = exp2(s*c - m*c), row sum, conversion to the bf16 operand).  The scores are taken key group by key
       // group (16 keys), query tile by query tile; score y of that order is done in slot y*7/8, so that the
       // probabilities of key group g are complete before the first slot that multiplies them, (16 + 4g)*QT.
-      const int kb = st_nxt * 2 * kKvTileBytes + k_lane_off;
-      const char* sv = smem + st_cur * 2 * kKvTileBytes + kKvTileBytes;
-      constexpr int RD = TL_ATTN_AHEAD, RN = RD + 1;   // fragments read ahead, ring size
-      bf16x8 fr[RN];
       bf16x8 pf[QT][4];
-      float psum[QT];
+      float psum[QT], m_part[QT], m_next[QT];
 #pragma unroll
       for (int u = 0; u < QT; u++) psum[u] = 0.f;
-#pragma unroll
-      for (int i = 0; i < RD; i++) fr[i] = kread(kb, i);
       static_for<0, 32 * QT>([&](auto s_c) {
         constexpr int sl = decltype(s_c)::value, f = sl / QT, u = sl % QT;
         if constexpr (u == 0) {
@@ -250,6 +271,21 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
           constexpr int j = f - 16;
           oacc[u][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % RN], pf[u][j >> 2], oacc[u][j & 3], 0, 0, 0);
         }
+        // the maximum of block blk+1's scores, ready for the next iteration (a masked block recomputes it after masking)
+        if constexpr (f >= 18 && f < 18 + 4 && u == 0) {
+          constexpr int q = f - 18;   // quarter of the 16 accumulator pairs
+#pragma unroll
+          for (int uu = 0; uu < QT; uu++) {
+            float m = q == 0 ? -1e30f : m_part[uu];
+#pragma unroll
+            for (int e = q * 4; e < q * 4 + 4; e++) m = fmaxf(m, fmaxf(n[uu][0][e], n[uu][1][e]));
+            m_part[uu] = m;
+          }
+        }
+        if constexpr (f == 23 && u == 0) {
+#pragma unroll
+          for (int uu = 0; uu < QT; uu++) m_next[uu] = halves_max(m_part[uu]);
+        }
         static_for<0, 32 * QT>([&](auto y_c) {
           constexpr int y = decltype(y_c)::value;
           if constexpr (y * 7 / 8 == sl) {
@@ -262,7 +298,10 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
         __builtin_amdgcn_sched_barrier(0);
       });
 #pragma unroll
-      for (int u = 0; u < QT; u++) l_run[u] = l_run[u] * alpha[u] + psum[u];
+      for (int u = 0; u < QT; u++) {
+        l_run[u] = l_run[u] * alpha[u] + psum[u];
+        m_blk[u] = m_next[u];
+      }
     }
     const int st_free = st_cur;
     st_cur = st_nxt; st_nxt = st_ld; st_ld = st_free;
@@ -282,6 +321,8 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
     for (int u = 0; u < QT; u++)
       sa[u][i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][i >> 1], i < 2 ? zero16 : sa[u][i & 1], 0, 0, 0);
   }
+#pragma unroll
+  for (int u = 0; u < QT; u++) m_blk[u] = block_max(sa[u]);
   for (int blk = 0; blk < n_kv; blk += 2) {
     block(blk, sa, sb);
     if (blk + 1 < n_kv) block(blk + 1, sb, sa);
@@ -290,7 +331,9 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   // ---- normalise and store: accumulator e of d-tile dt is d = dt*32 + (e/4)*8 + h*4 + e%4 of query l32 of tile u
 #pragma unroll
   for (int u = 0; u < QT; u++) {
-    const float l_tot = l_run[u] + xor32(l_run[u]);
+    float l_lo, l_hi;
+    both_halves(l_run[u], l_lo, l_hi);
+    const float l_tot = l_lo + l_hi;
     const float inv = 1.f / l_tot;
     const int row = qw0 + u * 32 + l32;
     if (row < p.S_loc) {
