@@ -93,6 +93,14 @@ typedef struct tl_config {
                               2 (tl_gemm_rs only; 1 elsewhere) = in addition the GEMM epilogue reduces the rows of the own
                               segment itself: it waits for the peers' contributions (peer_tile_wait) before such a tile and
                               writes `out` together with the own rows of `partial`; same arithmetic, same bits as 1. */
+  int ag_k_chunks;         /* tl_ag_gemm: >= 2 cuts every AllGather channel into that many chunks along K, each with a
+                              barrier of its own (flag index channel*ag_k_chunks + chunk); the producer tile is then
+                              comm_tile_m x K/ag_k_chunks and the queue delivers chunk 0 of all rows before chunk 1.  A
+                              GEMM tile starts as soon as the first chunk of its rows is there and waits for each
+                              further chunk when its K loop reaches it (the decoupled tile sizes of the paper's
+                              "tile size" sub-space, applied along K).  Needs K divisible by 64*ag_k_chunks with at
+                              least 8 K steps of 64 per chunk, comm_tile_n 0, and TL_COMM_WAVES or TL_COMM_SIDE_KERNEL
+                              with the 256x256 compute tile; elsewhere, and for 0 or 1, one flag per channel. */
 } tl_config;
 
 typedef struct tl_ctx tl_ctx;
@@ -264,9 +272,10 @@ int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims /*host*/, 
                      size_t* n /*host*/);
 
 /* The tile shape, grid sizes and flag geometry the library resolved for `dims` (host call).
- * info[0..12] = tile_m, tile_n, tile_k, compute_workgroups, comm_workgroups, comm_tile_m, comm_tile_n,
- *               n_consumer_tiles, n_comm_tiles, expected_per_channel, threads_per_workgroup, lds_bytes, group_m. */
-int tl_resolve(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* info /*host, 13 ints*/);
+ * info[0..13] = tile_m, tile_n, tile_k, compute_workgroups, comm_workgroups, comm_tile_m, comm_tile_n,
+ *               n_consumer_tiles, n_comm_tiles, expected_per_channel (per flag), threads_per_workgroup, lds_bytes,
+ *               group_m, k_chunks (flags per AllGather channel; 1 unless ag_k_chunks took effect). */
+int tl_resolve(const tl_ctx* ctx, int op, const long long* dims /*host*/, int* info /*host, 14 ints*/);
 
 #ifdef __cplusplus
 }

@@ -37,7 +37,7 @@ class tl_config(ctypes.Structure):
                 ("comm_tile_n", ctypes.c_int), ("comm_mode", ctypes.c_int), ("comm_workgroups", ctypes.c_int),
                 ("compute_workgroups", ctypes.c_int), ("tile_order", ctypes.c_int), ("xcd_swizzle", ctypes.c_int),
                 ("group_m", ctypes.c_int), ("spin_timeout_us", ctypes.c_uint), ("comm_alone", ctypes.c_int),
-                ("rs_direct_push", ctypes.c_int)]
+                ("rs_direct_push", ctypes.c_int), ("ag_k_chunks", ctypes.c_int)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -131,10 +131,11 @@ def tl_check_status(ctx, workspace):
 
 
 def tl_resolve(ctx, op, dims):
-    info = (_i * 13)()
+    info = (_i * 14)()
     _check(_lib.tl_resolve(ctx, op, _dims(dims), info))
     keys = ["tile_m", "tile_n", "tile_k", "compute_workgroups", "comm_workgroups", "comm_tile_m", "comm_tile_n",
-            "n_consumer_tiles", "n_comm_tiles", "expected_per_channel", "threads_per_workgroup", "lds_bytes", "group_m"]
+            "n_consumer_tiles", "n_comm_tiles", "expected_per_channel", "threads_per_workgroup", "lds_bytes", "group_m",
+            "k_chunks"]
     return dict(zip(keys, list(info)))
 
 

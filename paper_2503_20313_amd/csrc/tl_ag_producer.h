@@ -15,8 +15,11 @@ struct AgProducer {
   int Tm_p, Tn_p, n_ptm, n_ptn;     // producer tile and the number of tiles in the queue along rows / columns
   int rows_per_rank, rows_per_channel;
   int local_in_place;
+  int k_chunks;                     // 1: one flag per channel.  > 1: n_ptn == k_chunks column tiles, one flag per (channel,
+                                    // column tile) at flags[channel*k_chunks + tn], and the queue hands out column tile 0
+                                    // of every row tile before column tile 1 (a consumer can start on the first K chunk)
   unsigned wait_target;             // epoch * expected
-  unsigned* flags;                  // [R*C]
+  unsigned* flags;                  // [R*C*k_chunks]
   unsigned* ticket;                 // producer-tile queue head (grows by n_ptm*n_ptn per call)
   unsigned ticket_end;              // epoch * number of producer tiles
   WaitCtl ctl;
@@ -50,7 +53,9 @@ __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out)
 template <int DEPTH>
 __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid, int wave, int nthreads) {
   const int ptm_per_rank = p.rows_per_rank / p.Tm_p;
-  int tmi = i / p.n_ptn, tn = i - tmi * p.n_ptn;
+  int tmi, tn;
+  if (p.k_chunks > 1) { tn = i / p.n_ptm; tmi = i - tn * p.n_ptm; }
+  else { tmi = i / p.n_ptn; tn = i - tmi * p.n_ptn; }
   int tm = tmi + p.first_src * ptm_per_rank;  // ring order over source ranks: first_src, first_src+1, ...
   if (tm >= p.n_ptm_all) tm -= p.n_ptm_all;
   int row_lo = tm * p.Tm_p;
@@ -62,7 +67,7 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
     copy_tile<DEPTH>(s, p.ld, d, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
   }
   __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
-  if (wave == 0) wave_tile_notify(p.flags + channel);
+  if (wave == 0) wave_tile_notify(p.flags + (p.k_chunks > 1 ? channel * p.k_chunks + tn : channel));
 }
 
 // Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
@@ -82,7 +87,7 @@ __device__ __forceinline__ void ag_producer(const AgProducer& p, int tid, int nt
   }
 }
 
-// consumer_tile_wait for the channels set in chan_mask (bit = global channel index) by a whole workgroup: while a channel is short of its target
+// consumer_tile_wait for the channels set in chan_mask (bit = global channel index; with K chunks: their first chunk) by a whole workgroup: while a channel is short of its target
 // the workgroup works off producer tickets; with the queue empty it sleeps and polls (bounded by ctl.timeout).
 // DEPTH = loads in flight per lane when this workgroup copies a producer tile itself: deep where the caller's registers allow
 // (a ticket then takes a quarter of the time), shallow where they are full.
@@ -99,7 +104,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     for (unsigned long long m = chan_mask; m; m &= m - 1) {
       int qi = __builtin_ctzll(m) * tpc - p.first_src * ptm_per_rank;  // queue position of the channel's first row tile
       if (qi < 0) qi += p.n_ptm_all;
-      int end = (qi + tpc) * p.n_ptn;
+      int end = p.k_chunks > 1 ? qi + tpc : (qi + tpc) * p.n_ptn;  // with K chunks: the channel's tiles of chunk 0
       limit = end > limit ? end : limit;
     }
   }
@@ -110,7 +115,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
       int first_short = 0;
       for (unsigned long long m = chan_mask; m; m &= m - 1) {
         int ch = __builtin_ctzll(m);
-        unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + ch * p.k_chunks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if ((int)(f - p.wait_target) < 0 && state == -2) { state = -1; first_short = ch; }
       }
       if (state == -1) {

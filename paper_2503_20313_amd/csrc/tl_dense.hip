@@ -30,6 +30,25 @@ struct GemmRsParams {
   int n_comm, do_compute, do_notify;
 };
 
+// consumer_tile_wait inside the K loop, for AllGather channels that arrive in chunks along K: K step ks opens chunk
+// ks / steps_per_chunk; one wave polls the flags of that chunk for every channel the tile's rows touch while the
+// other waves go on to the barrier the K loop holds anyway.  The first chunk is waited for before the tile starts.
+struct ChunkWait {
+  static constexpr bool ENABLED = true;
+  unsigned* flags;
+  int k_chunks, steps_per_chunk, clo, chi;
+  unsigned target;
+  WaitCtl ctl;
+  __device__ __forceinline__ bool starts(int ks) const { return ks % steps_per_chunk == 0; }
+  __device__ __forceinline__ void wait(int ks) const {
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0) {   // wave 0, a uniform branch: the K loop holds barriers
+      const int kc = ks / steps_per_chunk;
+      for (int ch = clo; ch <= chi; ch++) wave_tile_wait(flags + ch * k_chunks + kc, target, ctl, ch * k_chunks + kc);
+    }
+  }
+  __device__ __forceinline__ void acquire() const { acquire_after_wait(ctl); }
+};
+
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -56,11 +75,17 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
     } else if (p.do_wait == 2) {
       // flags raised by somebody else (no ticket queue): plain wait
       if (tid == 0)
-        for (int ch = clo; ch <= chi; ch++) tile_wait(p.prod.flags + ch, p.prod.wait_target, p.prod.ctl, ch);
+        for (int ch = clo; ch <= chi; ch++) tile_wait(p.prod.flags + ch * p.prod.k_chunks, p.prod.wait_target, p.prod.ctl, ch * p.prod.k_chunks);
       __syncthreads();
     }
-    gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
-                   DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem);
+    if (p.prod.k_chunks > 1 && p.do_wait) {
+      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
+                     DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem,
+                     ChunkWait{p.prod.flags, p.prod.k_chunks, p.K / Cfg::BK / p.prod.k_chunks, clo, chi, p.prod.wait_target, p.prod.ctl});
+    } else {
+      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
+                     DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem);
+    }
   }
 }
 
@@ -236,11 +261,27 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
       return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer row tile %d must divide the rows per channel M/(R*C)=%d", Tm_p, r->rows_per_channel);
     int Tn_p = c.comm_tile_n ? c.comm_tile_n : K;
     if (Tn_p <= 0 || K % Tn_p || Tn_p % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "producer column tile %d must divide K=%d and be a multiple of 8", Tn_p, K);
+    // K chunks: only where the producers are certain to be resident beside the GEMM workgroups (a tile that is already
+    // in its K loop waits without helping them), i.e. the 256x256 tile with in-kernel or side-kernel producers
+    r->k_chunks = 1;
+    if (c.ag_k_chunks >= 2) {
+      if (c.comm_tile_n) return fail(TL_ERR_INVALID_ARG, "ag_k_chunks sets the producer column tile itself: comm_tile_n must be 0");
+      if (K % (64 * c.ag_k_chunks) || K / (64 * c.ag_k_chunks) < 8)
+        return fail(TL_ERR_UNSUPPORTED_SHAPE, "ag_k_chunks=%d needs K=%d to be a multiple of %d with at least 8 steps of 64 per chunk", c.ag_k_chunks, K, 64 * c.ag_k_chunks);
+      if (v == TILE_256x256 && (c.comm_mode == TL_COMM_WAVES || c.comm_mode == TL_COMM_SIDE_KERNEL)) {
+        r->k_chunks = c.ag_k_chunks;
+        Tn_p = K / r->k_chunks;
+        if (c.comm_tile_m == 0) {
+          // fewer, taller producer tiles: a tile is as many bytes as without chunks
+          while (Tm_p * 2 <= r->rows_per_channel && r->rows_per_channel % (Tm_p * 2) == 0 && Tm_p * 2 <= 32 * r->k_chunks) Tm_p *= 2;
+        }
+      }
+    }
     r->Tm_p = Tm_p;
     r->Tn_p = Tn_p;
     r->n_ptm = M / Tm_p;
     r->n_ptn = K / Tn_p;
-    r->expected = (r->rows_per_channel / Tm_p) * r->n_ptn;
+    r->expected = r->k_chunks > 1 ? r->rows_per_channel / Tm_p : (r->rows_per_channel / Tm_p) * r->n_ptn;
     r->first_block = 0;
     if (c.tile_order != TL_ORDER_NATURAL) {
       if (r->nbm % R == 0) r->first_block = c.rank * (r->nbm / R);
@@ -331,7 +372,8 @@ int tl_resolve(const tl_ctx* ctx, int op, const long long* dims, int* info) {
   if (op != TL_OP_AG_GEMM && op != TL_OP_GEMM_RS) return fail(TL_ERR_INVALID_ARG, "tl_resolve: operator %d has no dense tile geometry", op);
   Resolved r;
   if (int e = resolve_dense(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], &r)) return e;
-  int v[13] = {r.tile_m, r.tile_n, 64, r.G, r.n_comm, r.Tm_p, r.Tn_p, r.n_tiles, r.n_ptm * r.n_ptn, r.expected, r.threads, r.lds_bytes, r.group_m};
+  int v[14] = {r.tile_m, r.tile_n, 64, r.G, r.n_comm, r.Tm_p, r.Tn_p, r.n_tiles, r.n_ptm * r.n_ptn, r.expected, r.threads, r.lds_bytes, r.group_m,
+               r.k_chunks > 0 ? r.k_chunks : 1};
   memcpy(info, v, sizeof v);
   return TL_OK;
 }
@@ -344,7 +386,7 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t*
     if (int e = resolve_dense(ctx, op, (int)dims[0], (int)dims[1], (int)dims[2], &r)) return e;
     *ws_bytes = 256;  // status word (+ padding)
     if (op == TL_OP_AG_GEMM) {
-      *n_flags = (size_t)ctx->cfg.world_size * ctx->cfg.channels_per_rank;
+      *n_flags = (size_t)ctx->cfg.world_size * ctx->cfg.channels_per_rank * r.k_chunks;
     } else {
       size_t tiles_per_seg = (size_t)(r.rows_per_rank / r.Tm_p) * r.n_ptn;
       *n_flags = (size_t)r.n_ptm * r.n_ptn + 2 * (size_t)ctx->cfg.world_size * tiles_per_seg;
@@ -399,6 +441,11 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
   memset(&p, 0, sizeof p);
   fill_ag_producer(ctx, &p.prod, a_shards, a_gathered, K, r.Tm_p, r.Tn_p, r.n_ptm, r.n_ptn, r.rows_per_rank, r.rows_per_channel,
                    flags, epoch, workspace);
+  // the queue hands out the shards in the order in which the GEMM reads them: the owner of the schedule's first row
+  // block first (the local shard under the rotated orders: nothing to copy if it is in place, so its channels are
+  // ready at once), then along the ring
+  p.prod.first_src = r.first_block / (r.nbm / R > 0 ? r.nbm / R : 1) % R;
+  p.prod.k_chunks = r.k_chunks;
   p.b = (const bf16_t*)b;
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;

@@ -95,6 +95,29 @@ __device__ __forceinline__ bool tile_wait(const unsigned* flag, unsigned target,
   return ok;
 }
 
+// tile_wait by all lanes of one wave, with every branch uniform for the compiler too (the polled values go through
+// readfirstlane): for waits inside loops that hold workgroup barriers.  No acquire: the caller fences after the
+// barrier that publishes the wait to the other waves.
+__device__ __forceinline__ void wave_tile_wait(const unsigned* flag, unsigned target, const WaitCtl& ctl, int flag_index) {
+  unsigned long long t0 = 0;
+  const bool timed = ctl.timeout != 0;
+  if (timed) t0 = wall_clock64();
+  for (;;) {
+    unsigned f = __builtin_amdgcn_readfirstlane(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if ((int)(f - target) >= 0) break;
+    __builtin_amdgcn_s_sleep(4);
+    if (timed) {
+      int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      if (st != 0) break;  // abandoned elsewhere
+      if (wall_clock64() - t0 > ctl.timeout) {
+        int expected = 0;  // every lane tries, the first one wins, all carry the same value
+        __hip_atomic_compare_exchange_strong(ctl.status, &expected, 1 + flag_index, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Single-lane atomics without a divergent branch.  A loop whose body holds workgroup barriers
 // must stay uniform for the compiler as well as at run time: with an `if (tid == 0)` around an

@@ -84,6 +84,16 @@ struct DenseRows {
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(c + (long)r * ldc + col) = v; }
 };
 
+// Hook of gemm_tile for A operands that arrive in chunks along K: before the loads of K step `ks` are requested,
+// gemm_tile calls wait(ks) from every thread whenever starts(ks) holds, and acquire() after the barrier that follows.
+// The steps of the pipeline's prologue (ks < NS) are not announced: they belong to what the caller waited for.
+struct NoKWait {
+  static constexpr bool ENABLED = false;
+  __device__ __forceinline__ bool starts(int) const { return false; }
+  __device__ __forceinline__ void wait(int) const {}
+  __device__ __forceinline__ void acquire() const {}
+};
+
 // Computes one output tile.  `a` points at column 0 of the A rows: tile row r is A row r, or A row
 // a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index); `b` points at
 // row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
@@ -91,10 +101,10 @@ struct DenseRows {
 // `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
 // masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
-template <class Cfg, class Out>
+template <class Cfg, class Out, class KW = NoKWait>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
-                                          char* smem) {
+                                          char* smem, const KW& kw = KW{}) {
   constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
@@ -251,9 +261,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     const int nslot = slot + 1 == NS ? 0 : slot + 1;
     const char* nst = smem + nslot * Cfg::STAGE_BYTES;
     const bool more = s + NS < nk;  // a further stage remains to be requested
+    const bool new_chunk = KW::ENABLED && more && kw.starts(s + NS);
+    if (new_chunk) kw.wait(s + NS);
     // stage s+1 must have landed; while requests continue, the NS-2 younger stages may stay in flight
     if (more) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
     __syncthreads();
+    if (new_chunk) kw.acquire();
     slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nst, 0, more, slot);
     static_for<0, SL - 1>([&](auto sl_c) {
       constexpr int S = decltype(sl_c)::value;

@@ -43,6 +43,7 @@ struct Resolved {
   int threads, lds_bytes;
   int first_block;       // rotation of row blocks in the compute order
   int group_m;           // row blocks per group of the compute order
+  int k_chunks;          // AG+GEMM: flags per channel along K (1 = one flag per channel)
 };
 
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r);
@@ -92,6 +93,7 @@ inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const
   p->rows_per_rank = rows_per_rank;
   p->rows_per_channel = rows_per_channel;
   p->local_in_place = (const bf16_t*)shards[cfg.rank] == (const bf16_t*)gathered + (size_t)cfg.rank * rows_per_rank * ld;
+  p->k_chunks = 1;
   p->flags = flags;
   p->ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
   p->ticket_end = epoch * (unsigned)(n_ptm * n_ptn);

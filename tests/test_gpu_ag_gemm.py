@@ -164,6 +164,29 @@ def test_invalid_arguments_are_rejected_before_launch():
     tl.tl_ctx_destroy(ctx)
 
 
+@pytest.mark.parametrize("mode,kc,rank", [("side", 2, 1), ("side", 4, 3), ("waves", 4, 0)])
+def test_k_chunked_channels(mode, kc, rank):
+    """AllGather channels cut into chunks along K, one flag per (channel, chunk): ragged N, several epochs with new data."""
+    w = wl.ag_gemm_inputs(2048, 456, 2048, 4, config_id=15)
+    hs, g, c, flags, info = run_ag_gemm(w, rank, 2, MODES[mode], epochs=3, tile_m=256, tile_n=256, ag_k_chunks=kc, comm_workgroups=8)
+    assert info["k_chunks"] == kc and info["comm_tile_n"] == 2048 // kc
+    check(w, hs, g, c, f"k chunks {kc} {mode}")
+    assert flags.tolist() == [3 * info["expected_per_channel"]] * (4 * 2 * kc)
+
+
+def test_k_chunks_fall_back_and_reject():
+    # another tile shape or binding: one flag per channel, same results
+    w = wl.ag_gemm_inputs(1024, 256, 1024, 4, config_id=16)
+    hs, g, c, flags, info = run_ag_gemm(w, 0, 1, tl.TL_COMM_SIDE_KERNEL, tile_m=128, tile_n=128, ag_k_chunks=2)
+    assert info["k_chunks"] == 1 and len(flags) == 4
+    check(w, hs, g, c, "k chunks with the 128x128 tile")
+    ctx = make_ctx(world_size=4, rank=0, comm_mode=tl.TL_COMM_SIDE_KERNEL, ag_k_chunks=4)
+    with pytest.raises(tl.TileLinkError) as e:
+        tl.tl_query_workspace(ctx, tl.TL_OP_AG_GEMM, [1024, 256, 1024])     # 4 steps of 64 per chunk
+    assert e.value.status == tl.TL_ERR_UNSUPPORTED_SHAPE
+    tl.tl_ctx_destroy(ctx)
+
+
 @pytest.mark.parametrize("mode", ["waves", "side", "stream"])
 def test_full_size_tp8_share(mode):
     """BASELINE configuration 2: 8 shards of [1024,8192], B [8192,3584]; whole output compared.  `side` is the
@@ -178,3 +201,14 @@ def test_full_size_tp8_share(mode):
     assert np.array_equal(g, a_ref)
     rel, mx = assert_close_bf16(c, c_ref, f"cfg2 {mode}")
     print(f"cfg2 {mode}: tile {info['tile_m']}x{info['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")
+
+
+def test_full_size_tp8_share_k_chunks():
+    """The launch configuration bench.py times: side-kernel producers, local shard in place, four chunks along K."""
+    w = wl.ag_gemm_inputs(8192, 3584, 8192, 8, config_id=2)
+    hs, g, c, flags, info = run_ag_gemm(w, 5, 4, tl.TL_COMM_SIDE_KERNEL, epochs=2, in_place=True, tile_order=tl.TL_ORDER_OWN_FIRST, ag_k_chunks=4)
+    assert info["k_chunks"] == 4
+    a_ref, _, c_ref = ops.ag_gemm(hs, w["b"])
+    assert np.array_equal(g, a_ref)
+    assert_close_bf16(c, c_ref, "cfg2 side, 4 K chunks")
+    assert flags.tolist() == [2 * info["expected_per_channel"]] * (8 * 4 * 4)
