@@ -160,6 +160,8 @@ def main():
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--ag-comm-tile-m", type=int, default=0, help="rows of an AllGather producer tile (default: the library's choice)")
     ap.add_argument("--ag-k-chunks", type=int, default=1, help="chunks per AllGather channel along K, each with a flag of its own (1 = one flag per channel)")
+    ap.add_argument("--link-gbps", type=int, default=0, help="simulated link rate per source rank for the AllGather (0 = unthrottled local copy; xGMI: 153)")
+    ap.add_argument("--ag-order", default="own_first", choices=["own_first", "arrival"], help="tile order of AG+GEMM")
     ap.add_argument("--ag-tile", default="", help="compute tile of AG+GEMM as MxN (default: the library's choice)")
     ap.add_argument("--rs-tile", default="", help="compute tile of GEMM+RS as MxN (default: the library's choice)")
     ap.add_argument("--direct-push-mode", type=int, default=1, choices=[1, 2],
@@ -229,7 +231,9 @@ def main():
             self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
                                         comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
                                         ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
-                                        comm_workgroups=args.comm_workgroups, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                                        link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
+                                        comm_workgroups=args.comm_workgroups, xcd_swizzle=1,
+                                        tile_order=tl.TL_ORDER_ARRIVAL if op == tl.TL_OP_AG_GEMM and args.ag_order == "arrival" else tl.TL_ORDER_OWN_FIRST,
                                         spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else args.direct_push_mode)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
@@ -318,7 +322,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "MLP-5 TP=8 share: AG+GEMM 8x[1024,8192]->[8192,8192]x[8192,3584] then GEMM+RS [8192,3584]x[3584,8192]->[1024,8192]",
                    "world_size": R, "rank": rank, "comm_mode": args.comm_mode, "channels_per_rank": args.channels,
-                   "rs_direct_push": 0 if args.no_direct_push else args.direct_push_mode, "ag_k_chunks": args.ag_k_chunks},
+                   "rs_direct_push": 0 if args.no_direct_push else args.direct_push_mode, "ag_k_chunks": args.ag_k_chunks, "ag_order": args.ag_order, "link_gbps": args.link_gbps},
         "overlap_efficiency": round(min(res["ag_gemm"]["overlap_efficiency"], res["gemm_rs"]["overlap_efficiency"]), 4),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "ops": res,

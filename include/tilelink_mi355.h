@@ -60,7 +60,11 @@ enum { TL_COMM_NONE = 0,   /* data already in place: no producer runs, consumers
 enum { TL_ORDER_NATURAL = 0, /* row-major over (row block, column block) */
        TL_ORDER_RING = 1,    /* row blocks rotated by owner rank: AG+GEMM starts with the local
                                 shard's rows, GEMM+RS starts with rank r+1's segment and ends with its own */
-       TL_ORDER_OWN_FIRST = 2 /* as RING, but GEMM+RS starts with its own segment and then follows the ring */ };
+       TL_ORDER_OWN_FIRST = 2, /* as RING, but GEMM+RS starts with its own segment and then follows the ring */
+       TL_ORDER_ARRIVAL = 3    /* tl_ag_gemm: the local shard's row blocks, then row block j of every other rank along
+                                  the ring before row block j+1 of any -- the order in which links that run side by
+                                  side deliver -- and the producer queue in the same order (needs whole row blocks per
+                                  rank, else RING).  The other operators treat it as OWN_FIRST. */ };
 
 /* Operators, for tl_query_workspace / tl_dump_schedule. */
 enum { TL_OP_AG_GEMM = 0, TL_OP_GEMM_RS = 1, TL_OP_MOE_AG_GATHER_GEMM = 2, TL_OP_MOE_GEMM_SCATTER_RS = 3,
@@ -101,6 +105,11 @@ typedef struct tl_config {
                               "tile size" sub-space, applied along K).  Needs K divisible by 64*ag_k_chunks with at
                               least 8 K steps of 64 per chunk, comm_tile_n 0, and TL_COMM_WAVES or TL_COMM_SIDE_KERNEL
                               with the 256x256 compute tile; elsewhere, and for 0 or 1, one flag per channel. */
+  int link_gbps;           /* AllGather operators: 0 = the producers copy as fast as they can.  > 0 = simulated links: every
+                              other rank's shard arrives at this many GB/s (decimal), all ranks side by side, starting
+                              when the call's first producer starts; a producer tile of a remote shard is not copied
+                              before its last byte would have arrived, and the queue takes row tile j of every remote
+                              rank before row tile j+1 of any.  xGMI: 153.  Results are unchanged. */
 } tl_config;
 
 typedef struct tl_ctx tl_ctx;

@@ -67,13 +67,29 @@ def consumer_tile(tile_id_c: int, M: int, N: int, R: int, C: int, Tm_c: int, Tn_
 # position p.  Workgroup w of a grid of G takes positions w, w+G, w+2G, ...
 # ---------------------------------------------------------------------------
 
-def logical_order(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, group_m: int = 1):
+def arrival_rows(nbm: int, R: int, first_rank: int):
+    """Row blocks in the order in which they are complete when every other
+    rank sends its shard over a link of its own, all links side by side: the
+    blocks of `first_rank` (the local shard, nothing to send), then block j of
+    first_rank+1, first_rank+2, ... before block j+1 of any."""
+    bpr = nbm // R
+    rows = [first_rank * bpr + j for j in range(bpr)]
+    for j in range(bpr):
+        for q in range(1, R):
+            rows.append(((first_rank + q) % R) * bpr + j)
+    return rows
+
+
+def logical_order(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, group_m: int = 1, arrival: bool = False):
     """Row-blocks in natural order, or rotated so that the row-blocks owned by
-    `first_rank` come first and the other ranks follow in ring order.  The
-    (rotated) row blocks are taken in groups of `group_m`; inside a group all
-    row blocks of one column block come before the next column block."""
+    `first_rank` come first and the other ranks follow in ring order, or (with
+    `arrival`, if R divides nbm and R > 1) in arrival order.  The row blocks
+    are then taken in groups of `group_m`; inside a group all row blocks of
+    one column block come before the next column block."""
     blocks_per_rank = nbm // R if rotate else 0
     rows = [(i + first_rank * blocks_per_rank) % nbm if rotate else i for i in range(nbm)]
+    if arrival and rotate and nbm % R == 0 and R > 1:
+        rows = arrival_rows(nbm, R, first_rank)
     order = []
     for start in range(0, nbm, group_m):
         group = rows[start:start + group_m]
@@ -101,20 +117,20 @@ def xcd_positions(n_tiles: int, G: int):
     return pos
 
 
-def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool, group_m: int = 1):
+def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool, group_m: int = 1, arrival: bool = False):
     """Output-tile id at every schedule position."""
-    logical = logical_order(nbm, nbn, R, first_rank, rotate, group_m)
+    logical = logical_order(nbm, nbn, R, first_rank, rotate, group_m, arrival)
     n = nbm * nbn
     pos = xcd_positions(n, G) if swizzle else list(range(n))
     return [logical[pos[p]] for p in range(n)]
 
 
-def ag_gemm_schedule_records(M, N, K, R, C, rank, Tm_c, Tn_c, G, rotate=True, swizzle=True, group_m=1):
+def ag_gemm_schedule_records(M, N, K, R, C, rank, Tm_c, Tn_c, G, rotate=True, swizzle=True, group_m=1, arrival=False):
     """One 8-int record per schedule position:
     (tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0)."""
     nbm, nbn = ceil_div(M, Tm_c), ceil_div(N, Tn_c)
     recs = []
-    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle, group_m):
+    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle, group_m, arrival):
         bm, bn, lo, hi, clo, chi = consumer_tile(t, M, N, R, C, Tm_c, Tn_c)
         recs.append((t, bm, bn, lo, hi, clo, chi, 0))
     return recs

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
 
 TL_OK, TL_ERR_INVALID_ARG, TL_ERR_UNSUPPORTED_SHAPE, TL_ERR_WORKSPACE_TOO_SMALL, TL_ERR_HIP, TL_ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
 TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_EXTERNAL = 0, 1, 2, 3, 4
-TL_ORDER_NATURAL, TL_ORDER_RING, TL_ORDER_OWN_FIRST = 0, 1, 2
+TL_ORDER_NATURAL, TL_ORDER_RING, TL_ORDER_OWN_FIRST, TL_ORDER_ARRIVAL = 0, 1, 2, 3
 TL_OP_AG_GEMM, TL_OP_GEMM_RS, TL_OP_MOE_AG_GATHER_GEMM, TL_OP_MOE_GEMM_SCATTER_RS, TL_OP_SP_AG_ATTENTION = 0, 1, 2, 3, 4
 
 
@@ -37,7 +37,7 @@ class tl_config(ctypes.Structure):
                 ("comm_tile_n", ctypes.c_int), ("comm_mode", ctypes.c_int), ("comm_workgroups", ctypes.c_int),
                 ("compute_workgroups", ctypes.c_int), ("tile_order", ctypes.c_int), ("xcd_swizzle", ctypes.c_int),
                 ("group_m", ctypes.c_int), ("spin_timeout_us", ctypes.c_uint), ("comm_alone", ctypes.c_int),
-                ("rs_direct_push", ctypes.c_int), ("ag_k_chunks", ctypes.c_int)]
+                ("rs_direct_push", ctypes.c_int), ("ag_k_chunks", ctypes.c_int), ("link_gbps", ctypes.c_int)]
 
 
 if not os.path.exists(LIB_PATH):

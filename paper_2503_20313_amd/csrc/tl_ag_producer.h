@@ -18,6 +18,14 @@ struct AgProducer {
   int k_chunks;                     // 1: one flag per channel.  > 1: n_ptn == k_chunks column tiles, one flag per (channel,
                                     // column tile) at flags[channel*k_chunks + tn], and the queue hands out column tile 0
                                     // of every row tile before column tile 1 (a consumer can start on the first K chunk)
+  int interleave;                   // 0: the queue takes one source rank after the other.  1: the shard of first_src goes first
+                                    // as a whole (the local one under the rotated orders); then row tile j of every other
+                                    // rank comes before row tile j+1 of any, the order in which concurrent links deliver.
+                                    // Needs at least two source ranks in the queue.
+  unsigned pace_q8;                 // 0, or 256 x the ticks of the 100 MHz clock a link needs for one producer tile: a tile of
+                                    // a remote shard is then not copied before its last byte would have arrived
+  unsigned long long* pace_word;    // (epoch tag << 40 | start time) of the call in flight, set by its first producer
+  unsigned epoch;
   unsigned wait_target;             // epoch * expected
   unsigned* flags;                  // [R*C*k_chunks]
   unsigned* ticket;                 // producer-tile queue head (grows by n_ptm*n_ptn per call)
@@ -33,6 +41,32 @@ struct AgProducer {
 // workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
 // too instead of idling, so a consumer can never wait for a producer that is not resident.
 // ======================================================================================
+// A 64-bit value every lane holds alike, as a wave-uniform value for the compiler too.
+__device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
+  // the builtin returns int: through unsigned first, or a low word with its top bit set would sign-extend over the high word
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)v), hi = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (unsigned long long)lo | ((unsigned long long)hi << 32);
+}
+
+// Start time of the call in flight on the 100 MHz clock (low 40 bits), agreed on by all producers: the first one to
+// find another call's tag in the word replaces it with this call's tag and its own clock reading.  One lane of wave 0
+// of a workgroup tries the compare-and-swap (whichever workgroup's lands first wins); everybody then reads the word
+// until it carries this call's tag.  Every branch is wave-uniform for the compiler too.
+__device__ __forceinline__ unsigned long long pace_start(const AgProducer& p) {
+  const unsigned long long mask40 = (1ull << 40) - 1, tag = (unsigned long long)(p.epoch & 0xffffffu) << 40;
+  unsigned long long cur = uniform64(__hip_atomic_load(p.pace_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  if ((cur & ~mask40) != tag) {
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0) lane0_cas64(p.pace_word, cur, tag | ((unsigned long long)wall_clock64() & mask40));
+    // bounded: a caller that lets two calls share the workspace at the same time gets no pacing rather than a hang
+    int tries = 0;
+    do {
+      cur = uniform64(__hip_atomic_load(p.pace_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    } while ((cur & ~mask40) != tag && ++tries < 4096);
+    if ((cur & ~mask40) != tag) cur = 0;  // "started long ago": every tile is due
+  }
+  return cur & mask40;
+}
+
 // Called by every lane of one wave; the result is wave-uniform.
 __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out) {
   const unsigned count = (unsigned)(p.n_ptm * p.n_ptn);
@@ -56,11 +90,28 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
   int tmi, tn;
   if (p.k_chunks > 1) { tn = i / p.n_ptm; tmi = i - tn * p.n_ptm; }
   else { tmi = i / p.n_ptn; tn = i - tmi * p.n_ptn; }
-  int tm = tmi + p.first_src * ptm_per_rank;  // ring order over source ranks: first_src, first_src+1, ...
-  if (tm >= p.n_ptm_all) tm -= p.n_ptm_all;
+  int tm;
+  if (p.interleave && tmi >= ptm_per_rank) {
+    const int others = p.n_ptm / ptm_per_rank - 1;
+    int r = tmi - ptm_per_rank, jm = r / others, s = r - jm * others;
+    int q = p.first_src + 1 + s;
+    if (q >= p.R) q -= p.R;
+    tm = q * ptm_per_rank + jm;
+  } else {
+    tm = tmi + p.first_src * ptm_per_rank;  // ring order over source ranks: first_src, first_src+1, ...
+    if (tm >= p.n_ptm_all) tm -= p.n_ptm_all;
+  }
   int row_lo = tm * p.Tm_p;
   int src = tm / ptm_per_rank;                       // f_R
   int channel = tm / (p.rows_per_channel / p.Tm_p);  // f_C
+  if (p.pace_q8 && src != p.rank) {
+    // the links of all source ranks run side by side; this tile is number `nth` of what its rank sends
+    const int jm = tm - src * ptm_per_rank;
+    const int nth = p.k_chunks > 1 ? tn * ptm_per_rank + jm : jm * p.n_ptn + tn;
+    const unsigned long long due = ((unsigned long long)(nth + 1) * p.pace_q8) >> 8;
+    const unsigned long long t0 = pace_start(p);
+    while ((((unsigned long long)wall_clock64() - t0) & ((1ull << 40) - 1)) < due) __builtin_amdgcn_s_sleep(8);
+  }
   if (!(src == p.rank && p.local_in_place)) {
     const bf16_t* s = p.shards[src] + (long)(row_lo - src * p.rows_per_rank) * p.ld + (long)tn * p.Tn_p;
     bf16_t* d = p.gathered + (long)row_lo * p.ld + (long)tn * p.Tn_p;
@@ -102,12 +153,26 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
   {
     const int tpc = p.rows_per_channel / p.Tm_p, ptm_per_rank = p.rows_per_rank / p.Tm_p;
     for (unsigned long long m = chan_mask; m; m &= m - 1) {
-      int qi = __builtin_ctzll(m) * tpc - p.first_src * ptm_per_rank;  // queue position of the channel's first row tile
-      if (qi < 0) qi += p.n_ptm_all;
-      int end = p.k_chunks > 1 ? qi + tpc : (qi + tpc) * p.n_ptn;  // with K chunks: the channel's tiles of chunk 0
+      int qi, qn;  // queue position (in row tiles) of the channel's first row tile, and of the one after its last
+      const int ch0 = __builtin_ctzll(m), cpr = ptm_per_rank / tpc;
+      if (p.interleave && ch0 / cpr != p.first_src) {
+        const int others = p.n_ptm / ptm_per_rank - 1, c = ch0 % cpr;
+        int s = ch0 / cpr - p.first_src - 1;
+        if (s < 0) s += p.R;
+        qi = ptm_per_rank + c * tpc * others + s;
+        qn = ptm_per_rank + ((c + 1) * tpc - 1) * others + s + 1;
+      } else {
+        qi = __builtin_ctzll(m) * tpc - p.first_src * ptm_per_rank;
+        if (qi < 0) qi += p.n_ptm_all;
+        qn = qi + tpc;
+      }
+      int end = p.k_chunks > 1 ? qn : qn * p.n_ptn;  // with K chunks: the channel's tiles of chunk 0
       limit = end > limit ? end : limit;
     }
   }
+  // With simulated links a ticket is a tile that may not be due for a long time: a consumer that took one would sleep on
+  // it while its own rows arrive, and more workers do not make a link faster.  It only waits.
+  if (p.pace_q8) limit = 0;
   const unsigned queue_begin = p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn);
   for (;;) {
     if (wave == 0) {

@@ -437,6 +437,7 @@ int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, 
   p.kprod.first_src = 0; p.vprod.first_src = 0;
   p.kprod.n_ptm_all = p.vprod.n_ptm_all = R * (r.S_loc / r.Tm_p);
   p.vprod.ticket = (unsigned*)workspace + 2;  // word 1: K queue, word 2: V queue
+  p.kprod.pace_q8 *= 2; p.vprod.pace_q8 *= 2;  // K and V of a rank share its link
   p.kprod.wait_target = p.vprod.wait_target = epoch * (unsigned)r.expected;
   p.q = (const bf16_t*)q;
   p.o = (bf16_t*)o;

@@ -187,7 +187,7 @@ int fail(int code, const char* fmt, ...) {
 // Segment whose rows GEMM+ReduceScatter computes first: the next rank's in ring order (its own comes last,
 // as in a ring reduce-scatter), or its own (so that the reduction of the own segment, the heaviest piece of
 // the communication side, overlaps the remaining GEMM tiles and only a push is left at the end).
-static int rs_first_rank(const tl_config& c) { return c.tile_order == TL_ORDER_OWN_FIRST ? c.rank : (c.rank + 1) % c.world_size; }
+static int rs_first_rank(const tl_config& c) { return c.tile_order >= TL_ORDER_OWN_FIRST ? c.rank : (c.rank + 1) % c.world_size; }
 
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
   const tl_config& c = ctx->cfg;
@@ -254,7 +254,11 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     int Tm_p = c.comm_tile_m;
     if (Tm_p == 0) {
       Tm_p = r->rows_per_channel;
-      while (Tm_p > 32 && Tm_p % 2 == 0) Tm_p /= 2;  // small row tiles: many producer tiles per channel keeps all copy workgroups busy
+      // small row tiles: many producer tiles per channel keeps all copy workgroups busy.  With simulated links only the
+      // tiles that are due are being copied, a handful at a time and each by one workgroup at the pace of its own memory
+      // latency: smaller tiles keep that copy short against the time the link takes for the tile.
+      const int floor_rows = c.link_gbps > 0 ? 8 : 32;
+      while (Tm_p > floor_rows && Tm_p % 2 == 0) Tm_p /= 2;
       if (r->rows_per_channel % Tm_p) Tm_p = r->rows_per_channel;
     }
     if (Tm_p <= 0 || r->rows_per_channel % Tm_p)
@@ -273,7 +277,8 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
         Tn_p = K / r->k_chunks;
         if (c.comm_tile_m == 0) {
           // fewer, taller producer tiles: a tile is as many bytes as without chunks
-          while (Tm_p * 2 <= r->rows_per_channel && r->rows_per_channel % (Tm_p * 2) == 0 && Tm_p * 2 <= 32 * r->k_chunks) Tm_p *= 2;
+          const int cap = (c.link_gbps > 0 ? 8 : 32) * r->k_chunks;
+          while (Tm_p * 2 <= r->rows_per_channel && r->rows_per_channel % (Tm_p * 2) == 0 && Tm_p * 2 <= cap) Tm_p *= 2;
         }
       }
     }
@@ -285,6 +290,8 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
     r->first_block = 0;
     if (c.tile_order != TL_ORDER_NATURAL) {
       if (r->nbm % R == 0) r->first_block = c.rank * (r->nbm / R);
+      // arrival order needs whole row blocks per rank; else it is the ring
+      if (c.tile_order == TL_ORDER_ARRIVAL && r->nbm % R == 0 && R > 1) r->arrival_bpr = r->nbm / R;
     }
   } else {
     int Tm_r = c.comm_tile_m ? c.comm_tile_m : (r->tile_m <= r->rows_per_rank ? r->tile_m : r->rows_per_rank);
@@ -311,6 +318,7 @@ static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
   s.first_block = r.first_block;
   s.swizzle = ctx->cfg.xcd_swizzle;
   s.group_m = r.group_m;
+  s.arrival_bpr = r.arrival_bpr;
   return s;
 }
 
@@ -345,7 +353,8 @@ int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
   if (cfg->rank < 0 || cfg->rank >= cfg->world_size) return fail(TL_ERR_INVALID_ARG, "rank %d outside [0,%d)", cfg->rank, cfg->world_size);
   if (cfg->channels_per_rank < 1) return fail(TL_ERR_INVALID_ARG, "channels_per_rank must be >= 1");
   if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_EXTERNAL) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
-  if (cfg->tile_order < TL_ORDER_NATURAL || cfg->tile_order > TL_ORDER_OWN_FIRST) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
+  if (cfg->tile_order < TL_ORDER_NATURAL || cfg->tile_order > TL_ORDER_ARRIVAL) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
+  if (cfg->link_gbps < 0) return fail(TL_ERR_INVALID_ARG, "link_gbps must not be negative");
   if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0 || cfg->group_m < 0)
     return fail(TL_ERR_INVALID_ARG, "negative workgroup count or tile size");
   int dev = 0;
@@ -446,6 +455,7 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
   // ready at once), then along the ring
   p.prod.first_src = r.first_block / (r.nbm / R > 0 ? r.nbm / R : 1) % R;
   p.prod.k_chunks = r.k_chunks;
+  if (r.arrival_bpr) p.prod.interleave = 1;  // the queue follows the order in which the GEMM reads
   p.b = (const bf16_t*)b;
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;

@@ -143,6 +143,22 @@ __device__ __forceinline__ unsigned lane0_fetch_add(unsigned* ptr, unsigned v) {
   return __builtin_amdgcn_readfirstlane(r);
 }
 
+// 64-bit compare-and-swap by lane 0, no result: *ptr = desired if *ptr == expected.  Complete when it returns.
+__device__ __forceinline__ void lane0_cas64(unsigned long long* ptr, unsigned long long expected, unsigned long long desired) {
+  typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+  const u64x2 data = {desired, expected};  // the instruction takes the new value in the low half, the comparand in the high half
+  unsigned long long saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, 1\n\t"
+      "global_atomic_cmpswap_x2 %1, %2, off sc1\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "v"(ptr), "v"(data)
+      : "memory");
+}
+
 __device__ __forceinline__ void lane0_add(unsigned* ptr, unsigned v) {
   unsigned long long saved;
   asm volatile(
@@ -174,6 +190,8 @@ struct Sched {
   int first_block;  // rotation of row blocks (0 = natural)
   int swizzle;
   int group_m;      // >= 1
+  int arrival_bpr;  // 0, or the row blocks per rank: after the bpr blocks from first_block on (the local shard's), block j
+                    // of each further rank along the ring comes before block j+1 of any
 };
 
 // Die swizzle alone: the logical index of schedule position p.
@@ -209,7 +227,14 @@ __host__ __device__ inline int sched_tile(const Sched& s, int p) {
   if (gsz > s.group_m) gsz = s.group_m;
   int bn = within / gsz;
   int i = g * s.group_m + (within - bn * gsz);
-  int bm = i + s.first_block;
+  int bm;
+  if (s.arrival_bpr && i >= s.arrival_bpr) {
+    const int others = s.nbm / s.arrival_bpr - 1;
+    int r = i - s.arrival_bpr, j = r / others, q = r - j * others;
+    bm = s.first_block + (q + 1) * s.arrival_bpr + j;
+  } else {
+    bm = i + s.first_block;
+  }
   if (bm >= s.nbm) bm -= s.nbm;
   return bm * s.nbn + bn;
 }

@@ -44,6 +44,7 @@ struct Resolved {
   int first_block;       // rotation of row blocks in the compute order
   int group_m;           // row blocks per group of the compute order
   int k_chunks;          // AG+GEMM: flags per channel along K (1 = one flag per channel)
+  int arrival_bpr;       // AG+GEMM under TL_ORDER_ARRIVAL: row blocks per rank (0 = another order)
 };
 
 int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r);
@@ -94,6 +95,11 @@ inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const
   p->rows_per_channel = rows_per_channel;
   p->local_in_place = (const bf16_t*)shards[cfg.rank] == (const bf16_t*)gathered + (size_t)cfg.rank * rows_per_rank * ld;
   p->k_chunks = 1;
+  // simulated links: all source ranks deliver side by side, each at link_gbps
+  p->interleave = (cfg.link_gbps > 0 && n_ptm / (rows_per_rank / Tm_p) > 1) ? 1 : 0;
+  p->pace_q8 = cfg.link_gbps > 0 ? (unsigned)((double)Tm_p * Tn_p * sizeof(bf16_t) * 256.0 / (cfg.link_gbps * 10.0) + 0.5) : 0;
+  p->pace_word = (unsigned long long*)((char*)workspace + 16);
+  p->epoch = epoch;
   p->flags = flags;
   p->ticket = (unsigned*)workspace + 1;  // word 0 of the workspace is the status word
   p->ticket_end = epoch * (unsigned)(n_ptm * n_ptn);

@@ -571,7 +571,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
   // stage B raises one notification per reduce tile: for the RS consumer the "producer tile" is the reduce tile itself
   fill_rs_side(ctx, &p.rs, partial, peer_recv, peer_push, out, T, H, r.Tt, r.tile_n, r.Tt, r.tile_n, flags + (size_t)ntb * r.nbn, epoch, workspace);
   if (cfg.tile_order != TL_ORDER_NATURAL) {
-    int first = cfg.tile_order == TL_ORDER_OWN_FIRST ? cfg.rank : (cfg.rank + 1) % R;
+    int first = cfg.tile_order >= TL_ORDER_OWN_FIRST ? cfg.rank : (cfg.rank + 1) % R;
     p.rs.rs_first_block = first * (T / R / r.Tt);
   }
   if (p.rs.direct == 2) p.rs.direct = 1;  // the own segment is reduced by stage C here (stage B has no peer data at hand)

@@ -153,6 +153,58 @@ def test_schedule_dump_matches_mapping_oracle(rank, order, swz, gm):
     tl.tl_ctx_destroy(ctx)
 
 
+@pytest.mark.parametrize("rank,gm", [(5, 0), (0, 1), (7, 2)])
+def test_arrival_order_schedule_matches_mapping_oracle(rank, gm):
+    M, N, K, R, C = 8192, 3584, 8192, 8, 4
+    ctx = make_ctx(world_size=R, rank=rank, channels_per_rank=C, tile_order=tl.TL_ORDER_ARRIVAL, xcd_swizzle=1, group_m=gm)
+    info = tl.tl_resolve(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
+    got = tl.tl_dump_schedule(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
+    want = omap.ag_gemm_schedule_records(M, N, K, R, C, rank, info["tile_m"], info["tile_n"], info["compute_workgroups"],
+                                         rotate=True, swizzle=True, group_m=info["group_m"], arrival=True)
+    assert got == [v for rec in want for v in rec]
+    tl.tl_ctx_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode,order,kc", [("side", tl.TL_ORDER_ARRIVAL, 1), ("waves", tl.TL_ORDER_ARRIVAL, 2), ("side", tl.TL_ORDER_RING, 1)])
+def test_arrival_order_and_paced_links(mode, order, kc):
+    """Arrival tile order with the interleaved producer queue, with and without simulated links: same results, same
+    flags.  400 GB/s per link: a 1 MiB shard takes 2.6 us, the call stays short."""
+    w = wl.ag_gemm_inputs(2048, 456, 1024, 4, config_id=17)
+    for gbps in (0, 400):
+        hs, g, c, flags, info = run_ag_gemm(w, 2, 2, MODES[mode], epochs=2, tile_m=256, tile_n=256, tile_order=order, ag_k_chunks=kc,
+                                            link_gbps=gbps, comm_workgroups=8)
+        check(w, hs, g, c, f"order {order} {mode} k chunks {kc} links {gbps} GB/s")
+        assert flags.tolist() == [2 * info["expected_per_channel"]] * (4 * 2 * info["k_chunks"])
+
+
+def test_paced_links_take_the_time_of_the_link():
+    """Producers alone, 8 ranks, shards of 4 MiB at 50 GB/s per link: the gather may not finish before 4 MiB / 50 GB/s
+    = 84 us have passed (all links run side by side), and does not take several times that either."""
+    R, M, N, K = 8, 2048, 256, 8192
+    w = wl.ag_gemm_inputs(M, N, K, R, config_id=18)
+    ctx = make_ctx(world_size=R, rank=3, channels_per_rank=2, comm_mode=tl.TL_COMM_SIDE_KERNEL, comm_alone=1, link_gbps=50, tile_m=256, tile_n=256)
+    ws_bytes, n_flags = tl.tl_query_workspace(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
+    shards = [up(s) for s in w["a_shards"]]
+    gathered, b, c = poison((M, K)), up(w["b"]), poison((M, N))
+    flags = torch.zeros(n_flags, dtype=torch.int32, device=dev())
+    wsp = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=dev())
+    comm = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    times = []
+    for epoch in (1, 2, 3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(comm)
+        tl.tl_ag_gemm(ctx, shards, gathered, b, c, M, N, K, flags, epoch, wsp, ws_bytes, torch.cuda.current_stream(), comm)
+        e1.record(comm)
+        torch.cuda.synchronize()
+        tl.tl_check_status(ctx, wsp)
+        times.append(e0.elapsed_time(e1) * 1e3)
+    tl.tl_ctx_destroy(ctx)
+    assert np.array_equal(down(gathered), np.concatenate(w["a_shards"]))
+    link_us = (M // R) * K * 2 / 50e9 * 1e6
+    assert all(link_us * 0.98 <= t <= link_us * 2.5 for t in times), (times, link_us)
+
+
 def test_invalid_arguments_are_rejected_before_launch():
     ctx = make_ctx(world_size=4, rank=1, channels_per_rank=3)
     for dims in ([1023, 512, 512], [1024, 512, 100], [1024, 513, 512], [1024, 512, 512]):   # R∤M, K%64, N%8, C∤M/R

@@ -129,6 +129,28 @@ def test_grouped_order_hand_example():
         assert sorted(mp.logical_order(7, 5, 1, 0, False, gm)) == list(range(35))
 
 
+def test_arrival_order_pins():
+    """Hand example and invariants of the arrival order (links of all ranks deliver side by side)."""
+    # 3 ranks x 2 row blocks, rank 1 local: its blocks 2,3; then block 0 of ranks 2 and 0 (4, 0), then block 1 (5, 1)
+    assert mp.arrival_rows(6, 3, 1) == [2, 3, 4, 0, 5, 1]
+    assert mp.logical_order(6, 1, 3, 1, True, 1, True) == [2, 3, 4, 0, 5, 1]
+    # falls back to the ring when a rank does not own whole row blocks, and to natural order without rotation
+    assert mp.logical_order(5, 1, 2, 1, True, 1, True) == mp.logical_order(5, 1, 2, 1, True, 1, False)
+    assert mp.logical_order(6, 1, 3, 1, False, 1, True) == [0, 1, 2, 3, 4, 5]
+    for nbm, R, rank in [(32, 8, 5), (8, 8, 0), (12, 4, 3), (16, 2, 1)]:
+        rows = mp.arrival_rows(nbm, R, rank)
+        bpr = nbm // R
+        assert sorted(rows) == list(range(nbm))
+        assert all(r // bpr == rank for r in rows[:bpr])                      # the local shard first
+        rest = rows[bpr:]
+        assert [r % bpr for r in rest] == sorted(r % bpr for r in rest)        # block j of every rank before block j+1 of any
+        for j in range(bpr):                                                   # inside a round: ring order from rank+1
+            assert [r // bpr for r in rest[j * (R - 1):(j + 1) * (R - 1)]] == [(rank + q) % R for q in range(1, R)]
+    # with grouping and the die swizzle it stays a permutation of all tiles
+    sch = mp.tile_schedule(32, 14, 8, 5, True, 256, True, 4, True)
+    assert sorted(sch) == list(range(32 * 14))
+
+
 def test_rs_own_first_order():
     recs = mp.gemm_rs_schedule_records(1024, 512, 64, 4, 1, 256, 256, 128, 128, 8, True, False, 1, True)
     assert [r[1] for r in recs] == [1, 1, 2, 2, 3, 3, 0, 0]            # own segment (rank 1), then the ring 2, 3, 0
