@@ -152,6 +152,21 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards /*host array of dev*/, v
                void* c, int M, int N, int K, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/,
                size_t ws_bytes, void* compute_stream, void* comm_stream);
 
+/* The first half of the MLP layer with its activation folded into the GEMM's epilogue (paper, evaluation, "MLP
+ * Layer": AllGather + GEMM, then an activation layer such as SiLUMul or GeLUMul, then GEMM + ReduceScatter):
+ *   Y = act(A_gathered . W_gate) * (A_gathered . W_up),   SiLUMul: act(g) = g / (1 + exp(-g));  GeLUMul: act(g) =
+ *   g * Phi(g) with the exact normal distribution function; applied to the unrounded fp32 accumulators, rounded once.
+ * b_gate_up [K, 2F] row-major (device) holds both projections side by side in blocks of 32 columns: column 64t + j is
+ * gate feature 32t + j for j < 32 and up feature 32t + j - 32 for 32 <= j < 64 (the two values of a feature then sit
+ * in one lane's accumulators).  y [M, F] row-major (device).  F % 32 == 0.  Everything else -- shards, gathered buffer,
+ * flags, epochs, workspace, streams, bindings, errors -- as tl_ag_gemm with N = 2F (tl_query_workspace, tl_resolve and
+ * tl_dump_schedule with dims {M, 2F, K}); the 224-wide compute tile is not available. */
+enum { TL_ACT_SILU_MUL = 1, TL_ACT_GELU_MUL = 2 };
+int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards /*host array of R device ptrs*/, void* a_gathered /*device*/,
+                       const void* b_gate_up /*device*/, void* y /*device*/, int M, int F, int K, int act,
+                       unsigned* flags /*device*/, unsigned epoch, void* workspace /*device*/, size_t ws_bytes,
+                       void* compute_stream /*hipStream_t*/, void* comm_stream /*hipStream_t*/);
+
 /*
  * GEMM + ReduceScatter (paper: "Kernel Design", GEMM + ReduceScatter; evaluation: scatter by
  * copy, reduction on compute cores).  partial[M,N] = bf16(A[M,K] . B[K,N]) is stored locally and each

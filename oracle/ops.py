@@ -42,6 +42,32 @@ def ag_gemm(a_shards, b):
     return a, c, round_to_bf16(c)
 
 
+def act_mul(gate, up, act):
+    """The activation layer between the two halves of the MLP layer (paper,
+    evaluation, "MLP Layer": SiLUMul or GeLUMul), elementwise in float64:
+    "silu": gate * sigmoid(gate) * up;  "gelu": gate * Phi(gate) * up with Phi
+    the standard normal distribution function."""
+    from scipy.special import erf
+    gate = np.asarray(gate, dtype=np.float64)
+    up = np.asarray(up, dtype=np.float64)
+    if act == "silu":
+        return gate / (1.0 + np.exp(-gate)) * up
+    if act == "gelu":
+        return gate * 0.5 * (1.0 + erf(gate / np.sqrt(2.0))) * up
+    raise ValueError(act)
+
+
+def ag_gemm_act_mul(a_shards, w_gate, w_up, act):
+    """Y = act(A . W_gate) * (A . W_up) with A = AllGather_M(A_shards), both
+    weights [K, F].  The activation is applied to the unrounded products (a
+    kernel that folds it into the GEMM never stores them), so Y is rounded once.
+
+    Returns (gathered A bits [M,K], Y float64 [M,F], Y bf16 bits [M,F])."""
+    a = all_gather_rows(a_shards)
+    y = act_mul(widen(a) @ widen(w_gate), widen(a) @ widen(w_up), act)
+    return a, y, round_to_bf16(y)
+
+
 # ---------------------------------------------------------------------------
 # GEMM + ReduceScatter   (tensor-parallel FFN, second half)
 # ---------------------------------------------------------------------------

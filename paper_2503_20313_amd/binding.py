@@ -14,7 +14,7 @@ try:
     # its own copy of the runtime: loading torch first makes the dynamic loader resolve this library against that copy.
     import torch  # noqa: F401
 except ImportError:
-    pass
+    torch = None
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
 TL_OK, TL_ERR_INVALID_ARG, TL_ERR_UNSUPPORTED_SHAPE, TL_ERR_WORKSPACE_TOO_SMALL, TL_ERR_HIP, TL_ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
 TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_EXTERNAL = 0, 1, 2, 3, 4
 TL_ORDER_NATURAL, TL_ORDER_RING, TL_ORDER_OWN_FIRST, TL_ORDER_ARRIVAL = 0, 1, 2, 3
+TL_ACT_SILU_MUL, TL_ACT_GELU_MUL = 1, 2
 TL_OP_AG_GEMM, TL_OP_GEMM_RS, TL_OP_MOE_AG_GATHER_GEMM, TL_OP_MOE_GEMM_SCATTER_RS, TL_OP_SP_AG_ATTENTION = 0, 1, 2, 3, 4
 
 
@@ -55,6 +56,7 @@ _lib.tl_check_status.argtypes = [_vp, _vp]
 _lib.tl_resolve.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i)]
 _lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i), _sz, ctypes.POINTER(_sz)]
 _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_ag_gemm_act_mul.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_rs.argtypes = [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 
 _ip, _fp = ctypes.c_void_p, ctypes.c_void_p
@@ -153,6 +155,24 @@ def tl_dump_schedule(ctx, op, dims):
 def tl_ag_gemm(ctx, a_shards, a_gathered, b, c, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
     _check(_lib.tl_ag_gemm(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr(b), _ptr(c), M, N, K, _ptr(flags), epoch,
                            _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_ag_gemm_act_mul(ctx, a_shards, a_gathered, b_gate_up, y, M, F, K, act, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_ag_gemm_act_mul(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr(b_gate_up), _ptr(y), M, F, K, act, _ptr(flags), epoch,
+                                   _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def pack_gate_up(w_gate, w_up):
+    """[K, F] gate and up weights (numpy arrays or torch tensors of one dtype) -> the [K, 2F] layout tl_ag_gemm_act_mul
+    reads: blocks of 32 gate columns alternate with the blocks of the same 32 up columns.  F % 32 == 0."""
+    K, F = w_gate.shape
+    if tuple(w_up.shape) != (K, F) or F % 32:
+        raise ValueError("gate and up must both be [K, F] with F a multiple of 32")
+    g, u = w_gate.reshape(K, F // 32, 1, 32), w_up.reshape(K, F // 32, 1, 32)
+    if torch is not None and isinstance(w_gate, torch.Tensor):
+        return torch.cat([g, u], dim=2).reshape(K, 2 * F).contiguous()
+    import numpy as np
+    return np.ascontiguousarray(np.concatenate([g, u], axis=2).reshape(K, 2 * F))
 
 
 def tl_gemm_rs(ctx, a, b, partial, peer_recv, peer_push, out, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):

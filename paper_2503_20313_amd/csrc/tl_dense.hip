@@ -13,8 +13,9 @@ namespace tl {
 struct AgGemmParams {
   AgProducer prod;      // gathered A: shards, buffer, producer tiles, channel flags, ticket queue
   const bf16_t* b;
-  bf16_t* c;
+  bf16_t* c;            // [M, N], or [M, N/2] with an activation
   int M, N, K;
+  int act;              // 0, or ACT_*: B holds gate and up columns, the output is act(gate) * up
   Sched sched;
   int n_comm;           // producer workgroups at the front of the grid (0: none in this launch)
   int do_compute;       // 0: producers only
@@ -49,8 +50,9 @@ struct ChunkWait {
   __device__ __forceinline__ void acquire() const { acquire_after_wait(ctl); }
 };
 
-template <class Cfg>
+template <class Cfg, bool GATED = false>
 __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmParams p) {
+  typedef typename std::conditional<GATED, GatedRows, DenseRows>::type Out;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_ticket;
   const int tid = threadIdx.x;
@@ -78,13 +80,14 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
         for (int ch = clo; ch <= chi; ch++) tile_wait(p.prod.flags + ch * p.prod.k_chunks, p.prod.wait_target, p.prod.ctl, ch * p.prod.k_chunks);
       __syncthreads();
     }
+    Out out;
+    if constexpr (GATED) out = Out{p.c + (long)row_lo * (p.N / 2) + col_lo / 2, p.N / 2, p.act};
+    else out = Out{p.c + (long)row_lo * p.N + col_lo, p.N};
     if (p.prod.k_chunks > 1 && p.do_wait) {
-      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
-                     DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem,
+      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N, out, rows, cols, p.K, smem,
                      ChunkWait{p.prod.flags, p.prod.k_chunks, p.K / Cfg::BK / p.prod.k_chunks, clo, chi, p.prod.wait_target, p.prod.ctl});
     } else {
-      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N,
-                     DenseRows{p.c + (long)row_lo * p.N + col_lo, p.N}, rows, cols, p.K, smem);
+      gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N, out, rows, cols, p.K, smem);
     }
   }
 }
@@ -189,13 +192,14 @@ int fail(int code, const char* fmt, ...) {
 // the communication side, overlaps the remaining GEMM tiles and only a push is left at the end).
 static int rs_first_rank(const tl_config& c) { return c.tile_order >= TL_ORDER_OWN_FIRST ? c.rank : (c.rank + 1) % c.world_size; }
 
-int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
+int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, bool paired_columns) {
   const tl_config& c = ctx->cfg;
   if (M <= 0 || N <= 0 || K <= 0) return fail(TL_ERR_INVALID_ARG, "M, N, K must be positive (got %d, %d, %d)", M, N, K);
   const int R = c.world_size;
   if (M % R) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d must divide M=%d", R, M);
   if (K % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 64", K);  // every tile shape steps K by 32 or 64
   if (N % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "N=%d must be a multiple of 8", N);
+  if (paired_columns && N % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "gate and up columns alternate in blocks of 32: 2F=%d must be a multiple of 64", N);
   memset(r, 0, sizeof *r);
   // ---- compute tile
   int v = -1;
@@ -213,8 +217,9 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r) {
       long tiles = (long)ceil_div(M, tm) * ceil_div(N, tn), G = ctx->num_cus;
       return (double)((long)M * N) / ((double)((tiles + G - 1) / G * G) * tm * tn);
     };
-    v = (N % 224 == 0 && fill(256, 224) > 1.25 * fill(256, 256)) ? TILE_256x224 : TILE_256x256;
+    v = (!paired_columns && N % 224 == 0 && fill(256, 224) > 1.25 * fill(256, 256)) ? TILE_256x224 : TILE_256x256;
   }
+  if (paired_columns && v == TILE_256x224) return fail(TL_ERR_UNSUPPORTED_SHAPE, "the gated epilogue pairs 32-wide column blocks: the 256x224 tile has seven per wave");
   r->variant = v;
   r->tile_m = kTileM[v];
   r->tile_n = kTileN[v];
@@ -323,6 +328,11 @@ static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
 }
 
 static int launch_ag_gemm(int variant, const AgGemmParams& p, int grid, hipStream_t s) {
+  if (p.act) {
+    if (variant == TILE_256x256) return launch_fused<Cfg256x256>(ag_gemm_kernel<Cfg256x256, true>, p, grid, s);
+    if (variant == TILE_128x128) return launch_fused<Cfg128x128>(ag_gemm_kernel<Cfg128x128, true>, p, grid, s);
+    return fail(TL_ERR_UNSUPPORTED_SHAPE, "the gated epilogue needs the 256x256 or the 128x128 tile");
+  }
   switch (variant) {
     case TILE_256x256: return launch_fused<Cfg256x256>(ag_gemm_kernel<Cfg256x256>, p, grid, s);
     case TILE_256x224: return launch_fused<Cfg256x224>(ag_gemm_kernel<Cfg256x224>, p, grid, s);
@@ -432,14 +442,14 @@ int tl_check_status(tl_ctx* ctx, void* workspace) {
   return TL_OK;
 }
 
-int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K,
-               unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K, int act,
+                        unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
   if (int e = check_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!a_shards || !a_gathered || !b || !c || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: null pointer argument");
   if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: epoch starts at 1");
   Resolved r;
-  if (int e = resolve_dense(ctx, TL_OP_AG_GEMM, M, N, K, &r)) return e;
+  if (int e = resolve_dense(ctx, TL_OP_AG_GEMM, M, N, K, &r, act != 0)) return e;
   if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_ag_gemm: workspace of %zu bytes, 256 needed", ws_bytes);
   const int R = cfg.world_size;
   if (!aligned16(a_gathered) || !aligned16(b) || !aligned16(c)) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: device pointers must be 16-byte aligned");
@@ -459,6 +469,7 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
   p.b = (const bf16_t*)b;
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;
+  p.act = act;
   p.sched = make_sched(ctx, r);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
@@ -503,6 +514,19 @@ int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const
     }
   }
   return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: unknown comm_mode");
+}
+
+int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K,
+               unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  return ag_gemm_impl(ctx, a_shards, a_gathered, b, c, M, N, K, 0, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream);
+}
+
+int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b_gate_up, void* y, int M, int F, int K, int act,
+                       unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (act != TL_ACT_SILU_MUL && act != TL_ACT_GELU_MUL) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_act_mul: unknown activation %d", act);
+  if (F <= 0 || F > (1 << 29)) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_act_mul: F=%d out of range", F);
+  static_assert(TL_ACT_SILU_MUL == ACT_SILU_MUL && TL_ACT_GELU_MUL == ACT_GELU_MUL, "activation codes");
+  return ag_gemm_impl(ctx, a_shards, a_gathered, b_gate_up, y, M, 2 * F, K, act, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream);
 }
 
 int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv, void* const* peer_push,

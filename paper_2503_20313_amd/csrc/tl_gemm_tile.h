@@ -76,7 +76,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // Where the rows of an output tile go: dense = row r of the tile at c + r*ldc, unscaled.
 struct DenseRows {
-  static constexpr bool SCALED = false;
+  static constexpr bool SCALED = false, GATED = false;
   bf16_t* c;
   long ldc;
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
@@ -94,11 +94,31 @@ struct NoKWait {
   __device__ __forceinline__ void acquire() const {}
 };
 
+// Output of a GEMM whose B holds a gate and an up projection side by side, 32 columns of the one, then the same 32
+// features of the other (so that the two values of a feature sit in the same lane, in neighbouring 32x32 accumulator
+// blocks): the tile stores act(gate) * up, half as many columns as it computes (the activation between the two halves
+// of the MLP layer in the paper's evaluation, applied to the unrounded accumulators).  `c` points at the tile's first
+// output column (half the tile's first GEMM column).
+enum { ACT_SILU_MUL = 1, ACT_GELU_MUL = 2 };
+struct GatedRows {
+  static constexpr bool SCALED = false, GATED = true;
+  bf16_t* c;
+  long ldc;
+  int act;
+  __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
+  __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(c + (long)r * ldc + col) = v; }
+  __device__ __forceinline__ float apply(float g, float u) const {
+    if (act == ACT_SILU_MUL) return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;  // g * sigmoid(g) * u
+    return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)) * u;                                                          // g * Phi(g) * u
+  }
+};
+
 // Computes one output tile.  `a` points at column 0 of the A rows: tile row r is A row r, or A row
 // a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index); `b` points at
 // row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
 // column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED);
 // `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
+// With Out::GATED the tile's columns come in pairs of 32 (gate, up): out.apply(gate, up) is stored, at half the column.
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
 // masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
 template <class Cfg, class Out, class KW = NoKWait>
@@ -282,30 +302,47 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   // rounds its result to bf16 into an LDS region of its own and reads it back row-wise, so that a store instruction
   // writes whole 128-byte lines (16 bytes per lane, 8 lanes per row of a 64-wide wave tile).
   char* ep = smem + wave * (Cfg::WTM * Cfg::EP_PITCH);
+  constexpr int OUT_WTN = Out::GATED ? Cfg::WTN / 2 : Cfg::WTN;  // output columns of the wave tile
 #pragma unroll
   for (int mt = 0; mt < Cfg::MT; mt++) {
     const int row = mt * 32 + (lane & 31);
     float scale = 1.f;
     if (Out::SCALED && wm * Cfg::WTM + row < rows) out.row(wm * Cfg::WTM + row, scale);
+    if constexpr (Out::GATED) {
+      static_assert(!Out::GATED || Cfg::NT % 2 == 0, "gate and up blocks come in pairs");
 #pragma unroll
-    for (int nt = 0; nt < Cfg::NT; nt++) {
+      for (int np = 0; np < Cfg::NT / 2; np++) {
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        bf16x4 o;
+        for (int g = 0; g < 4; g++) {
+          bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; e++) o[e] = (bf16_t)(Out::SCALED ? acc[mt][nt][g * 4 + e] * scale : acc[mt][nt][g * 4 + e]);
-        *(bf16x4*)(ep + row * Cfg::EP_PITCH + (nt * 32 + g * 8 + (lane >> 5) * 4) * 2) = o;
+          for (int e = 0; e < 4; e++) o[e] = (bf16_t)out.apply(acc[mt][2 * np][g * 4 + e], acc[mt][2 * np + 1][g * 4 + e]);
+          *(bf16x4*)(ep + row * Cfg::EP_PITCH + (np * 32 + g * 8 + (lane >> 5) * 4) * 2) = o;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < Cfg::NT; nt++) {
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; e++) o[e] = (bf16_t)(Out::SCALED ? acc[mt][nt][g * 4 + e] * scale : acc[mt][nt][g * 4 + e]);
+          *(bf16x4*)(ep + row * Cfg::EP_PITCH + (nt * 32 + g * 8 + (lane >> 5) * 4) * 2) = o;
+        }
       }
     }
   }
-  constexpr int EP_CPR = Cfg::WTN / 8;                  // 16-byte chunks per row of the wave tile
+  constexpr int EP_CPR = OUT_WTN / 8;                   // 16-byte chunks per row of the wave tile's output
   constexpr int EP_ITERS = Cfg::WTM * EP_CPR / 64;
+  static_assert((Cfg::WTM * EP_CPR) % 64 == 0, "the epilogue hands out 16-byte chunks 64 at a time");
+  const int out_cols = Out::GATED ? cols / 2 : cols;
 #pragma unroll 4
   for (int i = 0; i < EP_ITERS; i++) {
     const int idx = i * 64 + lane;
     const int row = idx / EP_CPR, q = idx - row * EP_CPR;
-    const int grow = wm * Cfg::WTM + row, col = wn * Cfg::WTN + q * 8;
-    if (grow < rows && col < cols) {  // cols % 8 == 0: a chunk is all in or all out
+    const int grow = wm * Cfg::WTM + row, col = wn * OUT_WTN + q * 8;
+    if (grow < rows && col < out_cols) {  // cols % 8 == 0: a chunk is all in or all out
       out.store(grow, col, *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16));
     }
   }

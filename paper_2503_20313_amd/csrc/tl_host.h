@@ -47,7 +47,8 @@ struct Resolved {
   int arrival_bpr;       // AG+GEMM under TL_ORDER_ARRIVAL: row blocks per rank (0 = another order)
 };
 
-int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r);
+// paired_columns: the tile's 32-wide column blocks must come in pairs (gated epilogue): no 224-wide tile, N % 64 == 0
+int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, bool paired_columns = false);
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 

@@ -229,7 +229,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
 //   stage C (RS tiles): the shared ReduceScatter consumer on `partial`
 // ======================================================================================
 struct ScatterRows {
-  static constexpr bool SCALED = true;
+  static constexpr bool SCALED = true, GATED = false;
   bf16_t* scatter;        // [T*topk, H] at the tile's first column
   long ld;
   const int* rows;        // sorted_row + f_lo

@@ -77,7 +77,7 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
 // Where the rows of a [M,N] partial result go (output functor of the matrix tile): row g of the own segment to
 // partial[g,:], and with direct push row g of segment q to peer_push[q][g - q*seg_rows,:]; else all rows to partial.
 struct PushRows {
-  static constexpr bool SCALED = false;
+  static constexpr bool SCALED = false, GATED = false;
   const RsSide* rs;
   int row_lo, col_lo;
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const {

@@ -33,3 +33,24 @@ def test_binding_struct_matches_header_field_order():
     for decl in re.findall(r"(?:int|unsigned)\s+([^;]+);", body):
         fields += [f.strip() for f in decl.split(",")]
     assert fields == [f[0] for f in tl.tl_config._fields_]
+
+
+def test_pack_gate_up_layout():
+    """Column 64t + j of the packed matrix is gate column 32t + j for j < 32 and up column 32t + j - 32 otherwise."""
+    import numpy as np
+    import torch
+    import paper_2503_20313_amd as tl
+    K, F = 5, 96
+    g = np.arange(K * F, dtype=np.int32).reshape(K, F)
+    u = -1 - g
+    p = tl.pack_gate_up(g, u)
+    assert p.shape == (K, 2 * F) and p.flags["C_CONTIGUOUS"]
+    for c in range(2 * F):
+        t, j = divmod(c, 64)
+        want = g[:, 32 * t + j] if j < 32 else u[:, 32 * t + j - 32]
+        assert np.array_equal(p[:, c], want)
+    pt = tl.pack_gate_up(torch.from_numpy(g), torch.from_numpy(u))
+    assert torch.equal(pt, torch.from_numpy(p)) and pt.is_contiguous()
+    import pytest
+    with pytest.raises(ValueError):
+        tl.pack_gate_up(g[:, :40], u[:, :40])

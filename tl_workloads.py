@@ -71,6 +71,13 @@ def ag_gemm_inputs(M, N, K, world, config_id=2, a_dist="normal", b_std=0.02):
     return {"a_shards": shards, "b": b, "M": M, "N": N, "K": K, "world": world}
 
 
+def ag_gemm_gated_inputs(M, F, K, world, config_id=6, b_std=0.02):
+    """A sharded along M as in ag_gemm_inputs; gate and up projection weights, each [K, F]."""
+    w = ag_gemm_inputs(M, F, K, world, config_id=config_id, b_std=b_std)
+    return {"a_shards": w["a_shards"], "w_gate": w["b"], "w_up": normal_bf16((K, F), b_std, config_id, 2),
+            "M": M, "F": F, "K": K, "world": world}
+
+
 def gemm_rs_inputs(M, N, K, world, rank, config_id=3, b_std=0.02, peer_std=None):
     """Local A [M,K], B [K,N]; for every peer q != rank the rows of its partial
     product that fall in this rank's output segment, [M/world, N] bf16.
