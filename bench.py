@@ -60,8 +60,9 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
                 ms.wait_stream(cs)
                 call(st)
             t[name], _ = timed(fn, steps, warmup)
-            tl.tl_check_status(st["ctx"], st["wsp"])
-            tl.tl_ctx_destroy(st["ctx"])
+            for ctx_, wsp_ in [(st["ctx"], st["wsp"])] + st.get("also", []):
+                tl.tl_check_status(ctx_, wsp_)
+                tl.tl_ctx_destroy(ctx_)
         r = {k: round(v, 4) for k, v in t.items()}
         r["tflops"] = round(flop / t["fused_ms"] / 1e9, 1)
         r["compute_alone_tflops"] = round(flop / t["compute_alone_ms"] / 1e9, 1)
@@ -70,6 +71,61 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
         if extra:
             r.update(extra)
         return r
+
+    # ---------------- the whole MLP layer (MLP-5 share, rank 0): AllGather + GEMM over gate|up weights with SiLUMul in the
+    # epilogue, then GEMM + ReduceScatter on its output
+    M, F, H = 8192, 3584, 8192
+    wg = wl.ag_gemm_gated_inputs(M, F, H, R, config_id=6)
+    w3 = wl.gemm_rs_inputs(M, H, F, R, 0, config_id=3)
+    shards = [up(x) for x in wg["a_shards"]]
+    a_full = torch.cat(shards).clone()
+    b_gu = up(tl.pack_gate_up(wg["w_gate"], wg["w_up"]))
+    y = torch.zeros((M, F), dtype=torch.int16, device=dev)
+    w_down = up(w3["b"])
+    partial = torch.zeros((M, H), dtype=torch.int16, device=dev)
+    recv = [0] + [up(w3["peer_segments"][q]) for q in range(1, R)]
+    push = [0] + [torch.zeros((M // R, H), dtype=torch.int16, device=dev) for _ in range(1, R)]
+    out = torch.zeros((M // R, H), dtype=torch.int16, device=dev)
+
+    def mlp_make(m, alone):
+        st = {}
+        for part, op, dims in (("p1", tl.TL_OP_AG_GEMM, [M, 2 * F, H]), ("p2", tl.TL_OP_GEMM_RS, [M, H, F])):
+            ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=4, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                                   spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push)
+            ws, nf = tl.tl_query_workspace(ctx, op, dims)
+            st[part] = dict(ctx=ctx, ws=ws, flags=torch.zeros(nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev))
+        st["ctx"], st["wsp"] = st["p1"]["ctx"], st["p1"]["wsp"]
+        st["also"] = [(st["p2"]["ctx"], st["p2"]["wsp"])]
+        st["xg"] = a_full.clone() if m == tl.TL_COMM_NONE else torch.zeros((M, H), dtype=torch.int16, device=dev)
+        torch.cuda.synchronize()
+        return st
+
+    def mlp_call(st, parts=("p1", "p2")):
+        if "p1" in parts:
+            p = st["p1"]
+            tl.tl_ag_gemm_act_mul(p["ctx"], shards, st["xg"], b_gu, y, M, F, H, tl.TL_ACT_SILU_MUL, p["flags"], st["epoch"], p["wsp"], p["ws"], cs, ms)
+        if "p2" in parts:
+            p = st["p2"]
+            if "p1" in parts:
+                ms.wait_stream(cs)      # the reduce side of part 2 may not run ahead into part 1
+            tl.tl_gemm_rs(p["ctx"], y, w_down, partial, recv, push, out, M, H, F, p["flags"], st["epoch"], p["wsp"], p["ws"], cs, ms)
+
+    flop_mlp = 2.0 * M * (2 * F) * H + 2.0 * M * H * F
+    r = triple(mlp_make, mlp_call, flop_mlp, {"workload": "MLP-5 TP=8 share, rank 0: AG + GEMM [8192,8192]x[8192,2x3584] with SiLUMul, then GEMM [8192,3584]x[3584,8192] + RS"})
+    for part in ("p1", "p2"):
+        st = mlp_make(mode, 0)
+        st["epoch"] = 0
+
+        def fn(st=st, part=part):
+            st["epoch"] += 1
+            ms.wait_stream(cs)
+            mlp_call(st, (part,))
+        r[f"{part}_fused_ms"] = round(timed(fn, steps, warmup)[0], 4)
+        for q in ("p1", "p2"):
+            tl.tl_check_status(st[q]["ctx"], st[q]["wsp"])
+            tl.tl_ctx_destroy(st[q]["ctx"])
+    res["mlp_layer"] = r
+    del shards, a_full, b_gu, y, w_down, partial, recv, push, out
 
     # ---------------- MoE (configuration 4), rank 0
     c = wl.CONFIGS[4]
