@@ -48,6 +48,10 @@ __device__ __forceinline__ void both_halves(float v, float& lo, float& hi) {
   lo = __builtin_bit_cast(float, (unsigned)r[0]);
   hi = __builtin_bit_cast(float, (unsigned)r[1]);
 }
+// max(a, b) of two raw matrix-instruction results.  Written as a median with +inf, which the compiler turns into one
+// v_max_f32 on the raw registers; fmaxf() on them would first canonicalise each operand with an instruction of its own.
+__device__ __forceinline__ float raw_max(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
+
 __device__ __forceinline__ float halves_max(float v) {
   float lo, hi;
   both_halves(v, lo, hi);
@@ -181,7 +185,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   auto block_max = [&](const floatx16 (&sc)[2]) __attribute__((always_inline)) -> float {
     float m = -1e30f;
 #pragma unroll
-    for (int e = 0; e < 16; e++) m = fmaxf(m, fmaxf(sc[0][e], sc[1][e]));
+    for (int e = 0; e < 16; e += 2) m = fmaxf(m, fmaxf(raw_max(sc[0][e], sc[1][e]), raw_max(sc[0][e + 1], sc[1][e + 1])));
     return halves_max(m);
   };
   float m_blk[QT];   // block_max of the block the next iteration works on, computed one iteration early
@@ -278,7 +282,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
           for (int uu = 0; uu < QT; uu++) {
             float m = q == 0 ? -1e30f : m_part[uu];
 #pragma unroll
-            for (int e = q * 4; e < q * 4 + 4; e++) m = fmaxf(m, fmaxf(n[uu][0][e], n[uu][1][e]));
+            for (int e = q * 4; e < q * 4 + 4; e += 2) m = fmaxf(m, fmaxf(raw_max(n[uu][0][e], n[uu][1][e]), raw_max(n[uu][0][e + 1], n[uu][1][e + 1])));
             m_part[uu] = m;
           }
         }
@@ -291,8 +295,14 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
           if constexpr (y * 7 / 8 == sl) {
             constexpr int g = y / (8 * QT), uu = (y / 8) % QT, i = y % 8;
             const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(c[uu][g >> 1][(g & 1) * 8 + i], p.scale_log2e, mc[uu]));
-            psum[uu] += pv;
             pf[uu][g][i] = (bf16_t)pv;
+            // the row sum takes the probabilities as the matrix instruction will see them (rounded to bf16), two per
+            // instruction: one dot product with (1, 1) instead of two additions
+            if constexpr (i & 1) {
+              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+              const bf16x2 pr = {pf[uu][g][i - 1], pf[uu][g][i]}, ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+              psum[uu] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[uu], false);
+            }
           }
         });
         __builtin_amdgcn_sched_barrier(0);
