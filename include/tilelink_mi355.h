@@ -140,11 +140,14 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
  *   b          dev [K,N] bf16.           c  dev [M,N] bf16 (written).
  *   flags      dev unsigned[R*C]; channel index = src_rank*C + local channel (the global index of the
  *              paper's channel formula).  After call `epoch` every entry equals epoch * expected where
- *              expected = (M/(R*C)/Tm_p) * ceil(K/Tn_p) in WAVES mode and 1 in STREAM mode; untouched in NONE.
+ *              expected = (M/(R*C)/Tm_p) * ceil(K/Tn_p) in WAVES and SIDE_KERNEL mode and 1 in STREAM mode; untouched
+ *              in NONE.  With ag_k_chunks in effect: unsigned[R*C*k_chunks], index channel*k_chunks + chunk, expected =
+ *              M/(R*C)/Tm_p (tl_query_workspace and tl_resolve report the counts).
  *   Requirements: R | M, C | M/R, Tm_p | M/(R*C), K % 64 == 0, N % 8 == 0, Tn_p | K.
  *   workspace  word 0 = status word, word 1 = head of the producer-tile queue: it grows by the number of producer
  *              tiles per call, so the caller zeroes the workspace together with the flags (once, or when `epoch`
- *              restarts at 1).  In WAVES and SIDE_KERNEL mode producer tiles are handed out through this queue to the
+ *              restarts at 1).  Bytes 16..23 hold the start time of the call in flight when link_gbps is set.  One call at
+ *              a time per workspace.  In WAVES and SIDE_KERNEL mode producer tiles are handed out through this queue to the
  *              producer workgroups and to GEMM workgroups that would otherwise wait.
  *   compute_stream receives the fused kernel; comm_stream the copies in TL_COMM_STREAM.
  */
