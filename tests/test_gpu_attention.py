@@ -97,6 +97,17 @@ def test_shapes(S, heads, R, C, rank, causal, mode):
     check_gathered(w, res, rank, causal, C)
 
 
+@pytest.mark.parametrize("rank,mode,C", [(3, "side", 2), (0, "waves", 1), (2, "waves", 2)])
+def test_simulated_links(rank, mode, C):
+    """K and V shards arriving over simulated links (interleaved producer queue, paced tiles, consumers that only wait):
+    same result.  800 GB/s: a 128 KiB shard pair takes a fraction of a microsecond, the call stays short."""
+    w = wl.sp_attention_inputs(1024, 4, 128, 4, config_id=56)
+    res = run_attention(w, rank, True, MODES[mode], C=C, epochs=2, link_gbps=800)
+    _, _, _, o_ref = ops.sp_ag_attention(w["q_shards"][rank], w["k_shards"], w["v_shards"], rank, True)
+    assert_close_bf16(res["o"], o_ref, f"attention over simulated links rank {rank} {mode}")
+    check_gathered(w, res, rank, True, C, epochs=2)
+
+
 def test_peaked_scores_and_scale():
     """Large score spread (scale 4x the usual one): the running maximum moves a lot, old partial sums are rescaled
     by tiny factors, and most probabilities underflow to zero."""

@@ -99,6 +99,13 @@ def test_part1_small(mode):
     run_part1(w, 1, 2, MODES[mode], epochs=2, comm_workgroups=2)
 
 
+@pytest.mark.parametrize("mode", ["waves", "side"])
+def test_part1_simulated_links(mode):
+    """Token shards arriving over simulated links (interleaved queue, paced tiles, consumers only wait): same results."""
+    w = wl.moe_inputs(512, 128, 192, 4, 2, 4, 1, config_id=44)
+    run_part1(w, 1, 2, MODES[mode], epochs=2, comm_workgroups=4, link_gbps=400)
+
+
 def test_part1_ragged_tiles_and_many_channels():
     # 5 ranks, 5 experts, top-3, I = 320 (ragged for every tile width), explicit 128x128 tile -> short last tiles per expert
     w = wl.moe_inputs(640, 192, 320, 5, 3, 5, 2, config_id=43)
