@@ -21,25 +21,28 @@ PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk x 2.4 GHz (dense bf16 MF
 HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (1124 + 168 + 672 + 128) * 2 ** 20)
 
 
-def cpu_baseline(np, wl, ops):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
-    AG+GEMM restricted to the first 1024 of the 3584 output columns, GEMM+RS to the first 2048 of 8192."""
-    t_gen = time.time()
-    w = wl.ag_gemm_inputs(8192, 1024, 8192, 8, config_id=2)
-    w3 = wl.gemm_rs_inputs(8192, 2048, 3584, 8, 0, config_id=3)
-    t0 = time.time()
-    ops.ag_gemm(w["a_shards"], w["b"])
-    ops.gemm_rs(w3["a"], w3["b"], w3["peer_segments"], 0)
-    dt = time.time() - t0
-    flop = 2.0 * 8192 * 8192 * 1024 + 2.0 * 8192 * 2048 * 3584
+def cpu_baseline(np, ops, w2, w3, rank):
+    """The oracle as it stands, timed on the host cores on one whole step of the workload (the same arrays the GPU
+    path was given): AG+GEMM of configuration 2, then GEMM+RS of configuration 3, repeated for about ten seconds; the
+    fastest pass counts."""
+    flop = 2.0 * w2["M"] * w2["N"] * w2["K"] + 2.0 * w3["a"].shape[0] * w3["b"].shape[1] * w3["a"].shape[1]
+    best, passes = None, 0
+    t_all = time.time()
+    while passes < 2 or (time.time() - t_all < 10.0 and passes < 12):     # about 10 s of CPU work
+        t0 = time.time()
+        ops.ag_gemm(w2["a_shards"], w2["b"])
+        ops.gemm_rs(w3["a"], w3["b"], w3["peer_segments"], rank)
+        dt = time.time() - t0
+        best = dt if best is None else min(best, dt)
+        passes += 1
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
-    return {"value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "AG+GEMM 8192x1024x8192 (first 1024 of 3584 columns) + GEMM+RS 8192x2048x3584 (first 2048 of 8192 columns), "
-                      f"float64 numpy, {dt:.1f} s (+{t0 - t_gen:.1f} s input generation)"}
+    return {"value": flop / best / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"one whole step (AG+GEMM 8192x3584x8192 + GEMM+RS 8192x8192x3584, 9.6e11 flop), float64 numpy, "
+                      f"best of {passes} passes: {best:.1f} s ({time.time() - t_all:.1f} s in all)"}
 
 
 def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push):
@@ -283,16 +286,18 @@ def main():
     ms = torch.cuda.Stream()
 
     class Op:
-        def __init__(self, op, dims, comm_mode, comm_alone=0):
+        def __init__(self, op, dims, comm_mode, comm_alone=0, **over):
             tile = (args.ag_tile if op == tl.TL_OP_AG_GEMM else args.rs_tile) or "0x0"
             tm, tn = (int(v) for v in tile.split("x"))
-            self.ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
-                                        comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
-                                        ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
-                                        link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
-                                        comm_workgroups=args.comm_workgroups, xcd_swizzle=1,
-                                        tile_order=tl.TL_ORDER_ARRIVAL if op == tl.TL_OP_AG_GEMM and args.ag_order == "arrival" else tl.TL_ORDER_OWN_FIRST,
-                                        spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else args.direct_push_mode)
+            fields = dict(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
+                          comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
+                          ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
+                          link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
+                          comm_workgroups=args.comm_workgroups, xcd_swizzle=1,
+                          tile_order=tl.TL_ORDER_ARRIVAL if op == tl.TL_OP_AG_GEMM and args.ag_order == "arrival" else tl.TL_ORDER_OWN_FIRST,
+                          spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else args.direct_push_mode)
+            fields.update(over)
+            self.ctx = tl.tl_ctx_create(**fields)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
             self.flags = torch.zeros(n_flags, dtype=torch.int32, device=dev)
@@ -415,12 +420,25 @@ def main():
                      "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)"},
         "host_wall_ms_per_step": round(wall_step, 4),
     }
+    if not args.no_extras and mode != tl.TL_COMM_STREAM:
+        # AG+GEMM with the shards arriving over simulated xGMI links (153 GB/s per source rank, all side by side): arrival
+        # tile order, four K chunks per channel
+        links = dict(link_gbps=153, tile_order=tl.TL_ORDER_ARRIVAL, ag_k_chunks=4)
+        f_l, c_l = Op(tl.TL_OP_AG_GEMM, [M, N, K], mode, **links), Op(tl.TL_OP_AG_GEMM, [M, N, K], mode, comm_alone=1, **links)
+        t_cl, _ = timed(c_l, args.steps, args.warmup)
+        t_fl, _ = timed(f_l, args.steps, args.warmup)
+        for o in (f_l, c_l):
+            tl.tl_check_status(o.ctx, o.wsp)
+            tl.tl_ctx_destroy(o.ctx)
+        out["ag_gemm_links_153"] = {"fused_ms": round(t_fl, 4), "comm_alone_ms": round(t_cl, 4), "compute_alone_ms": res["ag_gemm"]["compute_alone_ms"],
+                                    "overlap_efficiency": round(max(res["ag_gemm"]["compute_alone_ms"], t_cl) / t_fl, 4),
+                                    "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 4}
     if not args.no_extras:
         out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
                                args.steps, args.warmup, 0 if args.no_direct_push else 1)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops
-        out["cpu_baseline"] = cpu_baseline(np, wl, oracle_ops)
+        out["cpu_baseline"] = cpu_baseline(np, oracle_ops, w2, w3, rank)
     print(json.dumps(out))
 
 
