@@ -3,7 +3,12 @@
 One step = AllGather+GEMM on one rank's TP=8 share of MLP-5's first half (8 shards of
 [1024,8192] gathered, B [8192,3584]) followed by GEMM+ReduceScatter on its second half
 (A [8192,3584] x B [3584,8192], 7 peers, output [1024,8192]); inputs are synthetic, seeded and
-already resident in HBM.  Prints ONE JSON line (see the design doc for the fields).
+already resident in HBM.  Prints ONE JSON line: `value` = whole-step TFLOP/s (9.62e11 flop per step over the step
+time); `ops` = per operator the fused time, the GEMM alone (repeated call, and with its input rewritten before each
+call), the communication side alone, and overlap efficiency = max(alone) / fused; `roofline` = the two tile kernels
+against the dense bf16 MFMA peak, with measured HBM/fabric traffic per launch; `ag_gemm_links_153` = AG+GEMM with the
+shards arriving over simulated 153 GB/s links; `extras` = the whole MLP layer, the MoE halves and sequence-parallel
+attention; `cpu_baseline` = the CPU oracle on the same step.
 """
 import argparse
 import json
