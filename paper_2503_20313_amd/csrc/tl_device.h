@@ -190,7 +190,7 @@ struct Sched {
   int first_block;  // rotation of row blocks (0 = natural)
   int swizzle;
   int group_m;      // >= 1
-  int arrival_bpr;  // 0, or the row blocks per rank: after the bpr blocks from first_block on (the local shard's), block j
+  int arrival_bpr = 0;  // 0, or the row blocks per rank: after the bpr blocks from first_block on (the local shard's), block j
                     // of each further rank along the ring comes before block j+1 of any
 };
 

@@ -187,10 +187,46 @@ struct MoeP1Params {
   int n_comm, do_compute, do_wait;
 };
 
+// Order of the row tiles of a grouped GEMM whose tiles skip their empty 32-row blocks (gemm_tile's SKIP_EMPTY): an
+// expert's last row tile is often nearly empty and then somewhat shorter than a full one (it still streams its whole
+// block of the expert's weights), so the long tiles (more than half the rows valid) go first, in the usual schedule, and the short ones are dealt out afterwards -- first,
+// two each, to the workgroups that the long tiles leave without work in their last round, then to all in turn.
+// perm[0 .. n_long) = the long row tiles in table order, perm[n_long .. n) = the short ones.  Computed by wave 0 of
+// every workgroup from the routing tables (a few hundred entries); callers fall back to table order above kMaxPerm.
+constexpr int kMaxPerm = 2048;
+__device__ __forceinline__ int long_tiles_first(const int* tile_tables, int n, int tile_m, unsigned short* perm, int tid) {
+  const int lane = tid & 63;
+  int n_long = 0;
+  if (__builtin_amdgcn_readfirstlane(tid >> 6) == 0) {
+    for (int c = 0; c < n; c += 64) {
+      const int i = c + lane;
+      const bool is_long = i < n && 2 * (tile_tables[(long)i * 8 + 1] - tile_tables[(long)i * 8]) > tile_m;
+      n_long += __builtin_popcountll(__builtin_amdgcn_ballot_w64(is_long));
+    }
+    int c_long = 0, c_short = 0;
+    for (int c = 0; c < n; c += 64) {
+      const int i = c + lane;
+      const bool valid = i < n;
+      const bool is_long = valid && 2 * (tile_tables[(long)i * 8 + 1] - tile_tables[(long)i * 8]) > tile_m;
+      const unsigned long long ml = __builtin_amdgcn_ballot_w64(is_long), mv = __builtin_amdgcn_ballot_w64(valid);
+      const unsigned long long below = (1ull << lane) - 1;
+      if (valid) {
+        const int pos = is_long ? c_long + __builtin_popcountll(ml & below) : n_long + c_short + __builtin_popcountll(mv & ~ml & below);
+        perm[pos] = (unsigned short)i;
+      }
+      c_long += __builtin_popcountll(ml);
+      c_short += __builtin_popcountll(mv & ~ml);
+    }
+  }
+  return n_long;  // meaningful in wave 0 only: the caller broadcasts it
+}
+
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const MoeP1Params p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_ticket;
+  __shared__ int s_n_long;
+  __shared__ unsigned short s_perm[kMaxPerm];
   const int tid = threadIdx.x;
   if ((int)blockIdx.x < p.n_comm) {
     ag_producer(p.prod, tid, Cfg::NTHREADS, &s_ticket);
@@ -199,25 +235,53 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
   if (!p.do_compute) return;
   __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
+  const int n_rt = *p.n_row_tiles;
+  constexpr bool kSkip = Cfg::MT >= 4;   // short tiles are cheaper only where their empty blocks are skipped
+  const bool reorder = kSkip && n_rt <= kMaxPerm;
+  int n_long = n_rt;
+  if (reorder) {
+    int nl = long_tiles_first(p.tile_tables, n_rt, Cfg::BM, s_perm, tid);
+    if (tid == 0) s_n_long = nl;
+    __syncthreads();
+    n_long = s_n_long;
+  }
   Sched sc;
-  sc.nbm = *p.n_row_tiles;
+  sc.nbm = n_long;
   sc.nbn = p.nbn;
   sc.n_tiles = sc.nbm * sc.nbn;
   sc.G = p.G;
   sc.first_block = 0;
   sc.swizzle = p.swizzle;
-  sc.group_m = p.group_m;
-  for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
-    int tile = sched_tile(sc, pos);
-    int bm = tile / sc.nbn, bn = tile - bm * sc.nbn;
+  sc.group_m = p.group_m < n_long ? p.group_m : (n_long > 0 ? n_long : 1);
+  sc.arrival_bpr = 0;
+  auto do_tile = [&](int bm, int bn) __attribute__((always_inline)) {
     const int* rec = p.tile_tables + (long)bm * 8;
     const int f_lo = rec[0], f_hi = rec[1], e = rec[2];
     const unsigned long long mask = (unsigned long long)(unsigned)rec[3] | ((unsigned long long)(unsigned)rec[4] << 32);
     const int col_lo = bn * Cfg::BN;
     const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.I - col_lo);
     if (p.do_wait) consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
-    gemm_tile<Cfg>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                   DenseRows{p.y1 + (long)f_lo * p.I + col_lo, p.I}, rows, cols, p.H, smem);
+    // empty 32-row blocks are skipped where a wave owns several of them (measured: the branch per matrix instruction costs
+    // the small tiles more than the skipped work saves)
+    gemm_tile<Cfg, DenseRows, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                                                       DenseRows{p.y1 + (long)f_lo * p.I + col_lo, p.I}, rows, cols, p.H, smem);
+  };
+  // the long tiles, in the usual order
+  for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
+    int tile = sched_tile(sc, pos);
+    int bi = tile / sc.nbn, bn = tile - bi * sc.nbn;
+    do_tile(reorder ? s_perm[bi] : bi, bn);
+  }
+  // the short tiles: number j goes to one of the `idle` workgroups that the long tiles leave free in their last round
+  // (two each), and beyond that to all workgroups in turn
+  const int n_short = (n_rt - n_long) * p.nbn;
+  const int used = sc.n_tiles % sc.G, idle = used ? sc.G - used : 0;
+  for (int j = 0; reorder && j < n_short; j++) {
+    int owner;
+    if (j < 2 * idle) owner = used + j % idle;
+    else owner = (j - 2 * idle) % sc.G;
+    if (owner != w) continue;
+    do_tile(s_perm[n_long + j / p.nbn], j % p.nbn);
   }
 }
 
