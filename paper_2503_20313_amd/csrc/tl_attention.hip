@@ -110,12 +110,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   const int n_kv = p.causal ? (g0 + wg_q_hi) / kBKV + 1 : (p.S + kBKV - 1) / kBKV;
   const char* kbase = (const char*)(p.kprod.gathered + (long)head * kD);
   const char* vbase = (const char*)(p.vprod.gathered + (long)head * kD);
-  // A lane's loads of a block differ from block to block only by a uniform offset: the per-lane part (row inside the
-  // block x pitch + chunk) is computed once, the block's base address is scalar arithmetic, and the loads take
-  // "scalar base + 32-bit lane offset" addresses.  Only a last block that reaches past S clamps its rows lane by lane.
-  const unsigned pitch = (unsigned)ldq * 2;                        // bytes per key row
   int ld_row[LPW], ld_kc[LPW], ld_vc[LPW];
-  unsigned ld_koff[LPW], ld_voff[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; i++) {
     int j = wave + i * NW;
@@ -123,28 +118,16 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
     ld_row[i] = row;
     ld_kc[i] = (pc ^ (row & 15)) * 16;
     ld_vc[i] = (pc ^ ((row & 3) << 2)) * 16;
-    ld_koff[i] = (unsigned)row * pitch + ld_kc[i];
-    ld_voff[i] = (unsigned)row * pitch + ld_vc[i];
   }
   auto issue_block = [&](int blk, int stage) __attribute__((always_inline)) {
     char* sk = smem + stage * 2 * kKvTileBytes;
     char* sv = sk + kKvTileBytes;
-    const long boff = (long)blk * kBKV * pitch;
-    if (blk * kBKV + kBKV <= p.S) {
 #pragma unroll
-      for (int i = 0; i < LPW; i++) {
-        int j = wave + i * NW;
-        lds_load16(kbase + boff + ld_koff[i], sk + j * 1024);
-        lds_load16(vbase + boff + ld_voff[i], sv + j * 1024);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < LPW; i++) {
-        int j = wave + i * NW;
-        long row = min(blk * kBKV + ld_row[i], p.S - 1);
-        lds_load16(kbase + row * pitch + ld_kc[i], sk + j * 1024);
-        lds_load16(vbase + row * pitch + ld_vc[i], sv + j * 1024);
-      }
+    for (int i = 0; i < LPW; i++) {
+      int j = wave + i * NW;
+      long row = min(blk * kBKV + ld_row[i], p.S - 1);
+      lds_load16(kbase + row * ldq * 2 + ld_kc[i], sk + j * 1024);
+      lds_load16(vbase + row * ldq * 2 + ld_vc[i], sv + j * 1024);
     }
   };
   // consumer_tile_wait on the K and V flags of the channel block `blk` starts, if it starts one
