@@ -426,9 +426,10 @@ def main():
         "host_wall_ms_per_step": round(wall_step, 4),
     }
     if not args.no_extras and mode != tl.TL_COMM_STREAM:
-        # AG+GEMM with the shards arriving over simulated xGMI links (153 GB/s per source rank, all side by side): arrival
-        # tile order, four K chunks per channel
-        links = dict(link_gbps=153, tile_order=tl.TL_ORDER_ARRIVAL, ag_k_chunks=4)
+        # AG+GEMM with the shards arriving over simulated xGMI links (153 GB/s per source rank, all side by side), arrival
+        # tile order.  (Four K chunks per channel are 2 % faster still, but need the producer kernel to run beside the
+        # GEMM, which a profiler that serialises kernels does not allow.)
+        links = dict(link_gbps=153, tile_order=tl.TL_ORDER_ARRIVAL, ag_k_chunks=0)
         f_l, c_l = Op(tl.TL_OP_AG_GEMM, [M, N, K], mode, **links), Op(tl.TL_OP_AG_GEMM, [M, N, K], mode, comm_alone=1, **links)
         t_cl, _ = timed(c_l, args.steps, args.warmup)
         t_fl, _ = timed(f_l, args.steps, args.warmup)
@@ -437,7 +438,7 @@ def main():
             tl.tl_ctx_destroy(o.ctx)
         out["ag_gemm_links_153"] = {"fused_ms": round(t_fl, 4), "comm_alone_ms": round(t_cl, 4), "compute_alone_ms": res["ag_gemm"]["compute_alone_ms"],
                                     "overlap_efficiency": round(max(res["ag_gemm"]["compute_alone_ms"], t_cl) / t_fl, 4),
-                                    "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 4}
+                                    "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 1}
     if not args.no_extras:
         out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
                                args.steps, args.warmup, 0 if args.no_direct_push else 1)

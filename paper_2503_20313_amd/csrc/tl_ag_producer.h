@@ -146,7 +146,7 @@ template <int DEPTH = 2>
 __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, unsigned long long chan_mask, int tid, int nthreads, int* s_ticket) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned long long t0 = 0;
-  if (wave == 0 && p.ctl.timeout) t0 = wall_clock64();
+  if (wave == 0 && (p.ctl.timeout || p.pace_q8)) t0 = wall_clock64();
   // Tickets are taken only while the queue head has not passed the last tile of the awaited channels: beyond that point every
   // tile this workgroup needs is already in the hands of a resident workgroup, and taking more tickets would only delay it.
   int limit = 0;
@@ -171,8 +171,10 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     }
   }
   // With simulated links a ticket is a tile that may not be due for a long time: a consumer that took one would sleep on
-  // it while its own rows arrive, and more workers do not make a link faster.  It only waits.
-  if (p.pace_q8) limit = 0;
+  // it while its own rows arrive, and more workers do not make a link faster.  It only waits -- unless nothing has come
+  // for far longer than a link takes (a millisecond): then no producer is running beside this kernel (a tool that runs
+  // kernels one at a time, say), and the consumers work the queue off themselves as they do without links.
+  const unsigned long long patience = p.pace_q8 ? 100000ull : 0ull;
   const unsigned queue_begin = p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn);
   for (;;) {
     if (wave == 0) {
@@ -186,7 +188,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
       if (state == -1) {
         unsigned t;
         unsigned head = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        if ((int)(head - queue_begin) < limit && claim_ticket(p, &t)) state = (int)t;
+        if ((int)(head - queue_begin) < limit && (!patience || wall_clock64() - t0 > patience) && claim_ticket(p, &t)) state = (int)t;
         else if (p.ctl.timeout) {
           int st = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.ctl.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
           if (st != 0) state = -2;  // abandoned elsewhere
