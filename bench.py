@@ -150,10 +150,10 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     push = [0] + [torch.zeros((T // R, H), dtype=torch.int16, device=dev) for _ in range(1, R)]
     out = torch.zeros((T // R, H), dtype=torch.int16, device=dev)
 
-    def moe_state(op, m, alone, C):
+    def moe_state(op, m, alone, C, cols=None):
         ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
                                spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push)
-        q = tl.tl_moe_query(ctx, op, T, H, I, E, k)
+        q = tl.tl_moe_query(ctx, op, T, H, cols or I, E, k)
         st = dict(ctx=ctx, q=q,
                   ids=torch.zeros((T, k), dtype=torch.int32, device=dev), tw=torch.zeros((T, k), dtype=torch.float32, device=dev),
                   off=torch.zeros(E + 1, dtype=torch.int32, device=dev), srow=torch.zeros(T * k, dtype=torch.int32, device=dev),
@@ -181,7 +181,30 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     res["moe_ag_gather_gemm"] = triple(p1_make, p1_call, flop_moe, {"workload": f"T={T} H={H} I={I} E={E} top{k}, TP=8 share, rank 0"})
     res["moe_gemm_scatter_rs"] = triple(lambda m, alone: moe_state(tl.TL_OP_MOE_GEMM_SCATTER_RS, m, alone, 1), p2_call, flop_moe,
                                         {"workload": f"T={T} H={H} I={I} E={E} top{k}, TP=8 share, rank 0; compute alone = grouped GEMM + scatter only"})
-    del x_shards, x_full, w1, w2, x2, y1, scatter, partial, recv, push, out
+
+    # the whole MoE layer: gather + grouped GEMM over gate|up expert weights with SiLUMul in the epilogue (I features each),
+    # then grouped GEMM + scatter + top-k reduce + ReduceScatter on its output
+    w1_gu = up(tl.pack_gate_up(w["w1"].reshape(E * H, I), w["w1_up"].reshape(E * H, I)))
+
+    def layer_make(m, alone):
+        p1 = moe_state(tl.TL_OP_MOE_AG_GATHER_GEMM, m, alone, 4, cols=2 * I)
+        p2 = moe_state(tl.TL_OP_MOE_GEMM_SCATTER_RS, m, alone, 1)
+        p1["xg"] = x_full.clone() if m == tl.TL_COMM_NONE else torch.zeros((T, H), dtype=torch.int16, device=dev)
+        return dict(p1=p1, p2=p2, ctx=p1["ctx"], wsp=p1["wsp"], also=[(p2["ctx"], p2["wsp"])])
+
+    def layer_call(st):
+        p = st["p1"]
+        tl.tl_moe_ag_gather_gemm_act_mul(p["ctx"], x_shards, p["xg"], w1_gu, p["srow"], p["tab"], p["nt"], y1, T, H, I, E, k, tl.TL_ACT_SILU_MUL,
+                                         p["flags"], st["epoch"], p["wsp"], p["q"]["ws_bytes"], cs, ms)
+        ms.wait_stream(cs)      # the reduce side of part 2 may not run ahead into part 1
+        p = st["p2"]
+        tl.tl_moe_gemm_scatter_rs(p["ctx"], y1, w2, p["srow"], p["tab"], p["nt"], p["tw"], scatter, partial, recv, push, out, T, H, I, E, k,
+                                  p["flags"], st["epoch"], p["wsp"], p["q"]["ws_bytes"], cs, ms)
+
+    res["moe_layer"] = triple(layer_make, layer_call, 3 * flop_moe,
+                              {"workload": f"T={T} H={H} I={I} E={E} top{k}, TP=8 share, rank 0: gather + grouped GEMM [.,{H}]x[{H},2x{I}] with "
+                                           f"SiLUMul, then grouped GEMM [.,{I}]x[{I},{H}] + scatter + top-k reduce + RS"})
+    del x_shards, x_full, w1, w1_gu, w2, x2, y1, scatter, partial, recv, push, out
 
     # ---------------- sequence-parallel attention (configuration 5), causal, rank 7
     c = wl.CONFIGS[5]

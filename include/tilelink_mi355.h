@@ -236,6 +236,17 @@ int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards /*host array 
                           int topk, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/, size_t ws_bytes,
                           void* compute_stream, void* comm_stream);
 
+/* MoE part 1 with the expert FFN's activation folded into the grouped GEMM's epilogue (as tl_ag_gemm_act_mul does for the
+ * dense layer): Y1[s,:] = act(x . Wgate[e]) * (x . Wup[e]) for x = the token of sorted row s and e = its expert.
+ * w1_gate_up dev [E, H, 2F] bf16: per expert the [H, 2F] layout of tl_ag_gemm_act_mul (32 gate columns, then the same
+ * 32 up columns).  y1 dev [T*topk, F].  F % 32 == 0; tl_moe_query with I = 2F gives the geometry.  Everything else as
+ * tl_moe_ag_gather_gemm; the 224-wide tile is not available. */
+int tl_moe_ag_gather_gemm_act_mul(tl_ctx* ctx, const void* const* x_shards /*host array of dev*/, void* x_gathered /*dev*/,
+                                  const void* w1_gate_up /*dev*/, const int* sorted_row /*dev*/, const int* tile_tables /*dev*/,
+                                  const int* n_tiles /*dev*/, void* y1 /*dev*/, int T, int H, int F, int E, int topk, int act,
+                                  unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/, size_t ws_bytes,
+                                  void* compute_stream, void* comm_stream);
+
 /*
  * MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter (paper: evaluation, MoE layer: "overlaps three kernels").
  *   stage A  Z[s,:] = bf16( topk_w[row] * (X2[s,:] . W2[expert(s)]) ) stored at scatter_buf[row,:], row = sorted_row[s]

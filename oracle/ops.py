@@ -201,6 +201,24 @@ def moe_ag_gather_gemm(x_shards, w1, sorted_row, expert_offset, topk):
     return x, y, round_to_bf16(y)
 
 
+def moe_ag_gather_gemm_act_mul(x_shards, w_gate, w_up, sorted_row, expert_offset, topk, act):
+    """MoE part 1 with the expert FFN's activation: Y1[s, :] = act(x . Wgate[e]) * (x . Wup[e]) for x = the token of
+    sorted row s and e = its expert; both weights [E, H, F]; the activation (act_mul) is applied to the unrounded
+    products, one rounding.
+
+    Returns (gathered X bits, Y1 float64 [T*k, F], Y1 bf16 bits)."""
+    x = all_gather_rows(x_shards)
+    xf = widen(x)
+    E, H, F = w_gate.shape
+    y = np.zeros((len(sorted_row), F), dtype=np.float64)
+    for e in range(E):
+        lo, hi = int(expert_offset[e]), int(expert_offset[e + 1])
+        if hi > lo:
+            tokens = np.asarray(sorted_row[lo:hi], dtype=np.int64) // topk
+            y[lo:hi] = act_mul(xf[tokens] @ widen(w_gate[e]), xf[tokens] @ widen(w_up[e]), act)
+    return x, y, round_to_bf16(y)
+
+
 # ---------------------------------------------------------------------------
 # MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter
 # ---------------------------------------------------------------------------

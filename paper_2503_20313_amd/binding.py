@@ -63,6 +63,7 @@ _ip, _fp = ctypes.c_void_p, ctypes.c_void_p
 _lib.tl_moe_query.argtypes = [_vp, _i, _i, _i, _i, _i, _i, ctypes.POINTER(_i)]
 _lib.tl_moe_route.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.tl_moe_ag_gather_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_moe_ag_gather_gemm_act_mul.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_moe_gemm_scatter_rs.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp,
                                         _i, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_sp_ag_attention.restype = _i
@@ -190,6 +191,13 @@ def tl_moe_query(ctx, op, T, H, I, E, topk):
 def tl_moe_route(ctx, gate_logits, T, E, topk, renormalize, tile_m, topk_ids, topk_w, expert_offsets, sorted_row, tile_tables, n_tiles, stream=None):
     _check(_lib.tl_moe_route(ctx, _ptr(gate_logits), T, E, topk, int(renormalize), tile_m, _ptr(topk_ids), _ptr(topk_w), _ptr(expert_offsets),
                              _ptr(sorted_row), _ptr(tile_tables), _ptr(n_tiles), _stream(stream)))
+
+
+def tl_moe_ag_gather_gemm_act_mul(ctx, x_shards, x_gathered, w1_gate_up, sorted_row, tile_tables, n_tiles, y1, T, H, F, E, topk, act, flags, epoch,
+                                  workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_moe_ag_gather_gemm_act_mul(ctx, _ptr_array(x_shards), _ptr(x_gathered), _ptr(w1_gate_up), _ptr(sorted_row), _ptr(tile_tables),
+                                              _ptr(n_tiles), _ptr(y1), T, H, F, E, topk, act, _ptr(flags), epoch, _ptr(workspace), ws_bytes,
+                                              _stream(compute_stream), _stream(comm_stream)))
 
 
 def tl_moe_ag_gather_gemm(ctx, x_shards, x_gathered, w1, sorted_row, tile_tables, n_tiles, y1, T, H, I, E, topk, flags, epoch, workspace, ws_bytes,

@@ -182,7 +182,8 @@ struct MoeP1Params {
   const int* sorted_row;
   const int* tile_tables;
   const int* n_row_tiles;   // device: number of row tiles (from the routing)
-  int H, I, topk;
+  int H, I, topk;           // I = columns of the GEMM (twice the output features with an activation)
+  int act;                  // 0, or ACT_*: W1 holds gate and up columns, y1 = act(gate) * up has I/2 columns
   int nbn, G, group_m, swizzle;
   int n_comm, do_compute, do_wait;
 };
@@ -221,8 +222,9 @@ __device__ __forceinline__ int long_tiles_first(const int* tile_tables, int n, i
   return n_long;  // meaningful in wave 0 only: the caller broadcasts it
 }
 
-template <class Cfg>
+template <class Cfg, bool GATED = false>
 __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const MoeP1Params p) {
+  typedef typename std::conditional<GATED, GatedRows, DenseRows>::type Out;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_ticket;
   __shared__ int s_n_long;
@@ -263,8 +265,11 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     if (p.do_wait) consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
     // empty 32-row blocks are skipped where a wave owns several of them (measured: the branch per matrix instruction costs
     // the small tiles more than the skipped work saves)
-    gemm_tile<Cfg, DenseRows, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                                                       DenseRows{p.y1 + (long)f_lo * p.I + col_lo, p.I}, rows, cols, p.H, smem);
+    Out out;
+    if constexpr (GATED) out = Out{p.y1 + (long)f_lo * (p.I / 2) + col_lo / 2, p.I / 2, p.act};
+    else out = Out{p.y1 + (long)f_lo * p.I + col_lo, p.I};
+    gemm_tile<Cfg, Out, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                                        out, rows, cols, p.H, smem);
   };
   // the long tiles, in the usual order
   for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
@@ -431,7 +436,7 @@ struct MoeResolved {
   int Tt;                                                                     // top-k reduce / RS tile rows (part 2)
 };
 
-static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk, MoeResolved* r) {
+static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk, MoeResolved* r, bool paired_columns = false) {
   const tl_config& c = ctx->cfg;
   const int R = c.world_size;
   if (T <= 0 || H <= 0 || I <= 0 || E <= 0 || topk <= 0) return fail(TL_ERR_INVALID_ARG, "T, H, I, E, topk must be positive");
@@ -457,8 +462,9 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
       long tiles = ((long)T * topk / 256 + E / 2) * ceil_div(N, tn), G = ctx->num_cus;
       return (double)tiles * tn / (double)((tiles + G - 1) / G * G);
     };
-    v = (N % 224 == 0 && (N % 256 != 0 || fill(224) > 1.25 * fill(256))) ? TILE_256x224 : TILE_256x256;
+    v = (!paired_columns && N % 224 == 0 && (N % 256 != 0 || fill(224) > 1.25 * fill(256))) ? TILE_256x224 : TILE_256x256;
   }
+  if (paired_columns && v == TILE_256x224) return fail(TL_ERR_UNSUPPORTED_SHAPE, "the gated epilogue pairs 32-wide column blocks: the 256x224 tile has seven per wave");
   r->variant = v;
   r->tile_m = kTileM[v];
   r->tile_n = kTileN[v];
@@ -543,16 +549,16 @@ int tl_moe_route(tl_ctx* ctx, const float* gate_logits, int T, int E, int topk, 
   return TL_OK;
 }
 
-int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1, const int* sorted_row,
-                          const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E, int topk, unsigned* flags,
-                          unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+static int moe_p1_impl(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1, const int* sorted_row,
+                       const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E, int topk, int act, unsigned* flags,
+                       unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
   if (int e = check_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!x_shards || !x_gathered || !w1 || !sorted_row || !tile_tables || !n_tiles || !y1 || !flags || !workspace)
     return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: null pointer argument");
   if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: epoch starts at 1");
   MoeResolved r;
-  if (int e = resolve_moe(ctx, TL_OP_MOE_AG_GATHER_GEMM, T, H, I, E, topk, &r)) return e;
+  if (int e = resolve_moe(ctx, TL_OP_MOE_AG_GATHER_GEMM, T, H, I, E, topk, &r, act != 0)) return e;
   if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_moe_ag_gather_gemm: workspace of %zu bytes, 256 needed", ws_bytes);
   for (int q = 0; q < cfg.world_size; q++)
     if (!x_shards[q] || !aligned16(x_shards[q])) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: x_shards[%d] is null or misaligned", q);
@@ -571,12 +577,17 @@ int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards, void* x_gath
   p.tile_tables = tile_tables;
   p.n_row_tiles = n_tiles;
   p.H = H; p.I = I; p.topk = topk;
+  p.act = act;
   p.nbn = r.nbn; p.G = r.G; p.swizzle = cfg.xcd_swizzle;
   p.group_m = cfg.group_m > 0 ? cfg.group_m : 4;
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
   const bool alone = cfg.comm_alone != 0;
   p.do_compute = alone ? 0 : 1;
   auto launch = [&](int grid) {
+    if (act) {
+      if (r.variant == TILE_256x256) return launch_fused<Cfg256x256>(moe_ag_gather_gemm_kernel<Cfg256x256, true>, p, grid, cs);
+      return launch_fused<Cfg128x128>(moe_ag_gather_gemm_kernel<Cfg128x128, true>, p, grid, cs);
+    }
     return launch_moe<MoeP1Params>(r.variant, moe_ag_gather_gemm_kernel<Cfg256x256>, moe_ag_gather_gemm_kernel<Cfg256x224>,
                                    moe_ag_gather_gemm_kernel<Cfg128x128>, p, grid, cs);
   };
@@ -595,6 +606,23 @@ int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards, void* x_gath
       return alone ? TL_OK : launch(r.G);
   }
   return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: unknown comm_mode");
+}
+
+int tl_moe_ag_gather_gemm(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1, const int* sorted_row,
+                          const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E, int topk, unsigned* flags,
+                          unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  return moe_p1_impl(ctx, x_shards, x_gathered, w1, sorted_row, tile_tables, n_tiles, y1, T, H, I, E, topk, 0, flags, epoch, workspace, ws_bytes,
+                     compute_stream, comm_stream);
+}
+
+int tl_moe_ag_gather_gemm_act_mul(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1_gate_up, const int* sorted_row,
+                                  const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int F, int E, int topk, int act,
+                                  unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (act != TL_ACT_SILU_MUL && act != TL_ACT_GELU_MUL) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm_act_mul: unknown activation %d", act);
+  if (F <= 0 || F > (1 << 29)) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm_act_mul: F=%d out of range", F);
+  if (F % 32) return fail(TL_ERR_UNSUPPORTED_SHAPE, "tl_moe_ag_gather_gemm_act_mul: F=%d is not a multiple of 32 (gate and up alternate in blocks of 32 columns)", F);
+  return moe_p1_impl(ctx, x_shards, x_gathered, w1_gate_up, sorted_row, tile_tables, n_tiles, y1, T, H, 2 * F, E, topk, act, flags, epoch, workspace,
+                     ws_bytes, compute_stream, comm_stream);
 }
 
 int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const int* sorted_row, const int* tile_tables, const int* n_tiles,

@@ -12,6 +12,7 @@ from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
 
 pytestmark = pytest.mark.gpu
 MODES = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL}
+ACTS = {"silu": tl.TL_ACT_SILU_MUL, "gelu": tl.TL_ACT_GELU_MUL}
 
 
 def route_on_gpu(ctx, logits, T, E, k, tile_m, max_tiles, renorm=True):
@@ -59,16 +60,22 @@ def test_route_tables_bit_exact(T, E, k, R, C, tile_m, renorm):
     tl.tl_ctx_destroy(ctx)
 
 
-def run_part1(w, rank, C, mode, epochs=1, **cfg):
+def run_part1(w, rank, C, mode, epochs=1, act=None, **cfg):
+    """`act` "silu" / "gelu": the gated part 1 (W1 = gate, w1_up = up, I features each, packed per expert)."""
     T, H, I, E, k, R = w["T"], w["H"], w["I"], w["E"], w["topk"], w["world"]
     ctx = make_ctx(world_size=R, rank=rank, channels_per_rank=C, comm_mode=mode, **cfg)
-    q = tl.tl_moe_query(ctx, tl.TL_OP_MOE_AG_GATHER_GEMM, T, H, I, E, k)
+    q = tl.tl_moe_query(ctx, tl.TL_OP_MOE_AG_GATHER_GEMM, T, H, 2 * I if act else I, E, k)
     got = route_on_gpu(ctx, w["logits"], T, E, k, q["tile_m"], q["max_row_tiles"])
     ids_ref, w_ref, off_ref, srow_ref = check_routing(w, R, C, q["tile_m"], got)
     ids, tw, off, srow, tab, nt = got
     shards = [up(s) for s in w["x_shards"]]
     xg = poison((T, H))
-    w1 = up(w["w1"].reshape(E * H, I))
+    if act and I % 32:
+        w1 = poison((E * H, 2 * I))      # no packed layout exists: the call has to refuse it
+    elif act:
+        w1 = up(tl.pack_gate_up(w["w1"].reshape(E * H, I), w["w1_up"].reshape(E * H, I)))
+    else:
+        w1 = up(w["w1"].reshape(E * H, I))
     y1 = poison((T * k, I))
     flags = torch.zeros(q["n_flags"], dtype=torch.int32, device=dev())
     wsp = torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev())
@@ -82,10 +89,17 @@ def run_part1(w, rank, C, mode, epochs=1, **cfg):
                 shards[r_].copy_(up(host_shards[r_]))
             y1.copy_(poison((T * k, I)))
         torch.cuda.synchronize()
-        tl.tl_moe_ag_gather_gemm(ctx, shards, xg, w1, srow, tab, nt, y1, T, H, I, E, k, flags, epoch, wsp, q["ws_bytes"], torch.cuda.current_stream(), comm)
+        tail = (flags, epoch, wsp, q["ws_bytes"], torch.cuda.current_stream(), comm)
+        if act:
+            tl.tl_moe_ag_gather_gemm_act_mul(ctx, shards, xg, w1, srow, tab, nt, y1, T, H, I, E, k, ACTS[act], *tail)
+        else:
+            tl.tl_moe_ag_gather_gemm(ctx, shards, xg, w1, srow, tab, nt, y1, T, H, I, E, k, *tail)
         torch.cuda.synchronize()
         tl.tl_check_status(ctx, wsp)
-    x_ref, _, y_ref = ops.moe_ag_gather_gemm(host_shards, w["w1"], srow_ref, off_ref, k)
+    if act:
+        x_ref, _, y_ref = ops.moe_ag_gather_gemm_act_mul(host_shards, w["w1"], w["w1_up"], srow_ref, off_ref, k, act)
+    else:
+        x_ref, _, y_ref = ops.moe_ag_gather_gemm(host_shards, w["w1"], srow_ref, off_ref, k)
     if mode != tl.TL_COMM_NONE:
         assert np.array_equal(down(xg), x_ref)
         assert flags.cpu().numpy().tolist() == [epochs * q["expected_per_channel"]] * (R * C)
@@ -111,6 +125,28 @@ def test_part1_ragged_tiles_and_many_channels():
     w = wl.moe_inputs(640, 192, 320, 5, 3, 5, 2, config_id=43)
     run_part1(w, 2, 4, tl.TL_COMM_WAVES, epochs=2, comm_workgroups=3, tile_m=128, tile_n=128, comm_tile_m=8, comm_tile_n=64)
     run_part1(w, 2, 4, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=3, tile_m=256, tile_n=224)
+
+
+@pytest.mark.parametrize("act", ["silu", "gelu"])
+@pytest.mark.parametrize("tile,mode", [((128, 128), "waves"), ((256, 256), "side")])
+def test_part1_gated_ragged(act, tile, mode):
+    """Expert FFN activation folded into the grouped GEMM's epilogue: 5 ranks, 5 experts, top-3, 224 features per half
+    (2F = 448: a ragged last column tile for both widths), short last row tiles per expert, two epochs."""
+    w = wl.moe_inputs(640, 192, 224, 5, 3, 5, 2, config_id=45)
+    (_, _), q = run_part1(w, 2, 4, MODES[mode], epochs=2, act=act, comm_workgroups=3, tile_m=tile[0], tile_n=tile[1])
+    assert (q["tile_m"], q["tile_n"]) == tile
+
+
+def test_part1_gated_rejects_unpaired_tile_and_odd_features():
+    w = wl.moe_inputs(256, 128, 224, 4, 2, 2, 0, config_id=46)
+    with pytest.raises(tl.TileLinkError) as e:
+        run_part1(w, 0, 1, tl.TL_COMM_WAVES, act="silu", comm_workgroups=2, tile_m=256, tile_n=224)
+    assert e.value.status == tl.TL_ERR_UNSUPPORTED_SHAPE
+    w = wl.moe_inputs(256, 128, 208, 4, 2, 2, 0, config_id=46)          # F % 32 != 0
+    with pytest.raises(tl.TileLinkError) as e:
+        run_part1(w, 0, 1, tl.TL_COMM_WAVES, act="silu", comm_workgroups=2)
+    assert e.value.status == tl.TL_ERR_UNSUPPORTED_SHAPE
+    torch.cuda.synchronize()
 
 
 def run_part2(w, mode, epochs=1, **cfg):

@@ -29,6 +29,26 @@ def test_activation_values_and_identities():
     assert ops.act_mul(1.0, 2.0, "silu") != ops.act_mul(2.0, 1.0, "silu")
 
 
+def test_gated_moe_part1_is_the_composition():
+    """The gated grouped GEMM equals act_mul of the two plain grouped GEMMs (which have pins of their own), and one
+    sorted row recomputed straight from the definition."""
+    w = wl.moe_inputs(64, 32, 32, 4, 2, 2, 0, config_id=36)
+    w_up = w["w1_up"]
+    ids, _ = ops.moe_route(w["logits"], 2)[:2]
+    _, off, srow = ops.moe_sort_rows(ids, 4)
+    x, y, y_bits = ops.moe_ag_gather_gemm_act_mul(w["x_shards"], w["w1"], w_up, srow, off, 2, "silu")
+    _, g, _ = ops.moe_ag_gather_gemm(w["x_shards"], w["w1"], srow, off, 2)
+    _, u, _ = ops.moe_ag_gather_gemm(w["x_shards"], w_up, srow, off, 2)
+    assert np.array_equal(y, ops.act_mul(g, u, "silu")) and np.array_equal(y_bits, round_to_bf16(y))
+    s = 37
+    e = int(np.searchsorted(np.asarray(off), s, side="right") - 1)
+    xrow = widen(x)[int(srow[s]) // 2]
+    for f in (0, 13, 31):
+        gg = float(xrow @ widen(w["w1"][e])[:, f])
+        uu = float(xrow @ widen(w_up[e])[:, f])
+        assert y[s, f] == pytest.approx(gg / (1 + math.exp(-gg)) * uu, rel=1e-12, abs=1e-15)
+
+
 @pytest.mark.parametrize("act", ["silu", "gelu"])
 def test_gated_ag_gemm_is_the_composition(act):
     w = wl.ag_gemm_gated_inputs(64, 32, 48, 4, config_id=31)

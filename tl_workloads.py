@@ -95,7 +95,8 @@ def gemm_rs_inputs(M, N, K, world, rank, config_id=3, b_std=0.02, peer_std=None)
 
 
 def moe_inputs(T, H, I, E, topk, world, rank, config_id=4, w_std=0.02):
-    """Token shards [T/world,H], gate logits [T,E] fp32, expert weights W1 [E,H,I],
+    """Token shards [T/world,H], gate logits [T,E] fp32, expert weights W1 [E,H,I]
+    (and a second one of the same shape, the "up" projection of a gated expert FFN),
     W2 [E,I,H], an independently seeded second-half input X2 [T*topk, I] and the
     peers' partial-output slices [T/world, H]."""
     assert T % world == 0
@@ -107,7 +108,9 @@ def moe_inputs(T, H, I, E, topk, world, rank, config_id=4, w_std=0.02):
     x2 = normal_bf16((T * topk, I), 1.0, config_id, 4)
     peer_std = float(np.sqrt(I)) * w_std
     peers = [None if q == rank else normal_bf16((ts, H), peer_std, config_id, 5, q) for q in range(world)]
-    return {"x_shards": x_shards, "logits": logits, "w1": w1, "w2": w2, "x2": x2, "peer_segments": peers,
+    w1_up = normal_bf16((E, H, I), w_std, config_id, 6)
+    return {"x_shards": x_shards, "logits": logits, "w1": w1, "w1_up": w1_up, "w2": w2, "x2": x2,
+            "peer_segments": peers,
             "T": T, "H": H, "I": I, "E": E, "topk": topk, "world": world, "rank": rank}
 
 
