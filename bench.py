@@ -50,7 +50,7 @@ def cpu_baseline(np, ops, w2, w3, rank):
                       f"best of {passes} passes: {best:.1f} s ({time.time() - t_all:.1f} s in all)"}
 
 
-def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push):
+def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push, comm_wgs=0):
     """Secondary measurements, outside the timed step: the two MoE halves (configuration 4) and sequence-parallel
     attention (configuration 5, causal, the last rank = the one with the most keys), each fused, compute alone
     (communication off, gathered inputs complete) and communication alone."""
@@ -99,7 +99,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
         st = {}
         for part, op, dims in (("p1", tl.TL_OP_AG_GEMM, [M, 2 * F, H]), ("p2", tl.TL_OP_GEMM_RS, [M, H, F])):
             ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=4, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
-                                   spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push)
+                                   spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push, comm_workgroups=comm_wgs)
             ws, nf = tl.tl_query_workspace(ctx, op, dims)
             st[part] = dict(ctx=ctx, ws=ws, flags=torch.zeros(nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev))
         st["ctx"], st["wsp"] = st["p1"]["ctx"], st["p1"]["wsp"]
@@ -152,7 +152,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
 
     def moe_state(op, m, alone, C, cols=None):
         ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
-                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push)
+                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=direct_push, comm_workgroups=comm_wgs)
         q = tl.tl_moe_query(ctx, op, T, H, cols or I, E, k)
         st = dict(ctx=ctx, q=q,
                   ids=torch.zeros((T, k), dtype=torch.int32, device=dev), tw=torch.zeros((T, k), dtype=torch.float32, device=dev),
@@ -217,7 +217,8 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     o = torch.zeros((S_loc, Hd, D), dtype=torch.int16, device=dev)
 
     def at_make(m, alone):
-        ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=1, comm_mode=m, spin_timeout_us=10_000_000, comm_alone=alone)
+        ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=1, comm_mode=m, spin_timeout_us=10_000_000, comm_alone=alone,
+                               comm_workgroups=comm_wgs)
         info = tl.tl_attn_query(ctx, S, Hd, D, True)
         full = m == tl.TL_COMM_NONE
         st = dict(ctx=ctx, info=info, kg=k_full if full else torch.zeros_like(k_full), vg=v_full if full else torch.zeros_like(v_full),
@@ -464,7 +465,7 @@ def main():
                                     "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 1}
     if not args.no_extras:
         out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
-                               args.steps, args.warmup, 0 if args.no_direct_push else 1)
+                               args.steps, args.warmup, 0 if args.no_direct_push else 1, args.comm_workgroups)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops
         out["cpu_baseline"] = cpu_baseline(np, oracle_ops, w2, w3, rank)

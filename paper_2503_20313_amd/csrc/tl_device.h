@@ -408,6 +408,29 @@ __device__ __forceinline__ void sum_tile(SrcFn src, int n_src, bf16_t* dst, long
       for (int w = 0; w < NP; w++) buf_store16(pack_bf16x8(s[w]), rd, dof, ts.off(st + w, dld));
     };
     int st = 0;
+    if (n_src == 2) {
+      // two sources (top-2 routing): no running sums to keep, so the registers hold eight loads in flight instead
+      // (four chunks of both sources); a chunk's sum lives only between its unpacking and its store
+      const rsrc_t r0 = tile_rsrc(src(0), src_ld, rows, cols), r1 = tile_rsrc(src(1), src_ld, rows, cols);
+      for (; st + 4 <= ts.n_full; st += 4) {
+        u32x4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          a[u] = buf_load16(r0, so, ts.off(st + u, sld));
+          b[u] = buf_load16(r1, so, ts.off(st + u, sld));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          float s[8];
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            s[2 * e] = __uint_as_float(a[u][e] << 16) + __uint_as_float(b[u][e] << 16);
+            s[2 * e + 1] = __uint_as_float(a[u][e] & 0xffff0000u) + __uint_as_float(b[u][e] & 0xffff0000u);
+          }
+          buf_store16(pack_bf16x8(s), rd, dof, ts.off(st + u, dld));
+        }
+      }
+    }
     for (; st + POS <= ts.n_full; st += POS) group(std::integral_constant<int, POS>{}, st);
     for (; st < ts.n_steps; st++)   // fewer than POS full steps, then the partial one (rows mode): predicated per lane
       if (st < ts.n_full || st * ts.dr + ts.lane_r < rows) group(std::integral_constant<int, 1>{}, st);
