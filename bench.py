@@ -133,7 +133,28 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
             tl.tl_check_status(st[q]["ctx"], st[q]["wsp"])
             tl.tl_ctx_destroy(st[q]["ctx"])
     res["mlp_layer"] = r
-    del shards, a_full, b_gu, y, w_down, partial, recv, push, out
+
+    # ---------------- GEMM + ring ReduceScatter (MLP-5 part 2 share, rank 0): every segment's running sum passes through
+    # the reduce side (7 x 16 MiB received, 7 x 16 MiB passed on, the own segment finished)
+    wr = wl.gemm_ring_rs_inputs(M, H, F, R, 0, config_id=7)
+    a_r = up(wr["a"])
+    ring_recv = [0 if t is None else up(t) for t in wr["ring_recv"]]
+
+    def ring_make(m, alone):
+        ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=1, comm_mode=m, tile_order=tl.TL_ORDER_RING, xcd_swizzle=1,
+                               spin_timeout_us=10_000_000, comm_alone=alone, comm_workgroups=comm_wgs)
+        ws, nf = tl.tl_query_workspace(ctx, tl.TL_OP_GEMM_RS, [M, H, F])
+        st = dict(ctx=ctx, ws=ws, flags=torch.zeros(nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev))
+        torch.cuda.synchronize()
+        return st
+
+    def ring_call(st):
+        tl.tl_gemm_ring_rs(st["ctx"], a_r, w_down, partial, ring_recv, push, out, M, H, F, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
+
+    res["gemm_ring_rs"] = triple(ring_make, ring_call, 2.0 * M * H * F,
+                                 {"workload": "MLP-5 part 2 TP=8 share as a ring, rank 0: GEMM [8192,3584]x[3584,8192], running sums of 7 segments "
+                                              "received and passed on, own segment finished"})
+    del shards, a_full, b_gu, y, w_down, partial, recv, push, out, a_r, ring_recv
 
     # ---------------- MoE (configuration 4), rank 0
     c = wl.CONFIGS[4]

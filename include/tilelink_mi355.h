@@ -195,6 +195,27 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
                unsigned epoch, void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
 
 /*
+ * GEMM + ring ReduceScatter (paper: "Kernel Design", the GEMM + ring ReduceScatter kernel: local reduction, pass the
+ * partial result to the previous rank, peer_tile_wait / peer_tile_notify between neighbours).  The running sum of
+ * segment q travels rank q-1 -> q-2 -> ... -> q (indices mod R); it is bf16 on every hop.  This rank r
+ *   - starts the chain of segment r+1: its partial rows of that segment go to ring_push[r+1] unchanged,
+ *   - for every other segment q != r: ring_push[q] = bf16(partial rows + ring_recv[q]) (fp32 sum),
+ *   - ends the chain of its own segment: out = bf16(partial rows + ring_recv[r]).
+ * The GEMM and the reduce side take the segments in chain order r+1, r+2, ..., r (unless tile_order is NATURAL).
+ *   ring_recv  host array of R dev pointers; entry q != r+1 is the running sum of segment q that rank r+1 handed on,
+ *              [M/R, N] bf16 (seeded by the caller); entry r+1 ignored.
+ *   ring_push  host array of R dev pointers; entry q != r is the landing zone at rank r-1 for this rank's running sum
+ *              of segment q, [M/R, N] bf16 (written); entry r ignored.
+ *   flags, workspace, partial, out, requirements and error behaviour as tl_gemm_rs (sizes from tl_query_workspace with
+ *   TL_OP_GEMM_RS); the arrival counters are indexed by segment (raised by the library's simulated next rank for every
+ *   segment but r+1), the pushed counters by segment (every segment but r).  tl_config.rs_direct_push is ignored:
+ *   every segment passes through the reduce side.
+ */
+int tl_gemm_ring_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* ring_recv /*host array of dev*/,
+                    void* const* ring_push /*host array of dev*/, void* out, int M, int N, int K, unsigned* flags /*dev*/,
+                    unsigned epoch, void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/*
  * MoE routing -> dynamic mapping tables (paper: "Tile-Centric Mapping", dynamic mapping: lookup tables f_S_low,
  * f_S_high, f_R, f_C "filled at runtime by other dynamic logics (e.g., dynamic routing)").  Enqueued on `stream`.
  *   gate_logits dev [T,E] fp32.  Per token the `topk` experts with the largest logits are taken (equal logits: the

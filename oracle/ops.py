@@ -95,6 +95,64 @@ def gemm_rs(a, b, peer_segments, rank):
     return p, out, round_to_bf16(out)
 
 
+def ring_hop(own_rows, incoming):
+    """One hop of the ring ReduceScatter (paper: kernel design, GEMM + ring ReduceScatter: local reduction, then the
+    partial result is passed to the previous rank): the running sum that leaves a rank is its own partial rows plus
+    what it received, as a tensor of the layer's dtype; the rank that starts a chain (incoming is None) passes its
+    own rows on unchanged.  bf16 bits in, bf16 bits out."""
+    if incoming is None:
+        return np.array(own_rows, copy=True)
+    return round_to_bf16(widen(own_rows) + widen(incoming))
+
+
+def ring_rs_rank(p, ring_recv, rank):
+    """What rank `rank` of a ring ReduceScatter does with its partial result p [M,N] (bf16 bits).  The running sum of
+    segment q travels rank q-1 -> q-2 -> ... -> q (mod R): ring_recv[q] is what rank+1 handed on for segment q (None
+    for q = rank+1, whose chain starts here).
+
+    Returns (passed: list of R, entry q = the running sum handed to rank-1 for segment q, None for q = rank;
+             out bf16 bits [M/R,N] = the finished sum of segment `rank`)."""
+    R = len(ring_recv)
+    seg = p.shape[0] // R
+    passed, out = [None] * R, None
+    for step in range(R):                      # chain order: segment rank+1 first, the own segment last
+        q = (rank + 1 + step) % R
+        v = ring_hop(p[q * seg:(q + 1) * seg], None if step == 0 else ring_recv[q])
+        if q == rank:
+            out = v
+        else:
+            passed[q] = v
+    return passed, out
+
+
+def ring_reduce_scatter(partials):
+    """All R ranks of the ring at once (for checking the one-rank function against the definition of a
+    ReduceScatter): partials[r] = rank r's [M,N] partial result.  Returns (outs: entry r = rank r's [M/R,N] result,
+    recv: recv[r][q] = what rank r received for segment q)."""
+    R = len(partials)
+    seg = partials[0].shape[0] // R
+    recv = [[None] * R for _ in range(R)]
+    outs = [None] * R
+    for step in range(R):
+        for r in range(R):
+            q = (r + 1 + step) % R             # the segment rank r handles at this step
+            v = ring_hop(partials[r][q * seg:(q + 1) * seg], recv[r][q])
+            if step == R - 1:
+                outs[r] = v
+            else:
+                recv[(r - 1) % R][q] = v
+    return outs, recv
+
+
+def gemm_ring_rs(a, b, ring_recv, rank):
+    """P = bf16(A . B), then this rank's part of the ring ReduceScatter of P (ring_rs_rank).
+
+    Returns (P bits [M,N], passed, out bf16 bits)."""
+    p = round_to_bf16(widen(a) @ widen(b))
+    passed, out = ring_rs_rank(p, ring_recv, rank)
+    return p, passed, out
+
+
 # ---------------------------------------------------------------------------
 # MoE routing -> dynamic mapping tables
 # ---------------------------------------------------------------------------

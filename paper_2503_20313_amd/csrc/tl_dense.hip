@@ -157,7 +157,9 @@ __global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R,
 
 int launch_peers_arrive(const RsSide& rs, hipStream_t s) {
   int n = rs.R * rs.tiles_per_seg;
-  hipLaunchKernelGGL(peers_arrive_kernel, dim3((n + 255) / 256), dim3(256), 0, s, rs.arrived, rs.tiles_per_seg, rs.R, rs.rank);
+  // nothing arrives for the own segment -- in ring order: for the segment whose chain starts at this rank
+  const int none = rs.ring ? (rs.rank + 1) % rs.R : rs.rank;
+  hipLaunchKernelGGL(peers_arrive_kernel, dim3((n + 255) / 256), dim3(256), 0, s, rs.arrived, rs.tiles_per_seg, rs.R, none);
   TL_HIP(hipGetLastError());
   return TL_OK;
 }
@@ -529,28 +531,45 @@ int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards, void* a_gathere
   return ag_gemm_impl(ctx, a_shards, a_gathered, b_gate_up, y, M, 2 * F, K, act, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream);
 }
 
-int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv, void* const* peer_push,
-               void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes,
-               void* compute_stream, void* comm_stream) {
+}  // extern "C"
+
+// tl_gemm_rs and its ring variant.  `ring`: peer_recv[q] is the running sum of segment q handed on by the next rank (none
+// for segment rank+1, whose chain starts here), peer_push[q] the landing zone of the previous rank (none for the own
+// segment, whose sum ends in `out`); the GEMM and the reduce side walk the segments in chain order rank+1, rank+2, ..., rank.
+static int gemm_rs_impl(const char* name, bool ring, tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv,
+                        void* const* peer_push, void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace,
+                        size_t ws_bytes, void* compute_stream, void* comm_stream) {
   if (int e = check_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
-  if (!a || !b || !partial || !peer_recv || !peer_push || !out || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: null pointer argument");
-  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: epoch starts at 1");
+  if (!a || !b || !partial || !peer_recv || !peer_push || !out || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "%s: null pointer argument", name);
+  if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "%s: epoch starts at 1", name);
   Resolved r;
   if (int e = resolve_dense(ctx, TL_OP_GEMM_RS, M, N, K, &r)) return e;
-  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_gemm_rs: workspace of %zu bytes, 256 needed", ws_bytes);
+  if (ws_bytes < 256) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes, 256 needed", name, ws_bytes);
   const int R = cfg.world_size;
-  if (!aligned16(a) || !aligned16(b) || !aligned16(partial) || !aligned16(out)) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: device pointers must be 16-byte aligned");
-  for (int q = 0; q < R; q++)
-    if (q != cfg.rank && (!peer_recv[q] || !peer_push[q] || !aligned16(peer_recv[q]) || !aligned16(peer_push[q])))
-      return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: peer_recv[%d] or peer_push[%d] is null or misaligned", q, q);
+  if (!aligned16(a) || !aligned16(b) || !aligned16(partial) || !aligned16(out)) return fail(TL_ERR_INVALID_ARG, "%s: device pointers must be 16-byte aligned", name);
+  const int no_recv = ring ? (cfg.rank + 1) % R : cfg.rank;   // the segment nothing is received for
+  for (int q = 0; q < R; q++) {
+    if (q != no_recv && (!peer_recv[q] || !aligned16(peer_recv[q]))) return fail(TL_ERR_INVALID_ARG, "%s: peer_recv[%d] is null or misaligned", name, q);
+    if (q != cfg.rank && (!peer_push[q] || !aligned16(peer_push[q]))) return fail(TL_ERR_INVALID_ARG, "%s: peer_push[%d] is null or misaligned", name, q);
+  }
 
   GemmRsParams p;
   memset(&p, 0, sizeof p);
   p.a = (const bf16_t*)a; p.b = (const bf16_t*)b; p.K = K;
+  int first_rank = rs_first_rank(cfg);
+  if (ring) {
+    first_rank = no_recv;
+    if (cfg.tile_order != TL_ORDER_NATURAL && r.nbm % R == 0) r.first_block = first_rank * (r.nbm / R);
+  }
   p.sched = make_sched(ctx, r);
   fill_rs_side(ctx, &p.rs, partial, peer_recv, peer_push, out, M, N, r.tile_m, r.tile_n, r.Tm_p, r.Tn_p, flags, epoch, workspace);
-  if (cfg.tile_order != TL_ORDER_NATURAL) p.rs.rs_first_block = rs_first_rank(cfg) * (r.rows_per_rank / r.Tm_p);
+  if (cfg.tile_order != TL_ORDER_NATURAL) p.rs.rs_first_block = first_rank * (r.rows_per_rank / r.Tm_p);
+  if (ring) {
+    p.rs.ring = 1;
+    p.rs.direct = 0;   // every segment passes through the reduce side
+    if (R > 1 && !aligned128(peer_recv[cfg.rank])) p.rs.ctl.strict = 1;
+  }
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
   auto peers_arrive = [&](hipStream_t s) -> int { return launch_peers_arrive(p.rs, s); };
 
@@ -558,7 +577,7 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
   p.do_compute = alone ? 0 : 1;
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
-      if (alone) return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: comm_alone needs a comm_mode with a reduce side");
+      if (alone) return fail(TL_ERR_INVALID_ARG, "%s: comm_alone needs a comm_mode with a reduce side", name);
       p.n_comm = 0; p.do_notify = 0; p.rs.do_wait = 0;
       if (p.rs.direct == 2) p.rs.direct = 1;  // no reduce side at all in this mode
       return launch_gemm_rs(r.variant, p, r.G, cs);
@@ -567,7 +586,7 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
       p.n_comm = r.n_comm; p.do_notify = alone ? 0 : 1; p.rs.do_wait = alone ? 0 : 1;
       return launch_gemm_rs(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
-      return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: TL_COMM_EXTERNAL is not defined for this operator");
+      return fail(TL_ERR_INVALID_ARG, "%s: TL_COMM_EXTERNAL is not defined for this operator", name);
     case TL_COMM_STREAM:
     case TL_COMM_SIDE_KERNEL: {
       // The GEMM kernel is enqueued before the reduce kernel that waits on it: should both streams share a
@@ -585,7 +604,23 @@ int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const v
       return TL_OK;
     }
   }
-  return fail(TL_ERR_INVALID_ARG, "tl_gemm_rs: unknown comm_mode");
+  return fail(TL_ERR_INVALID_ARG, "%s: unknown comm_mode", name);
+}
+
+extern "C" {
+
+int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv, void* const* peer_push,
+               void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes,
+               void* compute_stream, void* comm_stream) {
+  return gemm_rs_impl("tl_gemm_rs", false, ctx, a, b, partial, peer_recv, peer_push, out, M, N, K, flags, epoch, workspace, ws_bytes,
+                      compute_stream, comm_stream);
+}
+
+int tl_gemm_ring_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* ring_recv, void* const* ring_push,
+                    void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes,
+                    void* compute_stream, void* comm_stream) {
+  return gemm_rs_impl("tl_gemm_ring_rs", true, ctx, a, b, partial, ring_recv, ring_push, out, M, N, K, flags, epoch, workspace, ws_bytes,
+                      compute_stream, comm_stream);
 }
 
 int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims, int* out, size_t cap, size_t* n) {

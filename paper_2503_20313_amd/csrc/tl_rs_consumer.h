@@ -18,6 +18,8 @@ struct RsSide {
   int do_wait;                      // wait for the producer stage's notifications
   int direct;                       // 1: the producer stage stored the other segments' rows into peer_push itself;
                                     // 2: it also reduced the own segment in its epilogue (the consumer only forwards)
+  int ring;                         // ring ReduceScatter: peer_recv[q] = the next rank's running sum of segment q,
+                                    // peer_push[q] = the previous rank's landing zone for this rank's running sum of it
   unsigned epoch;
   unsigned* ready;                  // [ncm*ncn]
   unsigned* arrived;                // [R*tiles_per_seg]
@@ -43,6 +45,36 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
     const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
     const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
     const int seg_row = row_lo - dest * p.seg_rows;
+    if (p.ring) {
+      // Ring order (paper: kernel design, GEMM + ring ReduceScatter): the running sum of segment q travels from rank
+      // q-1 down to rank q.  This rank starts the chain of segment rank+1 (its partial rows go on unchanged), adds its
+      // partial rows to what the next rank passed on for every other segment, and hands the sum to the previous rank --
+      // or, for its own segment, the last hop, stores it as the result.
+      const int start = p.rank + 1 == p.R ? 0 : p.rank + 1;
+      if (tid == 0) {
+        if (p.do_wait) {
+          unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
+          unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
+          tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);                                    // consumer_tile_wait
+        }
+        if (dest != start) tile_wait(p.arrived + dest * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + dest * p.tiles_per_seg + local);  // peer_tile_wait
+      }
+      __syncthreads();
+      const long seg_off = (long)seg_row * p.N + col_lo;
+      const bf16_t* own = p.partial + (long)row_lo * p.N + col_lo;
+      bf16_t* dst = (dest == p.rank ? p.out : p.peer_push[dest]) + seg_off;
+      if (dest == start) {   // chain start (in a world of one rank also the last hop: dst is the result)
+        copy_tile(own, p.N, dst, p.N, rows, cols, tid, nthreads);
+      } else {
+        const bf16_t* inc = p.peer_recv[dest] + seg_off;
+        sum_tile<2, 2>([&](int j) { return j == 0 ? own : inc; }, 2, dst, p.N, p.N, rows, cols, tid, nthreads);
+      }
+      if (dest != p.rank) {
+        __syncthreads();
+        if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);                         // peer_tile_notify
+      }
+      continue;
+    }
     if (p.direct == 2 && dest == p.rank) continue;  // reduced by the producer stage's epilogue
     if (tid == 0) {
       if (p.do_wait) {

@@ -94,6 +94,21 @@ def gemm_rs_inputs(M, N, K, world, rank, config_id=3, b_std=0.02, peer_std=None)
     return {"a": a, "b": b, "peer_segments": peers, "M": M, "N": N, "K": K, "world": world, "rank": rank}
 
 
+def gemm_ring_rs_inputs(M, N, K, world, rank, config_id=7, b_std=0.02):
+    """Local A [M,K], B [K,N]; for every segment q != rank+1 the running sum [M/world, N] bf16 that rank+1 hands on
+    in a ring ReduceScatter.  The chain of segment q starts at rank q-1 and comes down the ranks, so what arrives
+    here already holds (q-1-rank) mod world partial products: drawn N(0, sigma) with sigma = sqrt(that count * K) * b_std."""
+    assert M % world == 0
+    a = normal_bf16((M, K), 1.0, config_id, 0)
+    b = normal_bf16((K, N), b_std, config_id, 1)
+    seg = M // world
+    recv = []
+    for q in range(world):
+        count = (q - 1 - rank) % world
+        recv.append(None if count == 0 else normal_bf16((seg, N), float(np.sqrt(count * K)) * b_std, config_id, 2, q))
+    return {"a": a, "b": b, "ring_recv": recv, "M": M, "N": N, "K": K, "world": world, "rank": rank}
+
+
 def moe_inputs(T, H, I, E, topk, world, rank, config_id=4, w_std=0.02):
     """Token shards [T/world,H], gate logits [T,E] fp32, expert weights W1 [E,H,I]
     (and a second one of the same shape, the "up" projection of a gated expert FFN),
