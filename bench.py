@@ -259,6 +259,171 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     return res
 
 
+MLP_TABLE = {"MLP-1": (8192, 4096, 11008), "MLP-2": (8192, 4096, 14336), "MLP-3": (8192, 3584, 14336), "MLP-4": (8192, 4608, 36864),
+             "MLP-5": (8192, 8192, 28672), "MLP-6": (8192, 8192, 29568)}
+MOE_TABLE = {"MoE-1": (8192, 2048, 1536, 8, 2), "MoE-2": (8192, 2048, 1536, 32, 2), "MoE-3": (8192, 2048, 1536, 32, 5),
+             "MoE-4": (8192, 4096, 2048, 8, 2), "MoE-5": (8192, 4096, 2048, 32, 2), "MoE-6": (8192, 4096, 2048, 32, 5)}
+ATTN_TABLE = {"Attn-1": 32, "Attn-2": 64}
+
+
+def shape_table(torch, tl, dev, timed, cs, ms, mode, steps, warmup, over_ag=None, over_rs=None, only=""):
+    """The shapes of the paper's benchmark table (evaluation: "Benchmark Shapes"), one rank's TP=8 share each: fused,
+    compute alone and communication alone per operator.  Timing only: the tensors are drawn on the GPU (N(0,1)
+    activations, N(0,0.02) weights, matched peers) -- parity at these shapes is the tests' business.  The K of a
+    GEMM + ReduceScatter share is rounded down to the tile kernels' K step (I/8 = 1376 -> 1344, 3696 -> 3648)."""
+    R = 8
+    torch.manual_seed(20313)
+
+    def rnd(shape, std=1.0):
+        return (torch.randn(shape, device=dev, dtype=torch.float32) * std).to(torch.bfloat16).view(torch.int16)
+
+    def zeros(shape):
+        return torch.zeros(shape, dtype=torch.int16, device=dev)
+
+    def run3(make, call, flop):
+        t = {}
+        for name, m, alone in (("compute_alone_ms", tl.TL_COMM_NONE, 0), ("comm_alone_ms", mode, 1), ("fused_ms", mode, 0)):
+            st = make(m, alone)
+            st["epoch"] = 0
+
+            def fn(st=st):
+                st["epoch"] += 1
+                ms.wait_stream(cs)
+                call(st)
+            t[name] = timed(fn, steps, warmup)[0]
+            tl.tl_check_status(st["ctx"], st["wsp"])
+            tl.tl_ctx_destroy(st["ctx"])
+        r = {k: round(v, 4) for k, v in t.items()}
+        r["tflops"] = round(flop / t["fused_ms"] / 1e9, 1)
+        r["overlap_efficiency"] = round(max(t["compute_alone_ms"], t["comm_alone_ms"]) / t["fused_ms"], 4)
+        return r
+
+    def dense_ctx(m, alone, op, dims, C):
+        over = (over_ag if op == tl.TL_OP_AG_GEMM else over_rs) or {}
+        ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=1, **(over if m != tl.TL_COMM_NONE else {}))
+        ws, nf = tl.tl_query_workspace(ctx, op, dims)
+        info = tl.tl_resolve(ctx, op, dims)
+        st = dict(ctx=ctx, ws=ws, flags=torch.zeros(nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev), info=info)
+        torch.cuda.synchronize()
+        return st
+
+    # some hundred milliseconds of load first: the chip's clocks settle under it
+    wa, wb = torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16), torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16)
+    for _ in range(400):
+        torch.mm(wa, wb)
+    torch.cuda.synchronize()
+    del wa, wb
+    table = {}
+    for name, (S, H, I) in MLP_TABLE.items():
+        if only and not name.startswith(only):
+            continue
+        N = I // R
+        shards = [rnd((S // R, H)) for _ in range(R)]
+        full = torch.cat(shards).clone()
+        b, c = rnd((H, N), 0.02), zeros((S, N))
+
+        def ag_make(m, alone):
+            st = dense_ctx(m, alone, tl.TL_OP_AG_GEMM, [S, N, H], 4)
+            st["g"] = full if m == tl.TL_COMM_NONE else zeros((S, H))
+            return st
+
+        def ag_call(st):
+            tl.tl_ag_gemm(st["ctx"], shards, st["g"], b, c, S, N, H, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
+        row = {"ag_gemm": dict(run3(ag_make, ag_call, 2.0 * S * N * H), M=S, N=N, K=H)}
+        del shards, full, b, c
+        K = N - N % 64
+        a, b, partial = rnd((S, K)), rnd((K, H), 0.02), zeros((S, H))
+        recv = [0] + [rnd((S // R, H), K ** 0.5 * 0.02) for _ in range(1, R)]
+        push = [0] + [zeros((S // R, H)) for _ in range(1, R)]
+        out = zeros((S // R, H))
+
+        def rs_make(m, alone):
+            return dense_ctx(m, alone, tl.TL_OP_GEMM_RS, [S, H, K], 1)
+
+        def rs_call(st):
+            tl.tl_gemm_rs(st["ctx"], a, b, partial, recv, push, out, S, H, K, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
+        row["gemm_rs"] = dict(run3(rs_make, rs_call, 2.0 * S * H * K), M=S, N=H, K=K)
+        table[name] = row
+        del a, b, partial, recv, push, out
+        print(f"[shape-table] {name} {row}", file=sys.stderr, flush=True)
+
+    for name, (T, H, I_full, E, k) in MOE_TABLE.items():
+        if only and not name.startswith(only):
+            continue
+        I = I_full // R
+        x_shards = [rnd((T // R, H)) for _ in range(R)]
+        x_full = torch.cat(x_shards).clone()
+        w1, w2, x2 = rnd((E * H, I), 0.02), rnd((E * I, H), 0.02), rnd((T * k, I))
+        logits = torch.randn((T, E), device=dev, dtype=torch.float32)
+        y1, scatter, partial = zeros((T * k, I)), zeros((T * k, H)), zeros((T, H))
+        recv = [0] + [rnd((T // R, H), I ** 0.5 * 0.02) for _ in range(1, R)]
+        push = [0] + [zeros((T // R, H)) for _ in range(1, R)]
+        out = zeros((T // R, H))
+
+        def moe_state(op, m, alone, C):
+            ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                                   spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=1)
+            q = tl.tl_moe_query(ctx, op, T, H, I, E, k)
+            st = dict(ctx=ctx, q=q, ids=torch.zeros((T, k), dtype=torch.int32, device=dev), tw=torch.zeros((T, k), dtype=torch.float32, device=dev),
+                      off=torch.zeros(E + 1, dtype=torch.int32, device=dev), srow=torch.zeros(T * k, dtype=torch.int32, device=dev),
+                      tab=torch.zeros((q["max_row_tiles"], 8), dtype=torch.int32, device=dev), nt=torch.zeros(1, dtype=torch.int32, device=dev),
+                      flags=torch.zeros(q["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(q["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+            with torch.cuda.stream(cs):
+                tl.tl_moe_route(ctx, logits, T, E, k, True, q["tile_m"], st["ids"], st["tw"], st["off"], st["srow"], st["tab"], st["nt"])
+            torch.cuda.synchronize()
+            return st
+
+        def p1_make(m, alone):
+            st = moe_state(tl.TL_OP_MOE_AG_GATHER_GEMM, m, alone, 4)
+            st["xg"] = x_full if m == tl.TL_COMM_NONE else zeros((T, H))
+            return st
+
+        def p1_call(st):
+            tl.tl_moe_ag_gather_gemm(st["ctx"], x_shards, st["xg"], w1, st["srow"], st["tab"], st["nt"], y1, T, H, I, E, k, st["flags"], st["epoch"],
+                                     st["wsp"], st["q"]["ws_bytes"], cs, ms)
+
+        def p2_call(st):
+            tl.tl_moe_gemm_scatter_rs(st["ctx"], x2, w2, st["srow"], st["tab"], st["nt"], st["tw"], scatter, partial, recv, push, out, T, H, I, E, k,
+                                      st["flags"], st["epoch"], st["wsp"], st["q"]["ws_bytes"], cs, ms)
+        flop = 2.0 * T * k * H * I
+        table[name] = {"moe_ag_gather_gemm": run3(p1_make, p1_call, flop),
+                       "moe_gemm_scatter_rs": run3(lambda m, alone: moe_state(tl.TL_OP_MOE_GEMM_SCATTER_RS, m, alone, 1), p2_call, flop),
+                       "T": T, "H": H, "I_share": I, "E": E, "topk": k}
+        del x_shards, x_full, w1, w2, x2, logits, y1, scatter, partial, recv, push, out
+        print(f"[shape-table] {name} {table[name]}", file=sys.stderr, flush=True)
+
+    D, rank = 128, R - 1
+    for name, heads in ATTN_TABLE.items():
+        for S in (16384, 32768, 65536, 131072):
+            if only and not name.startswith(only):
+                continue
+            S_loc = S // R
+            q_dev = rnd((S_loc, heads, D))
+            ks, vs = [rnd((S_loc, heads, D)) for _ in range(R)], [rnd((S_loc, heads, D)) for _ in range(R)]
+            k_full, v_full = torch.cat(ks).clone(), torch.cat(vs).clone()
+            o = zeros((S_loc, heads, D))
+
+            def at_make(m, alone):
+                ctx = tl.tl_ctx_create(world_size=R, rank=rank, channels_per_rank=1, comm_mode=m, spin_timeout_us=10_000_000, comm_alone=alone)
+                info = tl.tl_attn_query(ctx, S, heads, D, True)
+                nc = m == tl.TL_COMM_NONE
+                st = dict(ctx=ctx, info=info, kg=k_full if nc else torch.zeros_like(k_full), vg=v_full if nc else torch.zeros_like(v_full),
+                          flags=torch.zeros(info["n_flags"], dtype=torch.int32, device=dev), wsp=torch.zeros(info["ws_bytes"] // 4, dtype=torch.int32, device=dev))
+                torch.cuda.synchronize()
+                return st
+
+            def at_call(st):
+                tl.tl_sp_ag_attention(st["ctx"], q_dev, ks, vs, st["kg"], st["vg"], o, S, heads, D, True, D ** -0.5, st["flags"], st["epoch"],
+                                      st["wsp"], st["info"]["ws_bytes"], cs, ms)
+            lo = rank * S_loc
+            flop = 4.0 * D * heads * (S_loc * lo + S_loc * (S_loc + 1) / 2.0)
+            table[f"{name} S={S}"] = run3(at_make, at_call, flop)
+            del q_dev, ks, vs, k_full, v_full, o
+            print(f"[shape-table] {name} S={S} {table[f'{name} S={S}']}", file=sys.stderr, flush=True)
+    return table
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -281,6 +446,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (MoE halves, sequence-parallel attention); they are outside the timed step")
+    ap.add_argument("--shape-table", action="store_true",
+                    help="instead of the timed step: every shape of the paper's benchmark table (TP=8 share, rank 0; attention rank 7), "
+                         "fused / compute alone / communication alone, as one JSON line")
+    ap.add_argument("--shape-filter", default="", help="with --shape-table: only the rows whose name starts with this (MLP, MoE-3, Attn-1, ...)")
+    ap.add_argument("--rs-comm-tile-m", type=int, default=0, help="with --shape-table: rows of a ReduceScatter reduce tile (default: the library's choice)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (5 times): the known-size kernel against which the FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
@@ -401,6 +571,13 @@ def main():
         torch.cuda.synchronize()
         return sum(a.elapsed_time(b) for a, b in evs) / steps
 
+    if args.shape_table:
+        del shards, gathered, a_full, b2, c2, a3, b3, a3_src, partial, recv, push, out3
+        table = shape_table(torch, tl, dev, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL, min(args.steps, 20), 3,
+                            over_ag=dict(ag_k_chunks=args.ag_k_chunks, comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups),
+                            over_rs=dict(comm_tile_m=args.rs_comm_tile_m, comm_workgroups=args.comm_workgroups), only=args.shape_filter)
+        print(json.dumps({"shape_table": table, "data": "synthetic", "dtype": "bf16", "n_gpus": 1}))
+        return
     flop2, flop3 = 2.0 * M * N * K, 2.0 * M3 * N3 * K3
     res = {}
     ops_ = {}
