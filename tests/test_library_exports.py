@@ -54,3 +54,12 @@ def test_pack_gate_up_layout():
     import pytest
     with pytest.raises(ValueError):
         tl.pack_gate_up(g[:, :40], u[:, :40])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU's share is all this build covers: bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "--gpus must be 1" in r.stderr and r.stdout.strip() == ""
