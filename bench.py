@@ -301,7 +301,8 @@ def shape_table(torch, tl, dev, timed, cs, ms, mode, steps, warmup, over_ag=None
     def dense_ctx(m, alone, op, dims, C):
         over = (over_ag if op == tl.TL_OP_AG_GEMM else over_rs) or {}
         ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
-                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=1, **(over if m != tl.TL_COMM_NONE else {}))
+                               spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=1,
+                               **{k: v for k, v in over.items() if m != tl.TL_COMM_NONE or k in ("tile_m", "tile_n")})
         ws, nf = tl.tl_query_workspace(ctx, op, dims)
         info = tl.tl_resolve(ctx, op, dims)
         st = dict(ctx=ctx, ws=ws, flags=torch.zeros(nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev), info=info)
@@ -574,7 +575,8 @@ def main():
     if args.shape_table:
         del shards, gathered, a_full, b2, c2, a3, b3, a3_src, partial, recv, push, out3
         table = shape_table(torch, tl, dev, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL, min(args.steps, 20), 3,
-                            over_ag=dict(ag_k_chunks=args.ag_k_chunks, comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups),
+                            over_ag=dict(ag_k_chunks=args.ag_k_chunks, comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups,
+                                         tile_m=int((args.ag_tile or "0x0").split("x")[0]), tile_n=int((args.ag_tile or "0x0").split("x")[1])),
                             over_rs=dict(comm_tile_m=args.rs_comm_tile_m, comm_workgroups=args.comm_workgroups), only=args.shape_filter)
         print(json.dumps({"shape_table": table, "data": "synthetic", "dtype": "bf16", "n_gpus": 1}))
         return
