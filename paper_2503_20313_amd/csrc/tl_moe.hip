@@ -268,8 +268,13 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     Out out;
     if constexpr (GATED) out = Out{p.y1 + (long)f_lo * (p.I / 2) + col_lo / 2, p.I / 2, p.act};
     else out = Out{p.y1 + (long)f_lo * p.I + col_lo, p.I};
-    gemm_tile<Cfg, Out, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                                        out, rows, cols, p.H, smem);
+    // full tiles take the loop without the per-instruction predicates
+    if (kSkip && rows <= Cfg::BM - 32)
+      gemm_tile<Cfg, Out, NoKWait, true>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                                         out, rows, cols, p.H, smem);
+    else
+      gemm_tile<Cfg, Out, NoKWait, false>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                                          out, rows, cols, p.H, smem);
   };
   // the long tiles, in the usual order
   for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
