@@ -268,13 +268,16 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     Out out;
     if constexpr (GATED) out = Out{p.y1 + (long)f_lo * (p.I / 2) + col_lo / 2, p.I / 2, p.act};
     else out = Out{p.y1 + (long)f_lo * p.I + col_lo, p.I};
-    // full tiles take the loop without the per-instruction predicates
-    if (kSkip && rows <= Cfg::BM - 32)
-      gemm_tile<Cfg, Out, NoKWait, true>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                                         out, rows, cols, p.H, smem);
-    else
-      gemm_tile<Cfg, Out, NoKWait, false>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                                          out, rows, cols, p.H, smem);
+    // row tiles of at most 64 rows: the deeper ring of the small tile shape (same thread count, same column range)
+    if constexpr (Cfg::BM == 256 && Cfg::BN == 256) {
+      if (rows <= Cfg64x256::BM) {
+        gemm_tile<Cfg64x256, Out>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I, out, rows, cols,
+                                  p.H, smem);
+        return;
+      }
+    }
+    gemm_tile<Cfg, Out, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                                        out, rows, cols, p.H, smem);
   };
   // the long tiles, in the usual order
   for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
@@ -506,10 +509,15 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
   return TL_OK;
 }
 
+// LDS of the 256x256 kernels of part 1: they also hold the loop of the 64-row tile shape
+constexpr int kLds256 = Cfg256x256::LDS_BYTES > Cfg64x256::LDS_BYTES ? Cfg256x256::LDS_BYTES : Cfg64x256::LDS_BYTES;
+static_assert(Cfg64x256::NTHREADS == Cfg256x256::NTHREADS && Cfg64x256::BN == Cfg256x256::BN, "the two shapes share workgroup and column range");
+
 template <class P>
-static int launch_moe(int variant, void (*k0)(const P), void (*k1)(const P), void (*k2)(const P), const P& p, int grid, hipStream_t s) {
+static int launch_moe(int variant, void (*k0)(const P), void (*k1)(const P), void (*k2)(const P), const P& p, int grid, hipStream_t s,
+                      int lds256 = Cfg256x256::LDS_BYTES) {
   switch (variant) {
-    case TILE_256x256: return launch_fused<Cfg256x256>(k0, p, grid, s);
+    case TILE_256x256: return launch_fused<Cfg256x256>(k0, p, grid, s, lds256);
     case TILE_256x224: return launch_fused<Cfg256x224>(k1, p, grid, s);
     default: return launch_fused<Cfg128x128>(k2, p, grid, s);
   }
@@ -593,11 +601,11 @@ static int moe_p1_impl(tl_ctx* ctx, const void* const* x_shards, void* x_gathere
   p.do_compute = alone ? 0 : 1;
   auto launch = [&](int grid) {
     if (act) {
-      if (r.variant == TILE_256x256) return launch_fused<Cfg256x256>(moe_ag_gather_gemm_kernel<Cfg256x256, true>, p, grid, cs);
+      if (r.variant == TILE_256x256) return launch_fused<Cfg256x256>(moe_ag_gather_gemm_kernel<Cfg256x256, true>, p, grid, cs, kLds256);
       return launch_fused<Cfg128x128>(moe_ag_gather_gemm_kernel<Cfg128x128, true>, p, grid, cs);
     }
     return launch_moe<MoeP1Params>(r.variant, moe_ag_gather_gemm_kernel<Cfg256x256>, moe_ag_gather_gemm_kernel<Cfg256x224>,
-                                   moe_ag_gather_gemm_kernel<Cfg128x128>, p, grid, cs);
+                                   moe_ag_gather_gemm_kernel<Cfg128x128>, p, grid, cs, kLds256);
   };
   switch (cfg.comm_mode) {
     case TL_COMM_NONE:
