@@ -365,6 +365,14 @@ __device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int
   }
 }
 
+// A row tile of at most 64 rows in the small tile shape with the deeper ring (see part 1).  Kept out of line: inlined
+// beside the 256x256 loop it would raise the kernel's register count above what leaves room for the reduce kernel's
+// waves on the same SIMDs.
+__device__ __attribute__((noinline)) void moe_small_scatter_tile(const bf16_t* a, long lda, const bf16_t* b, long ldb, ScatterRows out, int rows,
+                                                                 int cols, int K, char* smem) {
+  gemm_tile<Cfg64x256>(a, lda, nullptr, 1, b, ldb, out, rows, cols, K, smem);
+}
+
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const MoeP2Params p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -396,8 +404,14 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
     const int f_lo = rec[0], f_hi = rec[1], e = rec[2];
     const int col_lo = bn * Cfg::BN;
     const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.H - col_lo);
-    gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
-                   ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
+    bool small = false;
+    if constexpr (Cfg::BM == 256 && Cfg::BN == 256) small = rows <= Cfg64x256::BM;
+    if (small)
+      moe_small_scatter_tile(p.x2 + (long)f_lo * p.I, p.I, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
+                             ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
+    else
+      gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
+                     ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
     if (p.do_notify) {
       // producer_tile_notify with a count: the rows of this tile are token-ascending, so each token block receives
       // one run of them; the first row of a run adds the run's length to the block's counter.  The token block of
@@ -509,7 +523,7 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
   return TL_OK;
 }
 
-// LDS of the 256x256 kernels of part 1: they also hold the loop of the 64-row tile shape
+// LDS of the 256x256 kernels: they also hold the loop of the 64-row tile shape
 constexpr int kLds256 = Cfg256x256::LDS_BYTES > Cfg64x256::LDS_BYTES ? Cfg256x256::LDS_BYTES : Cfg64x256::LDS_BYTES;
 static_assert(Cfg64x256::NTHREADS == Cfg256x256::NTHREADS && Cfg64x256::BN == Cfg256x256::BN, "the two shapes share workgroup and column range");
 
@@ -689,7 +703,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
   p.do_compute = alone ? 0 : 1;
   auto launch = [&](int grid) {
     return launch_moe<MoeP2Params>(r.variant, moe_gemm_scatter_kernel<Cfg256x256>, moe_gemm_scatter_kernel<Cfg256x224>,
-                                   moe_gemm_scatter_kernel<Cfg128x128>, p, grid, cs);
+                                   moe_gemm_scatter_kernel<Cfg128x128>, p, grid, cs, kLds256);
   };
   // split of the communication workgroups between stage B (top-k reduce: topk reads per output tile) and stage C
   // (ReduceScatter).  Without direct push C reads and writes every tile once more: even split.  With direct push C
