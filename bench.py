@@ -21,9 +21,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk x 2.4 GHz (dense bf16 MFMA)
 # HBM/fabric bytes per fused GEMM launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md (scaled by the plain-copy calibration): mean of AG+GEMM (954 + 168 MiB)
-# and GEMM+RS with direct push (685 + 128 MiB).  A measured constant, not recomputed by this script.
-HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (954 + 168 + 685 + 128) * 2 ** 20)
+# profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md (scaled by the plain-copy calibration): mean of AG+GEMM (784 + 56 MiB, the
+# tile kernel's own work: launches without communication) and GEMM+RS with direct push (672 + 128 MiB).  A measured constant, not recomputed by this script.
+HBM_TRAFFIC_BYTES_PER_LAUNCH = int(0.5 * (784 + 56 + 672 + 128) * 2 ** 20)
 
 
 def cpu_baseline(np, ops, w2, w3, rank):
