@@ -189,9 +189,10 @@ struct MoeP1Params {
 };
 
 // Order of the row tiles of a grouped GEMM whose tiles skip their empty 32-row blocks (gemm_tile's SKIP_EMPTY): an
-// expert's last row tile is often nearly empty and then somewhat shorter than a full one (it still streams its whole
-// block of the expert's weights), so the long tiles (more than half the rows valid) go first, in the usual schedule, and the short ones are dealt out afterwards -- first,
-// two each, to the workgroups that the long tiles leave without work in their last round, then to all in turn.
+// expert's last row tile is often nearly empty and then shorter than a full one -- by half with the 64-row tile shape,
+// less otherwise, since it still streams its whole block of the expert's weights -- so the long tiles (more than half
+// the rows valid) go first, in the usual schedule, and the short ones are dealt out afterwards: first, two each, to
+// the workgroups that the long tiles leave without work in their last round, then to all in turn.
 // perm[0 .. n_long) = the long row tiles in table order, perm[n_long .. n) = the short ones.  Computed by wave 0 of
 // every workgroup from the routing tables (a few hundred entries); callers fall back to table order above kMaxPerm.
 constexpr int kMaxPerm = 2048;
@@ -263,8 +264,6 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     const int col_lo = bn * Cfg::BN;
     const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.I - col_lo);
     if (p.do_wait) consumer_wait_or_produce(p.prod, mask, tid, Cfg::NTHREADS, &s_ticket);
-    // empty 32-row blocks are skipped where a wave owns several of them (measured: the branch per matrix instruction costs
-    // the small tiles more than the skipped work saves)
     Out out;
     if constexpr (GATED) out = Out{p.y1 + (long)f_lo * (p.I / 2) + col_lo / 2, p.I / 2, p.act};
     else out = Out{p.y1 + (long)f_lo * p.I + col_lo, p.I};
@@ -276,6 +275,8 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
         return;
       }
     }
+    // empty 32-row blocks are skipped where a wave owns several of them (measured: the branch per matrix instruction costs
+    // the 128x128 tiles more than the skipped work saves)
     gemm_tile<Cfg, Out, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
                                         out, rows, cols, p.H, smem);
   };
