@@ -11,7 +11,7 @@ from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
 
 pytestmark = pytest.mark.gpu
 
-MODES = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL}
+MODES = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM}
 
 
 def run_ring(w, mode, epochs=1, **cfg):
@@ -106,6 +106,32 @@ def test_single_rank_and_direct_push_ignored():
     w = wl.gemm_ring_rs_inputs(256, 256, 128, 2, 1, config_id=83)
     ha, partial, push, out, _, _ = run_ring(w, tl.TL_COMM_SIDE_KERNEL, comm_workgroups=2, rs_direct_push=2)
     check(w, ha, partial, push, out, "ring, direct push requested")
+
+
+def test_reduce_side_alone_on_a_finished_partial():
+    """comm_alone: the ring's reduce side runs on a partial product that a call without communication left behind."""
+    w = wl.gemm_ring_rs_inputs(512, 256, 128, 4, 2, config_id=86)
+    M, N, K, R, rank = 512, 256, 128, 4, 2
+    seg = M // R
+    a, b = up(w["a"]), up(w["b"])
+    partial, out = poison((M, N)), poison((seg, N))
+    recv = [0 if t is None else up(t) for t in w["ring_recv"]]
+    push = [None if q == rank else poison((seg, N)) for q in range(R)]
+    push_arg = [0 if t is None else t for t in push]
+    comm = torch.cuda.Stream()
+    for mode, alone in ((tl.TL_COMM_NONE, 0), (tl.TL_COMM_SIDE_KERNEL, 1)):
+        ctx = make_ctx(world_size=R, rank=rank, comm_mode=mode, comm_alone=alone, comm_workgroups=3)
+        ws_bytes, n_flags = tl.tl_query_workspace(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+        flags = torch.zeros(n_flags, dtype=torch.int32, device=dev())
+        wsp = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=dev())
+        torch.cuda.synchronize()
+        tl.tl_gemm_ring_rs(ctx, a, b, partial, recv, push_arg, out, M, N, K, flags, 1, wsp, ws_bytes, torch.cuda.current_stream(), comm)
+        torch.cuda.synchronize()
+        tl.tl_check_status(ctx, wsp)
+        tl.tl_ctx_destroy(ctx)
+        if not alone:
+            assert (down(out) == 0x7FC0).all()          # no reduce side in this mode
+    check(w, w["a"], down(partial), [None if t is None else down(t) for t in push], down(out), "ring reduce side alone")
 
 
 def test_rejects_missing_buffers():
