@@ -187,7 +187,9 @@ int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards /*host array of 
  *              the library's simulated peers), then the same number of pushed counters (this rank's pushes
  *              into peer q).  Each grows by its expected count per call.
  *   With tl_config.rs_direct_push the GEMM epilogue stores each output row at its final place (own segment: `partial`,
- *   segment q: peer_push[q]) and the reduce side only forwards the notifications of the pushed tiles.
+ *   segment q: peer_push[q]).  A reduce tile of another segment that one GEMM tile fills alone is then announced to its
+ *   owner by that GEMM tile (its pushed counter moves together with its ready counter); reduce tiles that several GEMM
+ *   tiles share are announced by the reduce side once all of them have stored their part.
  *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 64 == 0, N % 8 == 0.
  */
 int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv /*host array of dev*/,
@@ -279,7 +281,7 @@ int tl_moe_ag_gather_gemm_act_mul(tl_ctx* ctx, const void* const* x_shards /*hos
  *   peer_recv / peer_push host arrays of R dev pointers, each [T/R,H] bf16; out dev [T/R,H] bf16 (written)
  *   flags dev unsigned[info[3] of tl_moe_query]: row counters | reduce-tile ready | peer arrived | pushed
  *   With tl_config.rs_direct_push stage B stores the token blocks of another rank's segment straight into peer_push[]
- *   (and those of the own segment into `partial`), and stage C only forwards their notifications.
+ *   (and those of the own segment into `partial`) and announces them to their owner itself; stage C reduces the own segment.
  *   Requirements: those of tl_moe_route, H % tile_n == 0, tokens per reduce tile | T/R.  comm_mode: NONE (stage A only),
  *   WAVES or SIDE_KERNEL.
  */

@@ -144,7 +144,19 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
       int cm_lo = row_lo / rs.Tm_r, cm_hi = (row_lo + rows - 1) / rs.Tm_r;
       int cn_lo = col_lo / rs.Tn_r, cn_hi = (col_lo + cols - 1) / rs.Tn_r;
       int ncols = cn_hi - cn_lo + 1, cnt = (cm_hi - cm_lo + 1) * ncols;
-      for (int i = tid; i < cnt; i += Cfg::NTHREADS) tile_notify(rs.ready + (cm_lo + i / ncols) * rs.ncn + cn_lo + i % ncols);
+      for (int i = tid; i < cnt; i += Cfg::NTHREADS) {
+        const int cm = cm_lo + i / ncols, cn = cn_lo + i % ncols;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // one release, then relaxed adds
+        __hip_atomic_fetch_add(rs.ready + cm * rs.ncn + cn, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // a reduce tile of another rank's segment that this tile alone fills: tell its owner right away
+        const int r_lo = cm * rs.Tm_r, c_lo = cn * rs.Tn_r;
+        const int r_n = min(rs.Tm_r, rs.M - r_lo), c_n = min(rs.Tn_r, rs.N - c_lo);
+        if (producer_notifies_peer(rs, r_lo, r_n, c_lo, c_n)) {
+          const int dest = r_lo / rs.seg_rows;
+          const int local = (cm - dest * (rs.seg_rows / rs.Tm_r)) * rs.ncn + cn;
+          __hip_atomic_fetch_add(rs.pushed + dest * rs.tiles_per_seg + local, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
     }
   }
 }

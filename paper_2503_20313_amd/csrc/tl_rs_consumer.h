@@ -27,6 +27,16 @@ struct RsSide {
   WaitCtl ctl;
 };
 
+// With direct push a reduce tile of another rank's segment is final once the producer stage has stored it.  When one
+// producer tile covers the whole reduce tile, the producer's own notification can therefore tell the owner as well
+// (peer_tile_notify straight from the producer), and the consumer has nothing left to do for that tile; tiles that
+// several producer tiles share still go through the consumer, which waits for all of them.
+__device__ __forceinline__ bool producer_notifies_peer(const RsSide& p, int row_lo, int rows, int col_lo, int cols) {
+  if (!p.direct || p.ring || !p.do_wait) return false;
+  if (row_lo / p.seg_rows == p.rank) return false;
+  return (row_lo + rows - 1) / p.tile_m == row_lo / p.tile_m && (col_lo + cols - 1) / p.tile_n == col_lo / p.tile_n;
+}
+
 // ======================================================================================
 // ReduceScatter consumer: reduce tiles of the partial product.  Own segment: wait for every
 // peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
@@ -76,6 +86,7 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
       continue;
     }
     if (p.direct == 2 && dest == p.rank) continue;  // reduced by the producer stage's epilogue
+    if (producer_notifies_peer(p, row_lo, rows, col_lo, cols)) continue;
     if (tid == 0) {
       if (p.do_wait) {
         // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
