@@ -151,6 +151,34 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     def ring_call(st):
         tl.tl_gemm_ring_rs(st["ctx"], a_r, w_down, partial, ring_recv, push, out, M, H, F, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
 
+    # ---------------- AllGather + GEMM in push mode (MLP-5 part 1 share, rank 0): the local shard also goes to seven peers
+    N1 = F
+    wp = wl.ag_gemm_inputs(M, N1, H, R, config_id=2)
+    p_shards = [up(x) for x in wp["a_shards"]]
+    p_full = torch.cat(p_shards).clone()
+    p_b, p_c = up(wp["b"]), torch.zeros((M, N1), dtype=torch.int16, device=dev)
+    p_slots = [0] + [torch.zeros((M // R, H), dtype=torch.int16, device=dev) for _ in range(1, R)]
+
+    def push_make(m, alone):
+        ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=4, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
+                               spin_timeout_us=10_000_000, comm_alone=alone, comm_workgroups=comm_wgs)
+        ws, nf = tl.tl_query_workspace(ctx, tl.TL_OP_AG_GEMM, [M, N1, H])
+        st = dict(ctx=ctx, ws=ws, flags=torch.zeros(2 * nf, dtype=torch.int32, device=dev), wsp=torch.zeros(ws // 4, dtype=torch.int32, device=dev))
+        st["g"] = p_full if m == tl.TL_COMM_NONE else torch.zeros((M, H), dtype=torch.int16, device=dev)
+        torch.cuda.synchronize()
+        return st
+
+    def push_call(st):
+        if st["g"] is p_full:       # no communication: the plain entry point on the complete matrix
+            tl.tl_ag_gemm(st["ctx"], p_shards, st["g"], p_b, p_c, M, N1, H, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
+        else:
+            tl.tl_ag_gemm_push(st["ctx"], p_shards, st["g"], p_slots, p_b, p_c, M, N1, H, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
+
+    res["ag_gemm_push"] = triple(push_make, push_call, 2.0 * M * N1 * H,
+                                 {"workload": "MLP-5 part 1 TP=8 share in push mode, rank 0: the 7 remote shards arrive (library copies standing for "
+                                              "the peers' pushes) and the local shard is pushed into 7 peer slots: twice the copy traffic of the pull form"})
+    del p_shards, p_full, p_b, p_c, p_slots
+
     res["gemm_ring_rs"] = triple(ring_make, ring_call, 2.0 * M * H * F,
                                  {"workload": "MLP-5 part 2 TP=8 share as a ring, rank 0: GEMM [8192,3584]x[3584,8192], running sums of 7 segments "
                                               "received and passed on, own segment finished"})

@@ -171,6 +171,26 @@ int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards /*host array of 
                        void* compute_stream /*hipStream_t*/, void* comm_stream /*hipStream_t*/);
 
 /*
+ * AllGather + GEMM in push mode (paper: "Data Primitives": in the push mode the producer writes its local data to all
+ * other ranks and notifies its remote consumers; tile_push_data + peer_tile_notify).  Everything tl_ag_gemm does, and
+ * the producer side also pushes every producer tile of the LOCAL shard a_shards[r] into each peer's copy of the
+ * gathered matrix and raises that peer's channel counter.  On this one-GPU stand-in the shards of the peers still
+ * arrive through the library's own copies (they stand for what the peers push); those tiles head the ticket queue, the
+ * pushes of the local shard follow.
+ *   peer_slots  host array of R dev pointers; entry q != r is the place of this rank's shard in peer q's gathered
+ *               matrix, [M/R, K] bf16 (written: an exact copy of a_shards[r]); entry r ignored.
+ *   flags       dev unsigned[R*C + R*C]: the channel flags of tl_ag_gemm, then the pushed counters, index q*C + c =
+ *               this rank's channel c delivered to peer q; each grows per call by the producer tiles of a channel
+ *               (`expected_per_channel` of tl_resolve); entries of q = r stay untouched.
+ *   comm_mode TL_COMM_WAVES or TL_COMM_SIDE_KERNEL; ag_k_chunks and link_gbps must be off.  A workspace serves one
+ *   entry point and shape (the ticket counter grows by the call's number of tickets).  All else as tl_ag_gemm.
+ */
+int tl_ag_gemm_push(tl_ctx* ctx, const void* const* a_shards /*host array of R device ptrs*/, void* a_gathered /*device*/,
+                    void* const* peer_slots /*host array of R device ptrs*/, const void* b /*device*/, void* c /*device*/, int M, int N,
+                    int K, unsigned* flags /*device*/, unsigned epoch, void* workspace /*device*/, size_t ws_bytes,
+                    void* compute_stream /*hipStream_t*/, void* comm_stream /*hipStream_t*/);
+
+/*
  * GEMM + ReduceScatter (paper: "Kernel Design", GEMM + ReduceScatter; evaluation: scatter by
  * copy, reduction on compute cores).  partial[M,N] = bf16(A[M,K] . B[K,N]) is stored locally and each
  * GEMM tile notifies the reduce tiles it covers.  A reduce tile whose rows lie in this rank's segment

@@ -42,6 +42,28 @@ def ag_gemm(a_shards, b):
     return a, c, round_to_bf16(c)
 
 
+def push_all_gather(shards):
+    """AllGather in push mode, all ranks at once (paper: data primitives, push mode: every producer writes its local
+    data to all other ranks): rank r's shard lands at rows [r*m, (r+1)*m) of every rank's gathered matrix.
+    Returns the R gathered matrices (bf16 bits)."""
+    R, m = len(shards), shards[0].shape[0]
+    gathered = [np.zeros((R * m,) + shards[0].shape[1:], dtype=shards[0].dtype) for _ in range(R)]
+    for r in range(R):                 # rank r pushes (and keeps its own rows)
+        for q in range(R):
+            gathered[q][r * m:(r + 1) * m] = shards[r]
+    return gathered
+
+
+def ag_gemm_push(a_shards, b, rank):
+    """AllGather + GEMM of rank `rank` in push mode: its gathered matrix and product as in ag_gemm, plus what it
+    delivers: slots[q] = the copy of its shard that lands in peer q's gathered matrix (None for q = rank).
+
+    Returns (gathered A bits, C float64, C bf16 bits, slots)."""
+    a, c, c_bits = ag_gemm(a_shards, b)
+    slots = [None if q == rank else np.array(a_shards[rank], copy=True) for q in range(len(a_shards))]
+    return a, c, c_bits, slots
+
+
 def act_mul(gate, up, act):
     """The activation layer between the two halves of the MLP layer (paper,
     evaluation, "MLP Layer": SiLUMul or GeLUMul), elementwise in float64:

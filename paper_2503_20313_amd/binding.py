@@ -59,6 +59,7 @@ _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i,
 _lib.tl_ag_gemm_act_mul.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_rs.argtypes = [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_ring_rs.argtypes = _lib.tl_gemm_rs.argtypes
+_lib.tl_ag_gemm_push.argtypes = [_vp, ctypes.POINTER(_vp), _vp, ctypes.POINTER(_vp), _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 
 _ip, _fp = ctypes.c_void_p, ctypes.c_void_p
 _lib.tl_moe_query.argtypes = [_vp, _i, _i, _i, _i, _i, _i, ctypes.POINTER(_i)]
@@ -180,6 +181,11 @@ def pack_gate_up(w_gate, w_up):
 def tl_gemm_rs(ctx, a, b, partial, peer_recv, peer_push, out, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
     _check(_lib.tl_gemm_rs(ctx, _ptr(a), _ptr(b), _ptr(partial), _ptr_array(peer_recv), _ptr_array(peer_push), _ptr(out), M, N, K,
                            _ptr(flags), epoch, _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_ag_gemm_push(ctx, a_shards, a_gathered, peer_slots, b, c, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_ag_gemm_push(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr_array(peer_slots), _ptr(b), _ptr(c), M, N, K, _ptr(flags), epoch,
+                                _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
 
 
 def tl_gemm_ring_rs(ctx, a, b, partial, ring_recv, ring_push, out, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):

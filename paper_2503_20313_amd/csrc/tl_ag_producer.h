@@ -29,7 +29,11 @@ struct AgProducer {
   unsigned wait_target;             // epoch * expected
   unsigned* flags;                  // [R*C*k_chunks]
   unsigned* ticket;                 // producer-tile queue head (grows by n_ptm*n_ptn per call)
-  unsigned ticket_end;              // epoch * number of producer tiles
+  unsigned ticket_end;              // epoch * number of tickets per call (producer tiles + pushes)
+  int n_out;                        // push mode: tickets n_ptm*n_ptn .. +n_out-1 each push one producer tile of the LOCAL shard
+                                    // into one peer's copy of the gathered matrix (tile_push_data) and notify that peer
+  bf16_t* peer_slots[kMaxWorld];    // where this rank's shard lands at peer q, [rows_per_rank, ld]; entry `rank` unused
+  unsigned* pushed;                 // [R * channels per rank]: this rank's rows of channel c pushed into peer q at q*cpr + c
   WaitCtl ctl;
 };
 
@@ -69,7 +73,7 @@ __device__ __forceinline__ unsigned long long pace_start(const AgProducer& p) {
 
 // Called by every lane of one wave; the result is wave-uniform.
 __device__ __forceinline__ bool claim_ticket(const AgProducer& p, unsigned* out) {
-  const unsigned count = (unsigned)(p.n_ptm * p.n_ptn);
+  const unsigned count = (unsigned)(p.n_ptm * p.n_ptn + p.n_out);
   unsigned t = lane0_fetch_add(p.ticket, 1u);
   unsigned idx = t - (p.ticket_end - count);
   // outside this call's range: the queue is empty (or the counter does not belong to this epoch, e.g. a workspace that
@@ -121,6 +125,32 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
   if (wave == 0) wave_tile_notify(p.flags + (p.k_chunks > 1 ? channel * p.k_chunks + tn : channel));
 }
 
+// Push mode (paper: data primitives, "the push mode allows the producer to write local data to all other ranks while
+// notifying its remote consumers"): ticket j of the push range is producer tile j % (tiles per shard) of the local shard,
+// bound for peer rank+1+j/(tiles per shard).  The tile is written into that peer's copy of the gathered matrix and the
+// peer's channel counter is raised (peer_tile_notify; here: the pushed counters).
+template <int DEPTH>
+__device__ __forceinline__ void push_tile(const AgProducer& p, int j, int tid, int wave, int nthreads) {
+  const int tiles_per_shard = (p.rows_per_rank / p.Tm_p) * p.n_ptn;
+  const int d = j / tiles_per_shard, t = j - d * tiles_per_shard;
+  int q = p.rank + 1 + d;
+  if (q >= p.R) q -= p.R;
+  const int tm = t / p.n_ptn, tn = t - tm * p.n_ptn;
+  const long off = (long)tm * p.Tm_p * p.ld + (long)tn * p.Tn_p;
+  copy_tile<DEPTH>(p.shards[p.rank] + off, p.ld, p.peer_slots[q] + off, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
+  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
+  const int cpr = p.rows_per_rank / p.rows_per_channel;
+  if (wave == 0) wave_tile_notify(p.pushed + q * cpr + (tm * p.Tm_p) / p.rows_per_channel);
+}
+
+// A claimed ticket of either kind.
+template <int DEPTH>
+__device__ __forceinline__ void work_ticket(const AgProducer& p, int i, int tid, int wave, int nthreads) {
+  const int n_in = p.n_ptm * p.n_ptn;
+  if (i < n_in) produce_tile<DEPTH>(p, i, tid, wave, nthreads);
+  else push_tile<DEPTH>(p, i - n_in, tid, wave, nthreads);
+}
+
 // Every branch in the two loops below is wave-uniform for the compiler too (see lane0_fetch_add).
 __device__ __forceinline__ void ag_producer(const AgProducer& p, int tid, int nthreads, int* s_ticket) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -134,7 +164,7 @@ __device__ __forceinline__ void ag_producer(const AgProducer& p, int tid, int nt
     int i = __builtin_amdgcn_readfirstlane(*s_ticket);
     __syncthreads();
     if (i < 0) break;
-    produce_tile<8>(p, i, tid, wave, nthreads);
+    work_ticket<8>(p, i, tid, wave, nthreads);
   }
 }
 
@@ -175,7 +205,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
   // for far longer than a link takes (a millisecond): then no producer is running beside this kernel (a tool that runs
   // kernels one at a time, say), and the consumers work the queue off themselves as they do without links.
   const unsigned long long patience = p.pace_q8 ? 100000ull : 0ull;
-  const unsigned queue_begin = p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn);
+  const unsigned queue_begin = p.ticket_end - (unsigned)(p.n_ptm * p.n_ptn + p.n_out);
   for (;;) {
     if (wave == 0) {
       int state = -2;  // -2: ready, -1: not ready and nothing to produce, >= 0: ticket to work off
@@ -205,7 +235,7 @@ __device__ __forceinline__ void consumer_wait_or_produce(const AgProducer& p, un
     int state = __builtin_amdgcn_readfirstlane(*s_ticket);
     __syncthreads();
     if (state == -2) break;
-    if (state >= 0) produce_tile<DEPTH>(p, state, tid, wave, nthreads);
+    if (state >= 0) work_ticket<DEPTH>(p, state, tid, wave, nthreads);
     else __builtin_amdgcn_s_sleep(8);
   }
   acquire_after_wait(p.ctl);

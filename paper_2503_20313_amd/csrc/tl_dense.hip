@@ -457,7 +457,8 @@ int tl_check_status(tl_ctx* ctx, void* workspace) {
 }
 
 static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K, int act,
-                        unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+                        unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream,
+                        void* const* peer_slots = nullptr) {
   if (int e = check_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!a_shards || !a_gathered || !b || !c || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: null pointer argument");
@@ -480,6 +481,19 @@ static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gather
   p.prod.first_src = r.first_block / (r.nbm / R > 0 ? r.nbm / R : 1) % R;
   p.prod.k_chunks = r.k_chunks;
   if (r.arrival_bpr) p.prod.interleave = 1;  // the queue follows the order in which the GEMM reads
+  if (peer_slots) {
+    // push mode: behind the tiles that arrive here, one ticket per (producer tile of the local shard, peer)
+    if (cfg.comm_mode != TL_COMM_WAVES && cfg.comm_mode != TL_COMM_SIDE_KERNEL)
+      return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_push: comm_mode must be TL_COMM_WAVES or TL_COMM_SIDE_KERNEL");
+    if (r.k_chunks > 1 || cfg.link_gbps > 0) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_push: ag_k_chunks and link_gbps do not apply to the push form");
+    for (int q = 0; q < R; q++) {
+      if (q != cfg.rank && (!peer_slots[q] || !aligned16(peer_slots[q]))) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_push: peer_slots[%d] is null or misaligned", q);
+      p.prod.peer_slots[q] = (bf16_t*)peer_slots[q];
+    }
+    p.prod.n_out = (r.rows_per_rank / r.Tm_p) * r.n_ptn * (R - 1);
+    p.prod.pushed = flags + (size_t)R * cfg.channels_per_rank * r.k_chunks;
+    p.prod.ticket_end = epoch * (unsigned)(r.n_ptm * r.n_ptn + p.prod.n_out);
+  }
   p.b = (const bf16_t*)b;
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;
@@ -541,6 +555,12 @@ int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards, void* a_gathere
   if (F <= 0 || F > (1 << 29)) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_act_mul: F=%d out of range", F);
   static_assert(TL_ACT_SILU_MUL == ACT_SILU_MUL && TL_ACT_GELU_MUL == ACT_GELU_MUL, "activation codes");
   return ag_gemm_impl(ctx, a_shards, a_gathered, b_gate_up, y, M, 2 * F, K, act, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream);
+}
+
+int tl_ag_gemm_push(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, void* const* peer_slots, const void* b, void* c, int M, int N,
+                    int K, unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
+  if (!peer_slots) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_push: peer_slots is null");
+  return ag_gemm_impl(ctx, a_shards, a_gathered, b, c, M, N, K, 0, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream, peer_slots);
 }
 
 }  // extern "C"

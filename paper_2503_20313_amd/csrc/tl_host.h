@@ -99,6 +99,8 @@ inline void fill_ag_producer(const tl_ctx* ctx, AgProducer* p, const void* const
   p->rows_per_channel = rows_per_channel;
   p->local_in_place = (const bf16_t*)shards[cfg.rank] == (const bf16_t*)gathered + (size_t)cfg.rank * rows_per_rank * ld;
   p->k_chunks = 1;
+  p->n_out = 0;
+  p->pushed = nullptr;
   // simulated links: all source ranks deliver side by side, each at link_gbps
   p->interleave = (cfg.link_gbps > 0 && n_ptm / (rows_per_rank / Tm_p) > 1) ? 1 : 0;
   p->pace_q8 = cfg.link_gbps > 0 ? (unsigned)((double)Tm_p * Tn_p * sizeof(bf16_t) * 256.0 / (cfg.link_gbps * 10.0) + 0.5) : 0;

@@ -163,3 +163,19 @@ def test_reduce_scatter_exact_integers_and_rank_selectivity():
         peers = [None if q == rank else segs[q] for q in range(R)]
         out = ops.reduce_scatter_segment(own, peers, rank)
         assert np.all(out == 10.0 + sum(q + 1 for q in range(R) if q != rank))
+
+
+def test_push_all_gather_gives_every_rank_the_gathered_matrix():
+    """Push mode delivers the same matrix as the definition of AllGather (rows of rank r at r*m), at every rank, and a
+    rank's deliveries are exact copies of its shard."""
+    R = 4
+    shards = [wl.normal_bf16((6, 8), 1.0, 93, 0, r) for r in range(R)]
+    want = ops.all_gather_rows(shards)
+    for g in ops.push_all_gather(shards):
+        assert np.array_equal(g, want)
+    assert np.array_equal(want[2 * 6:3 * 6], shards[2]) and not np.array_equal(want[0:6], shards[2])
+    w = wl.ag_gemm_inputs(32, 16, 64, 4, config_id=94)
+    a, c, c_bits, slots = ops.ag_gemm_push(w["a_shards"], w["b"], 1)
+    a2, c2, c_bits2 = ops.ag_gemm(w["a_shards"], w["b"])
+    assert np.array_equal(a, a2) and np.array_equal(c_bits, c_bits2)
+    assert slots[1] is None and all(np.array_equal(slots[q], w["a_shards"][1]) for q in (0, 2, 3))
