@@ -99,6 +99,12 @@ def test_ragged_and_mismatched_reduce_tiles(tile, rt, direct):
     check(w, ha, partial, push, out, f"ragged tile={tile} reduce={rt} direct={direct}", direct=bool(direct))
     table = omap.rs_tile_table(1120, 456, 4, 1, tile[0], tile[1], rt[0], rt[1])
     assert flags[:len(table)].tolist() == [2 * e[7] for e in table]
+    # every reduce tile of another rank's segment is announced to its owner exactly once per call, whether the GEMM tile
+    # that fills it alone does so itself (direct push) or the reduce side forwards it; nothing is announced for the own segment
+    n_rt, tps = len(table), len(table) // 4
+    pushed = flags[n_rt + 4 * tps:n_rt + 8 * tps].reshape(4, tps)
+    for q in range(4):
+        assert pushed[q].tolist() == [0 if q == 1 else 2] * tps, f"pushed counters of segment {q}"
 
 
 @pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (7, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0), (5, tl.TL_ORDER_OWN_FIRST, 1)])
