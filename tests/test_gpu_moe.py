@@ -208,6 +208,13 @@ def run_part2(w, mode, epochs=1, **cfg):
     f = flags.cpu().numpy()
     assert f[:ntb * nbn].tolist() == [epochs * Tt * k] * (ntb * nbn)
     assert f[ntb * nbn:2 * ntb * nbn].tolist() == [epochs] * (ntb * nbn)
+    # ... then the peers' arrivals (simulated: all but the own segment's row) and this rank's announcements to the owners:
+    # once per call for every reduce tile of another segment, by stage B itself with direct push, else by stage C
+    tps = (ntb // R) * nbn
+    arrived = f[2 * ntb * nbn:2 * ntb * nbn + R * tps].reshape(R, tps)
+    pushed = f[2 * ntb * nbn + R * tps:2 * ntb * nbn + 2 * R * tps].reshape(R, tps)
+    for q_ in range(R):
+        assert arrived[q_].tolist() == [0 if q_ == rank else epochs] * tps and pushed[q_].tolist() == [0 if q_ == rank else epochs] * tps
     return q
 
 
