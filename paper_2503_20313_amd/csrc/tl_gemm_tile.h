@@ -121,24 +121,13 @@ struct GatedRows {
 // With Out::GATED the tile's columns come in pairs of 32 (gate, up): out.apply(gate, up) is stored, at half the column.
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
 // masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
-// SKIP_EMPTY: a wave leaves out the matrix instructions (and the A fragment reads) of its 32-row blocks that lie
-// entirely below the tile's last valid row: for tiles that are often short (the last row tile of an expert).
-template <class Cfg, class Out, class KW = NoKWait, bool SKIP_EMPTY = false>
+template <class Cfg, class Out, class KW = NoKWait>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
                                           char* smem, const KW& kw = KW{}) {
   constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
-  // 32-row blocks of this wave that hold valid rows (wave-uniform, and known to be so to the compiler)
-  int mt_valid = Cfg::MT;
-  if constexpr (SKIP_EMPTY) {
-    const int wm_u = __builtin_amdgcn_readfirstlane(tid >> 6) / Cfg::WN;
-    int v = rows - wm_u * Cfg::WTM;
-    v = v < 0 ? 0 : (v > Cfg::WTM ? Cfg::WTM : v);
-    mt_valid = __builtin_amdgcn_readfirstlane((v + 31) / 32);
-  }
-
   // ---- per-lane global addresses of this wave's share of the stage loads
   const char* a_src[Cfg::A_PER_WAVE];
   const char* b_src[Cfg::B_PER_WAVE];
@@ -225,7 +214,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       bfr[BUF][R] = __builtin_bit_cast(bf16x8, v);
     } else {
       constexpr int MTI = R - Cfg::NT;
-      if (!SKIP_EMPTY || MTI < mt_valid) af[BUF][MTI] = *(const bf16x8*)(st + a_off + MTI * 32 * Cfg::A_PITCH + ((a_x ^ (2 * sl)) << 4));
+      af[BUF][MTI] = *(const bf16x8*)(st + a_off + MTI * 32 * Cfg::A_PITCH + ((a_x ^ (2 * sl)) << 4));
     }
   };
   // One k-slice in fixed program order: the MFMAs of the slice held in register set CUR, with the
@@ -243,7 +232,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     static_for<0, N_MFMA>([&](auto m_c) {
       constexpr int M = decltype(m_c)::value;
       constexpr int MTI = M / Cfg::NT, NTI = M % Cfg::NT;
-      if (!SKIP_EMPTY || MTI < mt_valid) acc[MTI][NTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[CUR][NTI], af[CUR][MTI], acc[MTI][NTI], 0, 0, 0);
+      acc[MTI][NTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[CUR][NTI], af[CUR][MTI], acc[MTI][NTI], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (BS >= 0) {
         constexpr int G = BS * N_MFMA + M;  // MFMA index inside the loop body

@@ -188,11 +188,10 @@ struct MoeP1Params {
   int n_comm, do_compute, do_wait;
 };
 
-// Order of the row tiles of a grouped GEMM whose tiles skip their empty 32-row blocks (gemm_tile's SKIP_EMPTY): an
-// expert's last row tile is often nearly empty and then shorter than a full one -- by half with the 64-row tile shape,
-// less otherwise, since it still streams its whole block of the expert's weights -- so the long tiles (more than half
-// the rows valid) go first, in the usual schedule, and the short ones are dealt out afterwards: first, two each, to
-// the workgroups that the long tiles leave without work in their last round, then to all in turn.
+// Order of the row tiles of a grouped GEMM: an expert's last row tile is often nearly empty and then, in the 64-row tile
+// shape, takes half the time of a full one (it still streams its whole block of the expert's weights) -- so the long
+// tiles (more than half the rows valid) go first, in the usual schedule, and the short ones are dealt out afterwards:
+// first, two each, to the workgroups that the long tiles leave without work in their last round, then to all in turn.
 // perm[0 .. n_long) = the long row tiles in table order, perm[n_long .. n) = the short ones.  Computed by wave 0 of
 // every workgroup from the routing tables (a few hundred entries); callers fall back to table order above kMaxPerm.
 constexpr int kMaxPerm = 2048;
@@ -223,6 +222,14 @@ __device__ __forceinline__ int long_tiles_first(const int* tile_tables, int n, i
   return n_long;  // meaningful in wave 0 only: the caller broadcasts it
 }
 
+// A row tile of at most 64 rows in the small tile shape with the deeper ring.  Out of line: inlined beside the 256x256
+// loop it takes the kernel to 256 registers, which leaves no room for a producer wave beside two of its waves.
+template <class Out>
+__device__ __attribute__((noinline)) void moe_small_gather_tile(const bf16_t* a, long lda, const int* a_rows, int a_div, const bf16_t* b, long ldb,
+                                                                Out out, int rows, int cols, int K, char* smem) {
+  gemm_tile<Cfg64x256, Out>(a, lda, a_rows, a_div, b, ldb, out, rows, cols, K, smem);
+}
+
 template <class Cfg, bool GATED = false>
 __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const MoeP1Params p) {
   typedef typename std::conditional<GATED, GatedRows, DenseRows>::type Out;
@@ -239,8 +246,8 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
   __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   const int n_rt = *p.n_row_tiles;
-  constexpr bool kSkip = Cfg::MT >= 4;   // short tiles are cheaper only where their empty blocks are skipped
-  const bool reorder = kSkip && n_rt <= kMaxPerm;
+  constexpr bool kSmallShape = Cfg::BM == 256 && Cfg::BN == 256;   // short tiles are cheaper only where they have a shape of their own
+  const bool reorder = kSmallShape && n_rt <= kMaxPerm;
   int n_long = n_rt;
   if (reorder) {
     int nl = long_tiles_first(p.tile_tables, n_rt, Cfg::BM, s_perm, tid);
@@ -268,17 +275,15 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
     if constexpr (GATED) out = Out{p.y1 + (long)f_lo * (p.I / 2) + col_lo / 2, p.I / 2, p.act};
     else out = Out{p.y1 + (long)f_lo * p.I + col_lo, p.I};
     // row tiles of at most 64 rows: the deeper ring of the small tile shape (same thread count, same column range)
-    if constexpr (Cfg::BM == 256 && Cfg::BN == 256) {
+    if constexpr (kSmallShape) {
       if (rows <= Cfg64x256::BM) {
-        gemm_tile<Cfg64x256, Out>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I, out, rows, cols,
-                                  p.H, smem);
+        moe_small_gather_tile<Out>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I, out, rows, cols,
+                                   p.H, smem);
         return;
       }
     }
-    // empty 32-row blocks are skipped where a wave owns several of them (measured: the branch per matrix instruction costs
-    // the 128x128 tiles more than the skipped work saves)
-    gemm_tile<Cfg, Out, NoKWait, kSkip>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
-                                        out, rows, cols, p.H, smem);
+    gemm_tile<Cfg, Out>(p.prod.gathered, p.H, p.sorted_row + f_lo, p.topk, p.w1 + (long)e * p.H * p.I + col_lo, p.I,
+                        out, rows, cols, p.H, smem);
   };
   // the long tiles, in the usual order
   for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
