@@ -313,7 +313,11 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, b
       if (c.tile_order == TL_ORDER_ARRIVAL && r->nbm % R == 0 && R > 1) r->arrival_bpr = r->nbm / R;
     }
   } else {
-    int Tm_r = c.comm_tile_m ? c.comm_tile_m : (r->tile_m <= r->rows_per_rank ? r->tile_m : r->rows_per_rank);
+    int Tm_r = c.comm_tile_m;
+    if (Tm_r == 0) {   // the GEMM tile's rows, or the largest divisor of M/R below that
+      Tm_r = r->tile_m <= r->rows_per_rank ? r->tile_m : r->rows_per_rank;
+      while (Tm_r > 1 && r->rows_per_rank % Tm_r) Tm_r--;
+    }
     int Tn_r = c.comm_tile_n ? c.comm_tile_n : (N % r->tile_n == 0 ? r->tile_n : N);
     if (Tm_r <= 0 || r->rows_per_rank % Tm_r) return fail(TL_ERR_UNSUPPORTED_SHAPE, "reduce row tile %d must divide M/R=%d", Tm_r, r->rows_per_rank);
     if (Tn_r <= 0 || N % Tn_r || Tn_r % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "reduce column tile %d must divide N=%d and be a multiple of 8", Tn_r, N);

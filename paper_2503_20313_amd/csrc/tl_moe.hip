@@ -526,7 +526,11 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
   } else {
     // every reduce tile ends with a notification (a device-scope release, microseconds): measured at T=8192, H=4096 the
     // fused call takes 0.67 / 0.51 / 0.45 / 0.42 / 0.44 ms with 32 / 64 / 128 / 256 / 512 tokens per tile
-    int Tt = c.comm_tile_m ? c.comm_tile_m : (r->rows_per_rank >= 128 ? 128 : r->rows_per_rank);
+    int Tt = c.comm_tile_m;
+    if (Tt == 0) {   // the largest divisor of T/R up to 128
+      Tt = r->rows_per_rank >= 128 ? 128 : r->rows_per_rank;
+      while (Tt > 1 && r->rows_per_rank % Tt) Tt--;
+    }
     if (!c.comm_tile_m && r->rows_per_rank % 256 == 0 && (long)(T / 256) * r->nbn >= 2 * r->n_comm) Tt = 256;
     if (Tt <= 0 || r->rows_per_rank % Tt) return fail(TL_ERR_UNSUPPORTED_SHAPE, "top-k reduce tile of %d tokens must divide T/R=%d", Tt, r->rows_per_rank);
     if (H % r->tile_n) return fail(TL_ERR_UNSUPPORTED_SHAPE, "H=%d must be a multiple of the column tile %d", H, r->tile_n);

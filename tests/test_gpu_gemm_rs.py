@@ -107,6 +107,15 @@ def test_ragged_and_mismatched_reduce_tiles(tile, rt, direct):
         assert pushed[q].tolist() == [0 if q == 1 else 2] * tps, f"pushed counters of segment {q}"
 
 
+def test_default_reduce_tile_divides_the_segment():
+    """M/R = 224 rows per segment, no reduce tile given: the library picks a row count that divides the segment (112
+    under 128-row GEMM tiles) instead of refusing the shape."""
+    w = wl.gemm_rs_inputs(1120, 256, 128, 5, 3, config_id=23)
+    ha, partial, push, out, flags, info = run_gemm_rs(w, tl.TL_COMM_SIDE_KERNEL, epochs=2, comm_workgroups=3, rs_direct_push=1)
+    assert 224 % info["comm_tile_m"] == 0
+    check(w, ha, partial, push, out, "default reduce tile, 224-row segments", direct=True)
+
+
 @pytest.mark.parametrize("rank,order,swz", [(0, tl.TL_ORDER_RING, 1), (7, tl.TL_ORDER_RING, 1), (3, tl.TL_ORDER_NATURAL, 0), (5, tl.TL_ORDER_OWN_FIRST, 1)])
 def test_schedule_dump_matches_mapping_oracle(rank, order, swz):
     M, N, K, R = 8192, 8192, 3584, 8

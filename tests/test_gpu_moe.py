@@ -149,6 +149,13 @@ def test_part1_gated_rejects_unpaired_tile_and_odd_features():
     torch.cuda.synchronize()
 
 
+def test_part2_default_reduce_tile_divides_the_segment():
+    """T/R = 192 tokens per rank, no reduce tile given: 96-token reduce tiles instead of a refusal."""
+    w = wl.moe_inputs(768, 256, 128, 7, 3, 4, 2, config_id=47)
+    q = run_part2(w, tl.TL_COMM_SIDE_KERNEL, epochs=2, rs_direct_push=1, comm_workgroups=4)
+    assert 192 % q["tokens_per_reduce_tile"] == 0 and q["tokens_per_reduce_tile"] > 1
+
+
 def run_part2(w, mode, epochs=1, **cfg):
     T, H, I, E, k, R, rank = w["T"], w["H"], w["I"], w["E"], w["topk"], w["world"], w["rank"]
     ctx = make_ctx(world_size=R, rank=rank, comm_mode=mode, **cfg)
