@@ -53,8 +53,12 @@ enum { TL_COMM_NONE = 0,   /* data already in place: no producer runs, consumers
                               copy path (rank_copy_data + rank_notify); reduce work runs as a second kernel there */
        TL_COMM_SIDE_KERNEL = 3, /* device-side copy/reduce workgroups launched as a small-footprint kernel of their
                               own on comm_stream, so that they can share compute units with resident GEMM workgroups */
-       TL_COMM_EXTERNAL = 4 /* consumers wait on the flags but the library runs no producer: the caller (a peer,
-                              another library) moves the data and raises the flags itself */ };
+       TL_COMM_EXTERNAL = 4, /* consumers wait on the flags but the library runs no producer: the caller (a peer,
+                              another library) moves the data and raises the flags itself */
+       TL_COMM_COPY_ENGINE = 5 /* tl_ag_gemm family: as TL_COMM_STREAM, but every shard copy is handed to a copy (DMA) engine,
+                              which occupies no compute unit (rank_copy_data on the copy engine, the binding the paper's
+                              evaluation uses for the AllGather of the MLP layer); a one-wave kernel behind each copy
+                              raises the shard's flags (rank_notify).  The GEMM grid keeps every compute unit. */ };
 
 /* Tile order of the compute side. */
 enum { TL_ORDER_NATURAL = 0, /* row-major over (row block, column block) */
@@ -116,6 +120,11 @@ typedef struct tl_ctx tl_ctx;
 
 /* Creates a context for the current HIP device from *cfg (copied).  Host call. */
 int tl_ctx_create(const tl_config* cfg /*host*/, tl_ctx** out /*host*/);
+/* A context for the host-side queries only (tl_query_workspace, tl_resolve, tl_dump_schedule, tl_moe_query,
+ * tl_attn_query): no HIP call is made, `num_compute_units` stands for the device's compute-unit count (MI355X: 256).
+ * Every call that would enqueue GPU work returns TL_ERR_INVALID_ARG for such a context.  For planning on a machine
+ * without a GPU and for checking the mapping tables (paper: "Tile-Centric Mapping") on the CPU. */
+int tl_ctx_create_host(const tl_config* cfg /*host*/, int num_compute_units, tl_ctx** out /*host*/);
 int tl_ctx_destroy(tl_ctx* ctx);
 const char* tl_last_error(void);
 /* Library version string and the offload architecture it was built for. */
@@ -143,7 +152,8 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
  *              expected = (M/(R*C)/Tm_p) * ceil(K/Tn_p) in WAVES and SIDE_KERNEL mode and 1 in STREAM mode; untouched
  *              in NONE.  With ag_k_chunks in effect: unsigned[R*C*k_chunks], index channel*k_chunks + chunk, expected =
  *              M/(R*C)/Tm_p (tl_query_workspace and tl_resolve report the counts).
- *   Requirements: R | M, C | M/R, Tm_p | M/(R*C), K % 64 == 0, N % 8 == 0, Tn_p | K.
+ *   Requirements: R | M, C | M/R, R*C <= 64, Tm_p | M/(R*C), K % 8 == 0 (a last K step shorter than the kernel's is
+ *   zero-filled), N % 8 == 0, Tn_p | K; violations return TL_ERR_UNSUPPORTED_SHAPE before anything is enqueued.
  *   workspace  word 0 = status word, word 1 = head of the producer-tile queue: it grows by the number of producer
  *              tiles per call, so the caller zeroes the workspace together with the flags (once, or when `epoch`
  *              restarts at 1).  Bytes 16..23 hold the start time of the call in flight when link_gbps is set.  One call at
@@ -171,8 +181,7 @@ int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards /*host array of 
                        void* compute_stream /*hipStream_t*/, void* comm_stream /*hipStream_t*/);
 
 /*
- * AllGather + GEMM in push mode (paper: "Data Primitives": in the push mode the producer writes its local data to all
- * other ranks and notifies its remote consumers; tile_push_data + peer_tile_notify).  Everything tl_ag_gemm does, and
+ * AllGather + GEMM in push mode (paper: "Data Primitives", push mode; tile_push_data + peer_tile_notify).  Everything tl_ag_gemm does, and
  * the producer side also pushes every producer tile of the LOCAL shard a_shards[r] into each peer's copy of the
  * gathered matrix and raises that peer's channel counter.  On this one-GPU stand-in the shards of the peers still
  * arrive through the library's own copies (they stand for what the peers push); those tiles head the ticket queue, the
@@ -210,7 +219,7 @@ int tl_ag_gemm_push(tl_ctx* ctx, const void* const* a_shards /*host array of R d
  *   segment q: peer_push[q]).  A reduce tile of another segment that one GEMM tile fills alone is then announced to its
  *   owner by that GEMM tile (its pushed counter moves together with its ready counter); reduce tiles that several GEMM
  *   tiles share are announced by the reduce side once all of them have stored their part.
- *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 64 == 0, N % 8 == 0.
+ *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 8 == 0, N % 8 == 0.
  */
 int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv /*host array of dev*/,
                void* const* peer_push /*host array of dev*/, void* out, int M, int N, int K, unsigned* flags /*dev*/,
@@ -238,8 +247,8 @@ int tl_gemm_ring_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, co
                     unsigned epoch, void* workspace /*dev*/, size_t ws_bytes, void* compute_stream, void* comm_stream);
 
 /*
- * MoE routing -> dynamic mapping tables (paper: "Tile-Centric Mapping", dynamic mapping: lookup tables f_S_low,
- * f_S_high, f_R, f_C "filled at runtime by other dynamic logics (e.g., dynamic routing)").  Enqueued on `stream`.
+ * MoE routing -> dynamic mapping tables (paper: "Tile-Centric Mapping", dynamic mapping: the lookup tables f_S_low,
+ * f_S_high, f_R, f_C, which this call fills at run time from the routing).  Enqueued on `stream`.
  *   gate_logits dev [T,E] fp32.  Per token the `topk` experts with the largest logits are taken (equal logits: the
  *               lower expert index first; listed by descending logit); weight = softmax over all E experts,
  *               divided by the sum over the selected ones if `renormalize`.
@@ -291,7 +300,7 @@ int tl_moe_ag_gather_gemm_act_mul(tl_ctx* ctx, const void* const* x_shards /*hos
                                   void* compute_stream, void* comm_stream);
 
 /*
- * MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter (paper: evaluation, MoE layer: "overlaps three kernels").
+ * MoE part 2: GroupGEMM + Scatter + TopkReduce + ReduceScatter (paper: evaluation, MoE layer: three overlapped kernels).
  *   stage A  Z[s,:] = bf16( topk_w[row] * (X2[s,:] . W2[expert(s)]) ) stored at scatter_buf[row,:], row = sorted_row[s]
  *   stage B  partial[t,:] = bf16( sum_j scatter_buf[t*topk+j,:] )            (fp32 sum)
  *   stage C  ReduceScatter of partial over ranks as in tl_gemm_rs (own segment reduced into `out`, others pushed)

@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtilelink_mi355.so")
 
 TL_OK, TL_ERR_INVALID_ARG, TL_ERR_UNSUPPORTED_SHAPE, TL_ERR_WORKSPACE_TOO_SMALL, TL_ERR_HIP, TL_ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
-TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_EXTERNAL = 0, 1, 2, 3, 4
+TL_COMM_NONE, TL_COMM_WAVES, TL_COMM_STREAM, TL_COMM_SIDE_KERNEL, TL_COMM_EXTERNAL, TL_COMM_COPY_ENGINE = 0, 1, 2, 3, 4, 5
 TL_ORDER_NATURAL, TL_ORDER_RING, TL_ORDER_OWN_FIRST, TL_ORDER_ARRIVAL = 0, 1, 2, 3
 TL_ACT_SILU_MUL, TL_ACT_GELU_MUL = 1, 2
 TL_OP_AG_GEMM, TL_OP_GEMM_RS, TL_OP_MOE_AG_GATHER_GEMM, TL_OP_MOE_GEMM_SCATTER_RS, TL_OP_SP_AG_ATTENTION = 0, 1, 2, 3, 4
@@ -50,6 +50,7 @@ _vp, _i, _u, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
 _lib.tl_last_error.restype = ctypes.c_char_p
 _lib.tl_version.restype = ctypes.c_char_p
 _lib.tl_ctx_create.argtypes = [ctypes.POINTER(tl_config), ctypes.POINTER(_vp)]
+_lib.tl_ctx_create_host.argtypes = [ctypes.POINTER(tl_config), _i, ctypes.POINTER(_vp)]
 _lib.tl_ctx_destroy.argtypes = [_vp]
 _lib.tl_query_workspace.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
 _lib.tl_check_status.argtypes = [_vp, _vp]
@@ -118,6 +119,13 @@ def tl_ctx_create(**fields):
     cfg = tl_config(**fields)
     ctx = _vp()
     _check(_lib.tl_ctx_create(ctypes.byref(cfg), ctypes.byref(ctx)))
+    return ctx
+
+
+def tl_ctx_create_host(num_compute_units=256, **fields):
+    cfg = tl_config(**fields)
+    ctx = _vp()
+    _check(_lib.tl_ctx_create_host(ctypes.byref(cfg), num_compute_units, ctypes.byref(ctx)))
     return ctx
 
 

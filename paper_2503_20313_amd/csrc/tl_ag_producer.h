@@ -125,8 +125,7 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
   if (wave == 0) wave_tile_notify(p.flags + (p.k_chunks > 1 ? channel * p.k_chunks + tn : channel));
 }
 
-// Push mode (paper: data primitives, "the push mode allows the producer to write local data to all other ranks while
-// notifying its remote consumers"): ticket j of the push range is producer tile j % (tiles per shard) of the local shard,
+// Push mode (paper: "Data Primitives", push mode): ticket j of the push range is producer tile j % (tiles per shard) of the local shard,
 // bound for peer rank+1+j/(tiles per shard).  The tile is written into that peer's copy of the gathered matrix and the
 // peer's channel counter is raised (peer_tile_notify; here: the pushed counters).
 template <int DEPTH>

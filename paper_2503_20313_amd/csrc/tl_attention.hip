@@ -421,7 +421,7 @@ int tl_attn_query(const tl_ctx* ctx, int S, int heads, int head_dim, int causal,
 int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, const void* const* v_shards, void* k_gathered,
                        void* v_gathered, void* o, int S, int heads, int head_dim, int causal, float scale, unsigned* flags, unsigned epoch,
                        void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!q || !k_shards || !v_shards || !k_gathered || !v_gathered || !o || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: null pointer argument");
   if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: epoch starts at 1");
@@ -434,7 +434,7 @@ int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, 
   for (int s = 0; s < R; s++)
     if (!k_shards[s] || !v_shards[s] || !aligned16(k_shards[s]) || !aligned16(v_shards[s]))
       return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: k_shards[%d] or v_shards[%d] is null or misaligned", s, s);
-  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL || cfg.comm_mode == TL_COMM_COPY_ENGINE)
     return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: comm_mode must be NONE, WAVES or SIDE_KERNEL");
 
   AttnParams p;

@@ -211,7 +211,7 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, b
   if (M <= 0 || N <= 0 || K <= 0) return fail(TL_ERR_INVALID_ARG, "M, N, K must be positive (got %d, %d, %d)", M, N, K);
   const int R = c.world_size;
   if (M % R) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d must divide M=%d", R, M);
-  if (K % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 64", K);  // every tile shape steps K by 32 or 64
+  if (K % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "K=%d must be a multiple of 8 (rows of 16-byte pieces)", K);  // a short last K step is zero-filled
   if (N % 8) return fail(TL_ERR_UNSUPPORTED_SHAPE, "N=%d must be a multiple of 8", N);
   if (paired_columns && N % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "gate and up columns alternate in blocks of 32: 2F=%d must be a multiple of 64", N);
   memset(r, 0, sizeof *r);
@@ -268,6 +268,8 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, b
   // ---- communication tiles
   if (op == TL_OP_AG_GEMM) {
     const int C = c.channels_per_rank;
+    // the consumer's wait set is a 64-bit mask over the global channel index
+    if ((long)R * C > 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "world size %d x channels per rank %d = %ld channels; at most 64 are supported", R, C, (long)R * C);
     if (r->rows_per_rank % C) return fail(TL_ERR_UNSUPPORTED_SHAPE, "channels per rank %d must divide M/R=%d", C, r->rows_per_rank);
     r->rows_per_channel = r->rows_per_rank / C;
     int Tm_p = c.comm_tile_m;
@@ -375,16 +377,21 @@ extern "C" {
 const char* tl_last_error(void) { return g_err; }
 const char* tl_version(void) { return "tilelink_mi355 0.1 (gfx950)"; }
 
-int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
-  if (!cfg || !out) return fail(TL_ERR_INVALID_ARG, "cfg and out must not be null");
+static int check_config(const tl_config* cfg) {
   if (cfg->world_size < 1 || cfg->world_size > kMaxWorld) return fail(TL_ERR_INVALID_ARG, "world_size %d outside [1,%d]", cfg->world_size, kMaxWorld);
   if (cfg->rank < 0 || cfg->rank >= cfg->world_size) return fail(TL_ERR_INVALID_ARG, "rank %d outside [0,%d)", cfg->rank, cfg->world_size);
   if (cfg->channels_per_rank < 1) return fail(TL_ERR_INVALID_ARG, "channels_per_rank must be >= 1");
-  if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_EXTERNAL) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
+  if (cfg->comm_mode < TL_COMM_NONE || cfg->comm_mode > TL_COMM_COPY_ENGINE) return fail(TL_ERR_INVALID_ARG, "unknown comm_mode %d", cfg->comm_mode);
   if (cfg->tile_order < TL_ORDER_NATURAL || cfg->tile_order > TL_ORDER_ARRIVAL) return fail(TL_ERR_INVALID_ARG, "unknown tile_order %d", cfg->tile_order);
   if (cfg->link_gbps < 0) return fail(TL_ERR_INVALID_ARG, "link_gbps must not be negative");
   if (cfg->comm_workgroups < 0 || cfg->compute_workgroups < 0 || cfg->comm_tile_m < 0 || cfg->comm_tile_n < 0 || cfg->group_m < 0)
     return fail(TL_ERR_INVALID_ARG, "negative workgroup count or tile size");
+  return TL_OK;
+}
+
+int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
+  if (!cfg || !out) return fail(TL_ERR_INVALID_ARG, "cfg and out must not be null");
+  if (int e = check_config(cfg)) return e;
   int dev = 0;
   TL_HIP(hipGetDevice(&dev));
   hipDeviceProp_t prop;
@@ -394,6 +401,18 @@ int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
   c->cfg = *cfg;
   c->device = dev;
   c->num_cus = prop.multiProcessorCount;
+  *out = c;
+  return TL_OK;
+}
+
+int tl_ctx_create_host(const tl_config* cfg, int num_compute_units, tl_ctx** out) {
+  if (!cfg || !out) return fail(TL_ERR_INVALID_ARG, "cfg and out must not be null");
+  if (num_compute_units < 1) return fail(TL_ERR_INVALID_ARG, "num_compute_units must be positive");
+  if (int e = check_config(cfg)) return e;
+  tl_ctx* c = new tl_ctx;
+  c->cfg = *cfg;
+  c->device = -1;   // no device behind it: queries only
+  c->num_cus = num_compute_units;
   *out = c;
   return TL_OK;
 }
@@ -448,7 +467,7 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t*
 }
 
 int tl_check_status(tl_ctx* ctx, void* workspace) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   if (!workspace) return fail(TL_ERR_INVALID_ARG, "workspace is null");
   int st = 0;
   TL_HIP(hipMemcpy(&st, workspace, sizeof st, hipMemcpyDeviceToHost));
@@ -463,7 +482,7 @@ int tl_check_status(tl_ctx* ctx, void* workspace) {
 static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K, int act,
                         unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream,
                         void* const* peer_slots = nullptr) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!a_shards || !a_gathered || !b || !c || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: null pointer argument");
   if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: epoch starts at 1");
@@ -506,6 +525,7 @@ static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gather
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
   const bool alone = cfg.comm_alone != 0;  // communication side only (timing)
+  if (r.k_chunks > 1 && cfg.comm_mode != TL_COMM_WAVES && cfg.comm_mode != TL_COMM_SIDE_KERNEL) r.k_chunks = 1;
   if (alone && (cfg.comm_mode == TL_COMM_NONE || cfg.comm_mode == TL_COMM_EXTERNAL))
     return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm: comm_alone needs a comm_mode in which the library runs a producer");
   p.do_compute = alone ? 0 : 1;
@@ -530,16 +550,19 @@ static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gather
       TL_HIP(hipGetLastError());
       return alone ? TL_OK : launch_ag_gemm(r.variant, p, r.G, cs);
     }
-    case TL_COMM_STREAM: {
-      // rank_copy_data + rank_notify per source rank, ring order, through the runtime's copy path
+    case TL_COMM_STREAM:
+    case TL_COMM_COPY_ENGINE: {
+      // rank_copy_data + rank_notify per source rank, ring order: through the runtime's copy kernels, or through a copy
+      // engine, which takes no compute unit (the copy kind that asks the runtime to keep the compute units out of it)
       p.n_comm = 0; p.do_wait = 2;
       p.prod.wait_target = epoch;
+      const hipMemcpyKind kind = cfg.comm_mode == TL_COMM_COPY_ENGINE ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDeviceToDevice;
       const size_t shard_bytes = (size_t)r.rows_per_rank * K * sizeof(bf16_t);
       for (int i = 0; i < R; i++) {
         int q = (cfg.rank + i) % R;  // local shard first (it is usually free), then rank+1, ...
         char* dst = (char*)a_gathered + (size_t)q * shard_bytes;
-        if (!(q == cfg.rank && p.prod.local_in_place)) TL_HIP(hipMemcpyAsync(dst, a_shards[q], shard_bytes, hipMemcpyDeviceToDevice, ms));
-        hipLaunchKernelGGL(notify_kernel, dim3(1), dim3(64), 0, ms, flags + q * cfg.channels_per_rank, cfg.channels_per_rank, 1u);
+        if (!(q == cfg.rank && p.prod.local_in_place)) TL_HIP(hipMemcpyAsync(dst, a_shards[q], shard_bytes, kind, ms));
+        hipLaunchKernelGGL(notify_kernel, dim3((cfg.channels_per_rank + 63) / 64), dim3(64), 0, ms, flags + q * cfg.channels_per_rank, cfg.channels_per_rank, 1u);
         TL_HIP(hipGetLastError());
       }
       return alone ? TL_OK : launch_ag_gemm(r.variant, p, r.G, cs);
@@ -575,7 +598,7 @@ int tl_ag_gemm_push(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, 
 static int gemm_rs_impl(const char* name, bool ring, tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv,
                         void* const* peer_push, void* out, int M, int N, int K, unsigned* flags, unsigned epoch, void* workspace,
                         size_t ws_bytes, void* compute_stream, void* comm_stream) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!a || !b || !partial || !peer_recv || !peer_push || !out || !flags || !workspace) return fail(TL_ERR_INVALID_ARG, "%s: null pointer argument", name);
   if (epoch == 0) return fail(TL_ERR_INVALID_ARG, "%s: epoch starts at 1", name);
@@ -623,6 +646,8 @@ static int gemm_rs_impl(const char* name, bool ring, tl_ctx* ctx, const void* a,
       return launch_gemm_rs(r.variant, p, alone ? r.n_comm : r.G + r.n_comm, cs);
     case TL_COMM_EXTERNAL:
       return fail(TL_ERR_INVALID_ARG, "%s: TL_COMM_EXTERNAL is not defined for this operator", name);
+    case TL_COMM_COPY_ENGINE:
+      return fail(TL_ERR_INVALID_ARG, "%s: TL_COMM_COPY_ENGINE is an AllGather binding; the reduction needs compute units", name);
     case TL_COMM_STREAM:
     case TL_COMM_SIDE_KERNEL: {
       // The GEMM kernel is enqueued before the reduce kernel that waits on it: should both streams share a

@@ -59,6 +59,9 @@ struct TileCfg {
   static_assert((NS - 1) * LPW <= 63, "vmcnt is a 6-bit counter");
 };
 
+// Sixteen zero bytes: what a lane loads in place of a piece of A or B beyond the end of K.
+static __device__ __attribute__((aligned(16))) unsigned g_zero_chunk[4];
+
 __device__ __forceinline__ void lds_load16(const void* g, char* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
@@ -120,7 +123,10 @@ struct GatedRows {
 // `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
 // With Out::GATED the tile's columns come in pairs of 32 (gate, up): out.apply(gate, up) is stored, at half the column.
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
-// masked.  K % BK == 0.  All threads of the workgroup must call it; it ends with all LDS accesses complete.
+// masked.  K % 8 == 0 (rows of A start on 16-byte boundaries); a last K step shorter than BK is filled up with zeros:
+// the 16-byte pieces of it that lie beyond K are loaded from a block of zeros instead of from the matrices (every lane
+// of a direct-to-LDS load names its own global address), so both operands of the surplus products are zero.
+// All threads of the workgroup must call it; it ends with all LDS accesses complete.
 template <class Cfg, class Out, class KW = NoKWait>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
@@ -131,6 +137,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   // ---- per-lane global addresses of this wave's share of the stage loads
   const char* a_src[Cfg::A_PER_WAVE];
   const char* b_src[Cfg::B_PER_WAVE];
+  const int k_tail = K % Cfg::BK;  // k-values of the last K step if it is a short one, else 0
+  unsigned tail_ok = 0;            // bit L: this lane's load L of the short step lies inside K
 #pragma unroll
   for (int i = 0; i < Cfg::A_PER_WAVE; i++) {
     int j = wave + i * Cfg::NWAVES;  // wave-load index: LDS slots [64j, 64j+64)
@@ -141,6 +149,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     int grow = row < rows ? row : rows - 1;
     if (a_rows) grow = a_rows[grow] / a_div;
     a_src[i] = (const char*)(a + (long)grow * lda + chunk * 8);
+    if (chunk * 8 < k_tail) tail_ok |= 1u << i;
   }
 #pragma unroll
   for (int i = 0; i < Cfg::B_PER_WAVE; i++) {
@@ -151,26 +160,32 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     int nc = Cfg::B_SWZ ? (ncp ^ ((k & 3) << 2)) : ncp;
     int col = nc * 8 < cols ? nc * 8 : cols - 8;
     b_src[i] = (const char*)(b + (long)k * ldb + col);
+    if (k < k_tail) tail_ok |= 1u << (Cfg::A_PER_WAVE + i);
   }
   const long b_step = ldb * Cfg::BK * 2;  // bytes per K-step
 
   // Load number L (0..LPW-1) of this wave's share of the next stage in K order, into ring slot `slot`:
-  // loads 0..A_PER_WAVE-1 belong to the A tile, the rest to the B tile.  Advances that load's pointer.
-  auto issue_load = [&](int slot, auto l_c) {
+  // loads 0..A_PER_WAVE-1 belong to the A tile, the rest to the B tile.  Advances that load's pointer.  `tail` (uniform):
+  // the stage is the short last K step, lanes whose piece lies beyond K load zeros.
+  auto issue_load = [&](int slot, auto l_c, bool tail) {
     constexpr int L = decltype(l_c)::value;
     char* sa = smem + slot * Cfg::STAGE_BYTES;
     if constexpr (L < Cfg::A_PER_WAVE) {
       int j = wave + L * Cfg::NWAVES;
-      lds_load16(a_src[L], sa + (j < Cfg::A_LOADS ? j : Cfg::A_LOADS - 1) * 1024);
+      const char* src = a_src[L];
+      if (tail && !((tail_ok >> L) & 1u)) src = (const char*)g_zero_chunk;
+      lds_load16(src, sa + (j < Cfg::A_LOADS ? j : Cfg::A_LOADS - 1) * 1024);
       a_src[L] += Cfg::BK * 2;
     } else {
       constexpr int LB = L - Cfg::A_PER_WAVE;
       int j = wave + LB * Cfg::NWAVES;
-      lds_load16(b_src[LB], sa + Cfg::A_BYTES + (j < Cfg::B_LOADS ? j : Cfg::B_LOADS - 1) * 1024);
+      const char* src = b_src[LB];
+      if (tail && !((tail_ok >> L) & 1u)) src = (const char*)g_zero_chunk;
+      lds_load16(src, sa + Cfg::A_BYTES + (j < Cfg::B_LOADS ? j : Cfg::B_LOADS - 1) * 1024);
       b_src[LB] += b_step;
     }
   };
-  auto issue_stage = [&](int slot) { static_for<0, LPW>([&](auto l_c) { issue_load(slot, l_c); }); };
+  auto issue_stage = [&](int slot, bool tail) { static_for<0, LPW>([&](auto l_c) { issue_load(slot, l_c, tail); }); };
 
   // ---- per-lane LDS read offsets
   // A fragment (MFMA B operand): lane holds row (lane%32) of the wave's m-tile, k = 8*(lane/32)..+7 of the 16-wide k-slice.
@@ -224,7 +239,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   // (which spans SL slices): the LPW global loads of a newly requested stage are spread evenly over
   // the body's MFMAs, one at a time, so that no wave sits in a full memory-instruction queue while
   // its MFMAs wait behind it.
-  auto slice = [&](auto cur_c, auto bs_c, auto reads_c, const char* rst, int rsl, bool issue, int islot) {
+  auto slice = [&](auto cur_c, auto bs_c, auto reads_c, const char* rst, int rsl, bool issue, int islot, bool itail) {
     constexpr int CUR = decltype(cur_c)::value, BS = decltype(bs_c)::value;
     constexpr bool READS = decltype(reads_c)::value;
     constexpr int GAPS = N_MFMA > 2 ? N_MFMA - 2 : 1;
@@ -239,7 +254,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
         static_for<0, LPW>([&](auto l_c) {
           constexpr int L = decltype(l_c)::value;
           if constexpr (G == ((2 * L + 1) * SL * N_MFMA) / (2 * LPW)) {
-            if (issue) issue_load(islot, l_c);
+            if (issue) issue_load(islot, l_c, itail);
             __builtin_amdgcn_sched_barrier(0);
           }
         });
@@ -264,15 +279,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   //   body slice j>0 : multiply slice j-1 of stage s+1, read (stage s+1, slice j)
   //   throughout     : request stage s+NS into the slot stage s just left, one load at a time
   // The last NS bodies request nothing and wait for all outstanding loads instead.
-  const int nk = K / Cfg::BK;
+  const int nk = (K + Cfg::BK - 1) / Cfg::BK;
   const int n_pre = nk < NS ? nk : NS;
-  for (int s = 0; s < n_pre; s++) issue_stage(s);
+  for (int s = 0; s < n_pre; s++) issue_stage(s, k_tail != 0 && s == nk - 1);
   if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
   __syncthreads();
   static_for<0, N_READS>([&](auto r_c) { read_frag(smem, 0, integral_constant<int, 0>{}, r_c); });
   static_for<0, SL - 1>([&](auto sl_c) {
     constexpr int S = decltype(sl_c)::value;
-    slice(integral_constant<int, S & 1>{}, integral_constant<int, -1>{}, yes{}, smem, S + 1, false, 0);
+    slice(integral_constant<int, S & 1>{}, integral_constant<int, -1>{}, yes{}, smem, S + 1, false, 0, false);
   });
 
   int slot = 0;  // s % NS
@@ -280,20 +295,21 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     const int nslot = slot + 1 == NS ? 0 : slot + 1;
     const char* nst = smem + nslot * Cfg::STAGE_BYTES;
     const bool more = s + NS < nk;  // a further stage remains to be requested
+    const bool itail = k_tail != 0 && s + NS == nk - 1;  // ... and it is the short one
     const bool new_chunk = KW::ENABLED && more && kw.starts(s + NS);
     if (new_chunk) kw.wait(s + NS);
     // stage s+1 must have landed; while requests continue, the NS-2 younger stages may stay in flight
     if (more) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
     __syncthreads();
     if (new_chunk) kw.acquire();
-    slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nst, 0, more, slot);
+    slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nst, 0, more, slot, itail);
     static_for<0, SL - 1>([&](auto sl_c) {
       constexpr int S = decltype(sl_c)::value;
-      slice(integral_constant<int, S & 1>{}, integral_constant<int, S + 1>{}, yes{}, nst, S + 1, more, slot);
+      slice(integral_constant<int, S & 1>{}, integral_constant<int, S + 1>{}, yes{}, nst, S + 1, more, slot, itail);
     });
     slot = nslot;
   }
-  slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, smem, 0, false, 0);
+  slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, smem, 0, false, 0, false);
   __syncthreads();  // all operand reads of this tile are complete: LDS is free for the epilogue
 
   // ---- epilogue.  Accumulator register e of lane l holds C[row = l%32][col = (e/4)*8 + (l/32)*4 + e%4] of its 32x32

@@ -152,6 +152,13 @@ inline int check_ctx(const tl_ctx* ctx) {
   return TL_OK;
 }
 
+// For the calls that enqueue GPU work: a context made by tl_ctx_create_host serves the host-side queries only.
+inline int check_op_ctx(const tl_ctx* ctx) {
+  if (!ctx) return fail(TL_ERR_INVALID_ARG, "context is null");
+  if (ctx->device < 0) return fail(TL_ERR_INVALID_ARG, "this context was made by tl_ctx_create_host: it answers queries but cannot launch work");
+  return TL_OK;
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace tl

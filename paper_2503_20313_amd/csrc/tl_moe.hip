@@ -579,7 +579,7 @@ int tl_moe_query(const tl_ctx* ctx, int op, int T, int H, int I, int E, int topk
 
 int tl_moe_route(tl_ctx* ctx, const float* gate_logits, int T, int E, int topk, int renormalize, int tile_m, int* topk_ids, float* topk_w,
                  int* expert_offsets, int* sorted_row, int* tile_tables, int* n_tiles, void* stream) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   if (!gate_logits || !topk_ids || !topk_w || !expert_offsets || !sorted_row || !tile_tables || !n_tiles) return fail(TL_ERR_INVALID_ARG, "tl_moe_route: null pointer argument");
   const tl_config& c = ctx->cfg;
   if (T <= 0 || E <= 0 || topk <= 0 || tile_m <= 0) return fail(TL_ERR_INVALID_ARG, "tl_moe_route: T, E, topk, tile_m must be positive");
@@ -598,7 +598,7 @@ int tl_moe_route(tl_ctx* ctx, const float* gate_logits, int T, int E, int topk, 
 static int moe_p1_impl(tl_ctx* ctx, const void* const* x_shards, void* x_gathered, const void* w1, const int* sorted_row,
                        const int* tile_tables, const int* n_tiles, void* y1, int T, int H, int I, int E, int topk, int act, unsigned* flags,
                        unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!x_shards || !x_gathered || !w1 || !sorted_row || !tile_tables || !n_tiles || !y1 || !flags || !workspace)
     return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: null pointer argument");
@@ -609,7 +609,7 @@ static int moe_p1_impl(tl_ctx* ctx, const void* const* x_shards, void* x_gathere
   for (int q = 0; q < cfg.world_size; q++)
     if (!x_shards[q] || !aligned16(x_shards[q])) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: x_shards[%d] is null or misaligned", q);
   if (!aligned16(x_gathered) || !aligned16(w1) || !aligned16(y1)) return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: device pointers must be 16-byte aligned");
-  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL || cfg.comm_mode == TL_COMM_COPY_ENGINE)
     return fail(TL_ERR_INVALID_ARG, "tl_moe_ag_gather_gemm: comm_mode must be NONE, WAVES or SIDE_KERNEL");
 
   MoeP1Params p;
@@ -675,7 +675,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
                            const float* topk_w, void* scatter_buf, void* partial, const void* const* peer_recv, void* const* peer_push,
                            void* out, int T, int H, int I, int E, int topk, unsigned* flags, unsigned epoch, void* workspace,
                            size_t ws_bytes, void* compute_stream, void* comm_stream) {
-  if (int e = check_ctx(ctx)) return e;
+  if (int e = check_op_ctx(ctx)) return e;
   const tl_config& cfg = ctx->cfg;
   if (!x2 || !w2 || !sorted_row || !tile_tables || !n_tiles || !topk_w || !scatter_buf || !partial || !peer_recv || !peer_push || !out || !flags || !workspace)
     return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: null pointer argument");
@@ -689,7 +689,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
   for (int q = 0; q < R; q++)
     if (q != cfg.rank && (!peer_recv[q] || !peer_push[q] || !aligned16(peer_recv[q]) || !aligned16(peer_push[q])))
       return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: peer_recv[%d] or peer_push[%d] is null or misaligned", q, q);
-  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL || cfg.comm_mode == TL_COMM_COPY_ENGINE)
     return fail(TL_ERR_INVALID_ARG, "tl_moe_gemm_scatter_rs: comm_mode must be NONE, WAVES or SIDE_KERNEL");
 
   MoeP2Params p;

@@ -11,7 +11,7 @@ from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
 
 pytestmark = pytest.mark.gpu
 
-MODES = {"waves": tl.TL_COMM_WAVES, "stream": tl.TL_COMM_STREAM, "side": tl.TL_COMM_SIDE_KERNEL}
+MODES = {"waves": tl.TL_COMM_WAVES, "stream": tl.TL_COMM_STREAM, "side": tl.TL_COMM_SIDE_KERNEL, "copy_engine": tl.TL_COMM_COPY_ENGINE}
 
 
 def run_ag_gemm(w, rank, C, mode, epochs=1, in_place=False, **cfg):
@@ -61,7 +61,7 @@ def test_small_config_all_modes(mode, rank, C):
     w = wl.ag_gemm_inputs(256, 512, 512, 2, config_id=1, a_dist="uniform")
     hs, g, c, flags, info = run_ag_gemm(w, rank, C, MODES[mode], epochs=3, comm_workgroups=2)
     check(w, hs, g, c, f"cfg1 {mode} rank={rank} C={C}")
-    expected = info["expected_per_channel"] if mode != "stream" else 1
+    expected = info["expected_per_channel"] if mode not in ("stream", "copy_engine") else 1
     assert flags.tolist() == [3 * expected] * (2 * C)
 
 
@@ -208,7 +208,7 @@ def test_paced_links_take_the_time_of_the_link():
 
 def test_invalid_arguments_are_rejected_before_launch():
     ctx = make_ctx(world_size=4, rank=1, channels_per_rank=3)
-    for dims in ([1023, 512, 512], [1024, 512, 100], [1024, 513, 512], [1024, 512, 512]):   # R∤M, K%64, N%8, C∤M/R
+    for dims in ([1023, 512, 512], [1024, 512, 100], [1024, 513, 512], [1024, 512, 512]):   # R∤M, K%8, N%8, C∤M/R
         with pytest.raises(tl.TileLinkError) as e:
             tl.tl_query_workspace(ctx, tl.TL_OP_AG_GEMM, dims)
         assert e.value.status == tl.TL_ERR_UNSUPPORTED_SHAPE
@@ -240,28 +240,42 @@ def test_k_chunks_fall_back_and_reject():
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("mode", ["waves", "side", "stream"])
+@pytest.mark.parametrize("mode", ["waves", "side", "stream", "copy_engine"])
 def test_full_size_tp8_share(mode):
-    """BASELINE configuration 2: 8 shards of [1024,8192], B [8192,3584]; whole output compared.  `side` is the
-    launch configuration bench.py times.  In `stream` mode the copies are kernels of the runtime that must become
-    resident beside the persistent GEMM grid, so that case leaves a quarter of the compute units to them."""
+    """BASELINE configuration 2: 8 shards of [1024,8192], B [8192,3584]; whole output compared, every binding with the
+    grid the library picks by itself.  In `stream` mode the copies are kernels of the runtime that must become resident
+    beside the persistent GEMM grid, so the library leaves compute units free for them; in `copy_engine` mode a DMA
+    engine moves the shards and the GEMM grid keeps every compute unit."""
     w = wl.ag_gemm_inputs(8192, 3584, 8192, 8, config_id=2)
     a_ref, _, c_ref = ops.ag_gemm(w["a_shards"], w["b"])
-    extra = dict(compute_workgroups=192, tile_m=256, tile_n=256) if mode == "stream" else {}
-    hs, g, c, flags, info = run_ag_gemm(w, 0, 4, MODES[mode], epochs=2 if mode != "stream" else 1, **extra)
-    if mode != "stream":
-        a_ref, _, c_ref = ops.ag_gemm(hs, w["b"])
-    assert np.array_equal(g, a_ref)
-    rel, mx = assert_close_bf16(c, c_ref, f"cfg2 {mode}")
-    print(f"cfg2 {mode}: tile {info['tile_m']}x{info['tile_n']} rel_fro={rel:.2e} max={mx:.2e}")
-
-
-def test_full_size_tp8_share_k_chunks():
-    """The launch configuration bench.py times: side-kernel producers, local shard in place, four chunks along K."""
-    w = wl.ag_gemm_inputs(8192, 3584, 8192, 8, config_id=2)
-    hs, g, c, flags, info = run_ag_gemm(w, 5, 4, tl.TL_COMM_SIDE_KERNEL, epochs=2, in_place=True, tile_order=tl.TL_ORDER_OWN_FIRST, ag_k_chunks=4)
-    assert info["k_chunks"] == 4
+    hs, g, c, flags, info = run_ag_gemm(w, 0, 4, MODES[mode], epochs=2)
     a_ref, _, c_ref = ops.ag_gemm(hs, w["b"])
     assert np.array_equal(g, a_ref)
-    assert_close_bf16(c, c_ref, "cfg2 side, 4 K chunks")
-    assert flags.tolist() == [2 * info["expected_per_channel"]] * (8 * 4 * 4)
+    rel, mx = assert_close_bf16(c, c_ref, f"cfg2 {mode}")
+    if mode == "copy_engine":
+        assert info["compute_workgroups"] == torch.cuda.get_device_properties(0).multi_processor_count
+    if mode in ("stream", "copy_engine"):
+        assert flags.tolist() == [2] * 32
+    print(f"cfg2 {mode}: tile {info['tile_m']}x{info['tile_n']} grid {info['compute_workgroups']} rel_fro={rel:.2e} max={mx:.2e}")
+
+
+@pytest.mark.parametrize("kc,rank", [(1, 0), (4, 5)])
+def test_full_size_tp8_share_bench_configuration(kc, rank):
+    """The launch configuration bench.py times -- side-kernel producers, local shard in place, own-first tile order, four
+    channels per rank, one flag per channel, rank 0 -- and the same with four chunks along K (bench.py --ag-k-chunks 4)."""
+    w = wl.ag_gemm_inputs(8192, 3584, 8192, 8, config_id=2)
+    hs, g, c, flags, info = run_ag_gemm(w, rank, 4, tl.TL_COMM_SIDE_KERNEL, epochs=2, in_place=True, tile_order=tl.TL_ORDER_OWN_FIRST, ag_k_chunks=kc)
+    assert info["k_chunks"] == kc and (info["tile_m"], info["tile_n"]) == (256, 256)
+    a_ref, _, c_ref = ops.ag_gemm(hs, w["b"])
+    assert np.array_equal(g, a_ref)
+    assert_close_bf16(c, c_ref, f"cfg2 side, in place, own first, {kc} K chunk(s), rank {rank}")
+    assert flags.tolist() == [2 * info["expected_per_channel"]] * (8 * 4 * kc)
+
+
+@pytest.mark.parametrize("rank,C,in_place", [(1, 2, False), (0, 1, True)])
+def test_copy_engine_small(rank, C, in_place):
+    """rank_copy_data on a copy engine + rank_notify behind every shard: three calls with fresh data."""
+    w = wl.ag_gemm_inputs(1120, 456, 320, 4, config_id=19)
+    hs, g, c, flags, info = run_ag_gemm(w, rank, C, tl.TL_COMM_COPY_ENGINE, epochs=3, in_place=in_place)
+    check(w, hs, g, c, f"copy engine rank {rank} C {C}")
+    assert flags.tolist() == [3] * (4 * C)

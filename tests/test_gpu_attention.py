@@ -173,16 +173,24 @@ def test_invalid_arguments():
 
 @pytest.mark.parametrize("rank,mode", [(7, "side"), (3, "waves"), (0, "side")])
 def test_full_size_sampled(rank, mode):
-    """Config 5 (S=32768, 32 heads, head_dim 128, TP=8, causal) in the launch configuration the bench uses; the oracle
-    computes sampled (head, row) outputs: the first and last rows, rows around query-block and shard boundaries."""
+    """Config 5 (S=32768, 32 heads, head_dim 128, TP=8, causal) in the launch configuration the bench uses.  The oracle
+    computes EVERY head on rows of EVERY one of the 16 query blocks (a workgroup owns one head and 256 queries, a wave 32
+    of them): each block's first and last rows, the rows either side of its wave boundaries at 32, 128 and 224, and one
+    row inside -- 160 rows x 32 heads, so an indexing slip per head, per query block or per wave would meet the oracle."""
     c = wl.CONFIGS[5]
     w = wl.sp_attention_inputs(c["S"], c["heads"], c["head_dim"], c["world"])
     res = run_attention(w, rank, True, MODES[mode])
     S_loc = c["S"] // c["world"]
-    rows = np.array([0, 1, 31, 32, 63, 64, 255, 256, 257, 1000, 2047, 2048, 3071, S_loc - 257, S_loc - 2, S_loc - 1])
-    heads = [0, 5, 13, 31]
+    in_block = [0, 1, 31, 32, 77, 127, 128, 223, 224, 255]
+    rows = np.array([256 * b + i for b in range(S_loc // 256) for i in in_block])
+    heads = list(range(c["heads"]))
     _, _, _, o_ref = ops.sp_ag_attention(w["q_shards"][rank], w["k_shards"], w["v_shards"], rank, True, heads=heads, rows=rows)
     got = res["o"][rows][:, heads]
     assert_close_bf16(got, o_ref, f"attention full size rank {rank} {mode}")
+    for h in heads:                                   # no head may hide behind the others' norm
+        assert_close_bf16(got[:, h], o_ref[:, h], f"attention full size rank {rank} {mode} head {h}")
+    for b in range(S_loc // 256):                     # ... and no query block
+        sl = slice(b * len(in_block), (b + 1) * len(in_block))
+        assert_close_bf16(got[sl], o_ref[sl], f"attention full size rank {rank} {mode} query block {b}")
     check_gathered(w, res, rank, True, 1)
     assert not (res["o"] == POISON).any()

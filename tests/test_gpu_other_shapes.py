@@ -16,7 +16,8 @@ from tests.test_gpu_moe import run_part1, run_part2
 pytestmark = pytest.mark.gpu
 R = 8
 # name -> (S, H, I) of the paper's MLP table
-MLP = {"MLP-1": (8192, 4096, 11008), "MLP-3": (8192, 3584, 14336), "MLP-4": (8192, 4608, 36864), "MLP-6": (8192, 8192, 29568)}
+MLP = {"MLP-1": (8192, 4096, 11008), "MLP-2": (8192, 4096, 14336), "MLP-3": (8192, 3584, 14336), "MLP-4": (8192, 4608, 36864),
+       "MLP-6": (8192, 8192, 29568)}
 
 
 def sample_columns(N, n, seed):
@@ -26,7 +27,7 @@ def sample_columns(N, n, seed):
     return np.array(sorted(cols))
 
 
-@pytest.mark.parametrize("name,rank", [("MLP-1", 3), ("MLP-4", 0), ("MLP-6", 7)])
+@pytest.mark.parametrize("name,rank", [("MLP-1", 3), ("MLP-2", 6), ("MLP-4", 0), ("MLP-6", 7)])
 def test_ag_gemm_mlp_shares(name, rank):
     S, H, I = MLP[name]
     N = I // R                                       # 1376, 4608, 3696: the last two column tiles are ragged for 1376 and 3696
@@ -39,11 +40,10 @@ def test_ag_gemm_mlp_shares(name, rank):
     assert flags.tolist() == [info["expected_per_channel"]] * (R * 4)
 
 
-@pytest.mark.parametrize("name,rank,direct", [("MLP-1", 5, 1), ("MLP-3", 0, 0), ("MLP-6", 2, 1)])
+@pytest.mark.parametrize("name,rank,direct", [("MLP-1", 5, 1), ("MLP-2", 4, 1), ("MLP-3", 0, 0), ("MLP-6", 2, 1)])
 def test_gemm_rs_mlp_shares(name, rank, direct):
     S, H, I = MLP[name]
-    K = I // R
-    K -= K % 64                                      # the K step of the tile kernels; 1376 -> 1344, 3696 -> 3648
+    K = I // R                                       # 1376 = 43 K steps of 32; 3696 = 115 steps and a zero-filled half step
     w = wl.gemm_rs_inputs(S, H, K, R, rank, config_id=70 + rank)
     ha, partial, push, out, flags, info = run_gemm_rs(w, tl.TL_COMM_SIDE_KERNEL, tile_order=tl.TL_ORDER_OWN_FIRST, rs_direct_push=direct)
     cols = sample_columns(H, 384, 700 + rank)
@@ -72,13 +72,14 @@ def test_moe_8_experts_share():
     run_part2(w, tl.TL_COMM_SIDE_KERNEL, tile_order=tl.TL_ORDER_OWN_FIRST, rs_direct_push=1)
 
 
-@pytest.mark.parametrize("S,heads,rank,causal", [(16384, 64, 5, True), (8192, 32, 2, False)])
+@pytest.mark.parametrize("S,heads,rank,causal", [(16384, 64, 5, True), (8192, 32, 2, False), (65536, 32, 7, True), (131072, 32, 6, True)])
 def test_attention_other_configs(S, heads, rank, causal):
-    """Attn-2 (64 heads) at 16k causal, and non-causal attention at 8k; sampled heads and rows."""
+    """Attn-2 (64 heads) at 16k causal, non-causal attention at 8k, and Attn-1 at 64k and 128k (the long rows of the
+    paper's table: 32 and 64 query blocks per head, shards of 8192 and 16384 keys); sampled heads and rows."""
     w = wl.sp_attention_inputs(S, heads, 128, R, config_id=90 + rank)
     res = run_attention(w, rank, causal, tl.TL_COMM_SIDE_KERNEL)
     S_loc = S // R
-    rows = np.array([0, 1, 31, 32, 255, 256, 257, S_loc // 2, S_loc - 2, S_loc - 1])
+    rows = np.array(sorted({0, 1, 31, 32, 255, 256, 257, S_loc // 2 - 1, S_loc // 2, S_loc - 257, S_loc - 256, S_loc - 2, S_loc - 1}))
     hsel = [0, 7, heads // 2 + 1, heads - 1]
     _, _, _, o_ref = ops.sp_ag_attention(w["q_shards"][rank], w["k_shards"], w["v_shards"], rank, causal, heads=hsel, rows=rows)
     assert_close_bf16(res["o"][rows][:, hsel], o_ref, f"attention S={S} heads={heads} rank {rank} causal={causal}")
