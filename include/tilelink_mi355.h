@@ -136,7 +136,8 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims /*host*/
                        size_t* n_flags /*host*/);
 
 /* Synchronous: copies the status word out of `workspace` (after the caller synchronised the
- * streams) and returns TL_OK or TL_ERR_TIMEOUT; clears the word. */
+ * streams) and returns TL_OK or TL_ERR_TIMEOUT; clears the word.  workspace = NULL: the static scratch of
+ * tl_ag_gemm_static on the context's device. */
 int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
 
 /*
@@ -164,6 +165,23 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
 int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards /*host array of dev*/, void* a_gathered, const void* b,
                void* c, int M, int N, int K, unsigned* flags /*dev*/, unsigned epoch, void* workspace /*dev*/,
                size_t ws_bytes, void* compute_stream, void* comm_stream);
+
+/*
+ * tl_ag_gemm for callers that cannot allocate device memory or ask anybody to: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and bindings as tl_ag_gemm, but the
+ * workspace and the channel flags live in a static device array inside the library (16.25 KiB per device, held until
+ * the process ends) instead of in caller memory; this call allocates nothing.  The caller still passes inputs and outputs.
+ *   - The context must have been created (tl_ctx_create sets the array up) on the device that is current at the call.
+ *   - At most 4096 channel flags (R*C*k_chunks); more returns TL_ERR_WORKSPACE_TOO_SMALL before anything is enqueued.
+ *   - Every call first clears the workspace and its flags on compute_stream (a fill kernel) and makes comm_stream wait
+ *     for that, then runs as call number 1: no epoch to keep.  All calls on one device share the one array, so calls
+ *     that overlap on a device race (also with tl_check_status); serialise them, e.g. on one pair of streams.
+ *   - tl_check_status(ctx, NULL) reads and clears this array's status word (after the streams were synchronised).
+ * Everything else -- arguments, requirements, streams, errors -- as tl_ag_gemm.
+ */
+int tl_ag_gemm_static(tl_ctx* ctx, const void* const* a_shards /*host array of R device ptrs*/, void* a_gathered /*device*/,
+                      const void* b /*device*/, void* c /*device*/, int M, int N, int K, void* compute_stream /*hipStream_t*/,
+                      void* comm_stream /*hipStream_t*/);
 
 /* The first half of the MLP layer with its activation folded into the GEMM's epilogue (paper, evaluation, "MLP
  * Layer": AllGather + GEMM, then an activation layer such as SiLUMul or GeLUMul, then GEMM + ReduceScatter):

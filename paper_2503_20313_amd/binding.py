@@ -57,6 +57,7 @@ _lib.tl_check_status.argtypes = [_vp, _vp]
 _lib.tl_resolve.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i)]
 _lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i), _sz, ctypes.POINTER(_sz)]
 _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
+_lib.tl_ag_gemm_static.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 _lib.tl_ag_gemm_act_mul.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_rs.argtypes = [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
 _lib.tl_gemm_ring_rs.argtypes = _lib.tl_gemm_rs.argtypes
@@ -166,6 +167,10 @@ def tl_dump_schedule(ctx, op, dims):
 def tl_ag_gemm(ctx, a_shards, a_gathered, b, c, M, N, K, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):
     _check(_lib.tl_ag_gemm(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr(b), _ptr(c), M, N, K, _ptr(flags), epoch,
                            _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)))
+
+
+def tl_ag_gemm_static(ctx, a_shards, a_gathered, b, c, M, N, K, compute_stream=None, comm_stream=None):
+    _check(_lib.tl_ag_gemm_static(ctx, _ptr_array(a_shards), _ptr(a_gathered), _ptr(b), _ptr(c), M, N, K, _stream(compute_stream), _stream(comm_stream)))
 
 
 def tl_ag_gemm_act_mul(ctx, a_shards, a_gathered, b_gate_up, y, M, F, K, act, flags, epoch, workspace, ws_bytes, compute_stream=None, comm_stream=None):

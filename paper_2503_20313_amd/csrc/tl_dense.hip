@@ -5,6 +5,8 @@
 #include "tl_host.h"
 #include "tl_rs_consumer.h"
 
+#include <mutex>
+
 namespace tl {
 
 // ======================================================================================
@@ -184,6 +186,39 @@ __global__ void __launch_bounds__(256) rs_consumer_kernel(const RsSide p) {
 // Host side
 // ======================================================================================
 static thread_local char g_err[512] = "";
+
+// Scratch memory of tl_ag_gemm_static, the entry point for callers that cannot allocate: the 256-byte workspace (status
+// word, ticket queue, pacing word) followed by the channel flags.  Every device the library runs on holds its own copy
+// of this array until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// address kernels and copies are given is the per-device pointer kept in g_static below.
+constexpr size_t kStaticWorkspaceBytes = 256;
+constexpr size_t kStaticFlagWords = 4096;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes + kStaticFlagWords * sizeof(unsigned)];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  void* ptr;          // device address of `scratch` on this device
+  hipEvent_t cleared; // orders the communication stream behind the clearing of the scratch on the compute stream
+};
+static StaticScratch g_static[kMaxDevices];
+
+__global__ void clear_words_kernel(unsigned* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// Once per device, from tl_ctx_create, with that device current.
+static int setup_static_scratch(int dev) {
+  if (dev < 0 || dev >= kMaxDevices) return TL_OK;   // such a device simply has no static entry point
+  if (g_static[dev].ptr) return TL_OK;
+  void* ptr = nullptr;
+  TL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+  hipEvent_t ev;
+  TL_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+  g_static[dev].cleared = ev;
+  g_static[dev].ptr = ptr;
+  return TL_OK;
+}
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -397,6 +432,11 @@ int tl_ctx_create(const tl_config* cfg, tl_ctx** out) {
   hipDeviceProp_t prop;
   TL_HIP(hipGetDeviceProperties(&prop, dev));
   if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(TL_ERR_HIP, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+  {
+    static std::mutex m;   // contexts may be created from several threads
+    std::lock_guard<std::mutex> lock(m);
+    if (int e = setup_static_scratch(dev)) return e;
+  }
   tl_ctx* c = new tl_ctx;
   c->cfg = *cfg;
   c->device = dev;
@@ -468,6 +508,7 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t*
 
 int tl_check_status(tl_ctx* ctx, void* workspace) {
   if (int e = check_op_ctx(ctx)) return e;
+  if (!workspace && ctx->device < kMaxDevices) workspace = g_static[ctx->device].ptr;   // the scratch of tl_ag_gemm_static
   if (!workspace) return fail(TL_ERR_INVALID_ARG, "workspace is null");
   int st = 0;
   TL_HIP(hipMemcpy(&st, workspace, sizeof st, hipMemcpyDeviceToHost));
@@ -574,6 +615,33 @@ static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gather
 int tl_ag_gemm(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K,
                unsigned* flags, unsigned epoch, void* workspace, size_t ws_bytes, void* compute_stream, void* comm_stream) {
   return ag_gemm_impl(ctx, a_shards, a_gathered, b, c, M, N, K, 0, flags, epoch, workspace, ws_bytes, compute_stream, comm_stream);
+}
+
+int tl_ag_gemm_static(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b, void* c, int M, int N, int K,
+                      void* compute_stream, void* comm_stream) {
+  if (int e = check_op_ctx(ctx)) return e;
+  int cur = -1;
+  TL_HIP(hipGetDevice(&cur));
+  if (cur != ctx->device) return fail(TL_ERR_INVALID_ARG, "tl_ag_gemm_static: the context belongs to device %d, the current device is %d", ctx->device, cur);
+  if (cur >= kMaxDevices || !g_static[cur].ptr) return fail(TL_ERR_HIP, "tl_ag_gemm_static: no static scratch was set up for device %d", cur);
+  Resolved r;
+  if (int e = resolve_dense(ctx, TL_OP_AG_GEMM, M, N, K, &r)) return e;
+  const size_t n_flags = (size_t)ctx->cfg.world_size * ctx->cfg.channels_per_rank * (r.k_chunks > 0 ? r.k_chunks : 1);
+  if (n_flags > kStaticFlagWords)
+    return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_ag_gemm_static: %zu channel flags needed, the static scratch holds %zu; use tl_ag_gemm with a caller's workspace", n_flags, kStaticFlagWords);
+  unsigned* ws = (unsigned*)g_static[cur].ptr;
+  unsigned* flags = ws + kStaticWorkspaceBytes / sizeof(unsigned);
+  hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
+  // The scratch keeps the last call's counters: start from zero (a fill kernel, which a captured graph replays
+  // faithfully), and let the communication stream's producers start behind it.
+  const int n_clear = (int)(kStaticWorkspaceBytes / sizeof(unsigned) + n_flags);
+  hipLaunchKernelGGL(clear_words_kernel, dim3((n_clear + 255) / 256), dim3(256), 0, cs, ws, n_clear);
+  TL_HIP(hipGetLastError());
+  if (ms != cs) {
+    TL_HIP(hipEventRecord(g_static[cur].cleared, cs));
+    TL_HIP(hipStreamWaitEvent(ms, g_static[cur].cleared, 0));
+  }
+  return ag_gemm_impl(ctx, a_shards, a_gathered, b, c, M, N, K, 0, flags, 1u, ws, kStaticWorkspaceBytes, compute_stream, comm_stream);
 }
 
 int tl_ag_gemm_act_mul(tl_ctx* ctx, const void* const* a_shards, void* a_gathered, const void* b_gate_up, void* y, int M, int F, int K, int act,
