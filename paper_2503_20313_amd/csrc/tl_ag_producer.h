@@ -45,13 +45,6 @@ struct AgProducer {
 // workgroups drain the queue, and a GEMM workgroup whose channel is not ready yet takes tickets
 // too instead of idling, so a consumer can never wait for a producer that is not resident.
 // ======================================================================================
-// A 64-bit value every lane holds alike, as a wave-uniform value for the compiler too.
-__device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
-  // the builtin returns int: through unsigned first, or a low word with its top bit set would sign-extend over the high word
-  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)v), hi = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-  return (unsigned long long)lo | ((unsigned long long)hi << 32);
-}
-
 // Start time of the call in flight on the 100 MHz clock (low 40 bits), agreed on by all producers: the first one to
 // find another call's tag in the word replaces it with this call's tag and its own clock reading.  One lane of wave 0
 // of a workgroup tries the compare-and-swap (whichever workgroup's lands first wins); everybody then reads the word

@@ -177,6 +177,13 @@ __device__ __forceinline__ void wave_tile_notify(unsigned* flag, unsigned inc = 
   lane0_add(flag, inc);
 }
 
+// A 64-bit value every lane holds alike, as a wave-uniform value for the compiler too.
+__device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
+  // the builtin returns int: through unsigned first, or a low word with its top bit set would sign-extend over the high word
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)v), hi = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (unsigned long long)lo | ((unsigned long long)hi << 32);
+}
+
 // ---------------------------------------------------------------------------------------
 // Tile order.  Position p of the schedule is computed by persistent workgroup p % G in its
 // round p / G.  Inside a full round the workgroups of one die get a contiguous run of G/8

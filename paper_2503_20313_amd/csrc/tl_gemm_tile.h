@@ -67,6 +67,18 @@ __device__ __forceinline__ void lds_load16(const void* g, char* lds_wave_base) {
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// The same load with the global address given as a scalar base (the same for every lane) plus a 32-bit lane offset:
+// advancing the address from one K step to the next is then scalar arithmetic.  The compiler's builtin always takes the
+// per-lane 64-bit form, hence the instruction is written out; M0 carries the wave's LDS destination (lane l lands at
+// M0 + 16 l).  One wait state between the write of M0 and its use by the load.
+__device__ __forceinline__ void lds_load16_sbase(const char* base, unsigned lane_off, unsigned lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_wave_base), "v"(lane_off), "s"(base) : "memory");
+}
+// ... and with a per-lane 64-bit address, the LDS destination given as a 32-bit LDS address.
+__device__ __forceinline__ void lds_load16_at(const char* g, unsigned lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(g) : "memory");
+}
+
 __device__ __forceinline__ short4_t lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
 }
@@ -117,8 +129,9 @@ struct GatedRows {
 };
 
 // Computes one output tile.  `a` points at column 0 of the A rows: tile row r is A row r, or A row
-// a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index); `b` points at
-// row 0 of B at the tile's first column; `out.row(r, scale)` gives the address of the tile's first
+// a_rows[r] / a_div when a_rows is given (row gather: the tile's rows are picked by index; the picked rows must lie
+// within 4 GiB of `a`); `b` points at row 0 of B at the tile's first column; both are the same for every lane.
+// `out.row(r, scale)` gives the address of the tile's first
 // column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED);
 // `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
 // With Out::GATED the tile's columns come in pairs of 32 (gate, up): out.apply(gate, up) is stored, at half the column.
@@ -127,16 +140,24 @@ struct GatedRows {
 // the 16-byte pieces of it that lie beyond K are loaded from a block of zeros instead of from the matrices (every lane
 // of a direct-to-LDS load names its own global address), so both operands of the surplus products are zero.
 // All threads of the workgroup must call it; it ends with all LDS accesses complete.
+//
+// LDS: the NS stages of the A tile, then the NS stages of the B tile.  The K loop is unrolled NS times so that the ring
+// slot of every stage is a compile-time constant: all fragment reads then address LDS as (a lane register fixed for the
+// whole tile) + (an immediate), and the direct-to-LDS loads as (a scalar base that advances per K step) + (a lane
+// offset fixed for the whole tile).  The loop body is left with no vector-ALU instruction besides the matrix ones:
+// measured on this chip, a plain vector instruction does not overlap a matrix instruction of the same SIMD, it delays it.
 template <class Cfg, class Out, class KW = NoKWait>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
                                           char* smem, const KW& kw = KW{}) {
   constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int A_REGION = NS * Cfg::A_BYTES;   // the B stages start here
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform for the compiler too
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
-  // ---- per-lane global addresses of this wave's share of the stage loads
-  const char* a_src[Cfg::A_PER_WAVE];
-  const char* b_src[Cfg::B_PER_WAVE];
+  // ---- this wave's share of the stage loads: a scalar base per matrix and a lane offset per load
+  unsigned a_voff[Cfg::A_PER_WAVE], b_voff[Cfg::B_PER_WAVE];
+  K = __builtin_amdgcn_readfirstlane(K);   // the trip counts of the K loops must be uniform for the compiler too
   const int k_tail = K % Cfg::BK;  // k-values of the last K step if it is a short one, else 0
   unsigned tail_ok = 0;            // bit L: this lane's load L of the short step lies inside K
 #pragma unroll
@@ -148,7 +169,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     int chunk = (slot % Cfg::A_CPR) ^ ((row / Cfg::A_RPB) % Cfg::A_CPR);  // logical 16-byte chunk stored at this slot
     int grow = row < rows ? row : rows - 1;
     if (a_rows) grow = a_rows[grow] / a_div;
-    a_src[i] = (const char*)(a + (long)grow * lda + chunk * 8);
+    a_voff[i] = (unsigned)grow * (unsigned)(lda * 2) + (unsigned)(chunk * 16);
     if (chunk * 8 < k_tail) tail_ok |= 1u << i;
   }
 #pragma unroll
@@ -159,50 +180,61 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
     int k = slot / Cfg::B_CPR, ncp = slot - k * Cfg::B_CPR;
     int nc = Cfg::B_SWZ ? (ncp ^ ((k & 3) << 2)) : ncp;
     int col = nc * 8 < cols ? nc * 8 : cols - 8;
-    b_src[i] = (const char*)(b + (long)k * ldb + col);
+    b_voff[i] = (unsigned)k * (unsigned)(ldb * 2) + (unsigned)(col * 2);
     if (k < k_tail) tail_ok |= 1u << (Cfg::A_PER_WAVE + i);
   }
-  const long b_step = ldb * Cfg::BK * 2;  // bytes per K-step
+  // scalar registers hold the two bases; they advance by one K step per requested stage
+  const char* a_base = (const char*)uniform64((unsigned long long)a);
+  const char* b_base = (const char*)uniform64((unsigned long long)b);
+  // (made uniform explicitly: inside a function that is not inlined the arguments arrive in vector registers)
+  const long b_step = (long)uniform64((unsigned long long)(ldb * Cfg::BK * 2));  // bytes per K-step
+  const unsigned smem_u = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem);
 
-  // Load number L (0..LPW-1) of this wave's share of the next stage in K order, into ring slot `slot`:
-  // loads 0..A_PER_WAVE-1 belong to the A tile, the rest to the B tile.  Advances that load's pointer.  `tail` (uniform):
-  // the stage is the short last K step, lanes whose piece lies beyond K load zeros.
-  auto issue_load = [&](int slot, auto l_c, bool tail) {
+  // Load number L (0..LPW-1) of this wave's share of the stage the bases point at, into ring slot `slot`:
+  // loads 0..A_PER_WAVE-1 belong to the A tile, the rest to the B tile.  `tail` (compile-time): the stage is the short
+  // last K step, lanes whose piece lies beyond K load zeros.
+  auto issue_load = [&](int slot, auto l_c, auto tail_c) {
     constexpr int L = decltype(l_c)::value;
-    char* sa = smem + slot * Cfg::STAGE_BYTES;
-    if constexpr (L < Cfg::A_PER_WAVE) {
-      int j = wave + L * Cfg::NWAVES;
-      const char* src = a_src[L];
-      if (tail && !((tail_ok >> L) & 1u)) src = (const char*)g_zero_chunk;
-      lds_load16(src, sa + (j < Cfg::A_LOADS ? j : Cfg::A_LOADS - 1) * 1024);
-      a_src[L] += Cfg::BK * 2;
+    constexpr bool TAIL = decltype(tail_c)::value;
+    constexpr bool IS_A = L < Cfg::A_PER_WAVE;
+    constexpr int LL = IS_A ? L : L - Cfg::A_PER_WAVE;
+    int j = wave + LL * Cfg::NWAVES;
+    if (j >= (IS_A ? Cfg::A_LOADS : Cfg::B_LOADS)) j = (IS_A ? Cfg::A_LOADS : Cfg::B_LOADS) - 1;
+    const unsigned lds = smem_u + (IS_A ? slot * Cfg::A_BYTES : A_REGION + slot * Cfg::B_BYTES) + j * 1024;
+    unsigned voff;
+    if constexpr (IS_A) voff = a_voff[LL]; else voff = b_voff[LL];
+    const char* base = IS_A ? a_base : b_base;
+    if constexpr (TAIL) {
+      const char* src = ((tail_ok >> L) & 1u) ? base + voff : (const char*)g_zero_chunk;
+      lds_load16_at(src, lds);
     } else {
-      constexpr int LB = L - Cfg::A_PER_WAVE;
-      int j = wave + LB * Cfg::NWAVES;
-      const char* src = b_src[LB];
-      if (tail && !((tail_ok >> L) & 1u)) src = (const char*)g_zero_chunk;
-      lds_load16(src, sa + Cfg::A_BYTES + (j < Cfg::B_LOADS ? j : Cfg::B_LOADS - 1) * 1024);
-      b_src[LB] += b_step;
+      lds_load16_sbase(base, voff, lds);
     }
   };
-  auto issue_stage = [&](int slot, bool tail) { static_for<0, LPW>([&](auto l_c) { issue_load(slot, l_c, tail); }); };
+  auto issue_stage = [&](int slot, auto tail_c) {
+    static_for<0, LPW>([&](auto l_c) { issue_load(slot, l_c, tail_c); });
+    a_base += Cfg::BK * 2;
+    b_base += b_step;
+  };
 
-  // ---- per-lane LDS read offsets
+  // ---- per-lane LDS read addresses (fixed for the tile; the stage and slice offsets are immediates)
   // A fragment (MFMA B operand): lane holds row (lane%32) of the wave's m-tile, k = 8*(lane/32)..+7 of the 16-wide k-slice.
   const int a_row = wm * Cfg::WTM + (lane & 31);
   const int a_x = (lane >> 5) ^ ((a_row / Cfg::A_RPB) % Cfg::A_CPR);
-  const int a_off = a_row * Cfg::A_PITCH;
+  const char* a_rd[SL];
+#pragma unroll
+  for (int sl = 0; sl < SL; sl++) a_rd[sl] = smem + a_row * Cfg::A_PITCH + ((a_x ^ (2 * sl)) << 4);
   // B fragment (MFMA A operand) via transposing reads: lane supplies the address of k-row
   // 8*(lane/32) + (lane%16)/4 (+4 for the second read), columns 16*((lane/16)%2) + 4*(lane%4)..+3.
   const int b_k = 8 * (lane >> 5) + ((lane & 15) >> 2);
   const int b_n = wn * Cfg::WTN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  int b_off[Cfg::NT];
+  const char* b_rd[Cfg::NT];
 #pragma unroll
   for (int nt = 0; nt < Cfg::NT; nt++) {
     int n = b_n + nt * 32;
     int nc = n >> 3;
     if (Cfg::B_SWZ) nc ^= (b_k & 3) << 2;
-    b_off[nt] = (b_k * Cfg::B_CPR + nc) * 16 + (n & 4) * 2;
+    b_rd[nt] = smem + A_REGION + (b_k * Cfg::B_CPR + nc) * 16 + (n & 4) * 2;
   }
 
   floatx16 acc[Cfg::MT][Cfg::NT];
@@ -214,14 +246,14 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       for (int e = 0; e < 16; e++) acc[mt][nt][e] = 0.f;
 
   bf16x8 af[2][Cfg::MT], bfr[2][Cfg::NT];
-  // One LDS fragment read of k-slice `sl` of the stage at LDS address `st` into register set BUF:
+  // One LDS fragment read of k-slice `sl` of the stage in ring slot `slot` into register set BUF:
   // reads 0..NT-1 fetch the B fragments (two transposing reads each), NT..NT+MT-1 the A fragments.
   constexpr int N_READS = Cfg::NT + Cfg::MT;
   constexpr int N_MFMA = Cfg::MT * Cfg::NT;
-  auto read_frag = [&](const char* st, int sl, auto buf_c, auto r_c) {
-    constexpr int BUF = decltype(buf_c)::value, R = decltype(r_c)::value;
+  auto read_frag = [&](int slot, auto sl_c, auto buf_c, auto r_c) {
+    constexpr int BUF = decltype(buf_c)::value, R = decltype(r_c)::value, S = decltype(sl_c)::value;
     if constexpr (R < Cfg::NT) {
-      const char* p = st + Cfg::A_BYTES + b_off[R] + sl * 16 * Cfg::B_CPR * 16;
+      const char* p = b_rd[R] + slot * Cfg::B_BYTES + S * 16 * Cfg::B_CPR * 16;
       short4_t lo = lds_read_tr(p);
       short4_t hi = lds_read_tr(p + 4 * Cfg::B_CPR * 16);
       typedef short short8_t __attribute__((ext_vector_type(8)));
@@ -229,19 +261,22 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       bfr[BUF][R] = __builtin_bit_cast(bf16x8, v);
     } else {
       constexpr int MTI = R - Cfg::NT;
-      af[BUF][MTI] = *(const bf16x8*)(st + a_off + MTI * 32 * Cfg::A_PITCH + ((a_x ^ (2 * sl)) << 4));
+      af[BUF][MTI] = *(const bf16x8*)(a_rd[S] + slot * Cfg::A_BYTES + MTI * 32 * Cfg::A_PITCH);
     }
   };
+  using std::integral_constant;
+  typedef integral_constant<bool, true> yes;
+  typedef integral_constant<bool, false> no;
   // One k-slice in fixed program order: the MFMAs of the slice held in register set CUR, with the
-  // fragment reads of the following slice (k-slice rsl of the stage at rst) placed after the first
+  // fragment reads of the following slice (k-slice RSL of the stage in ring slot rslot) placed after the first
   // MFMA, RPG per MFMA: no read sits between the wait for this slice's fragments and its first MFMA,
   // and the last read still has several MFMAs of cover.  BS = position of the slice in the loop body
-  // (which spans SL slices): the LPW global loads of a newly requested stage are spread evenly over
-  // the body's MFMAs, one at a time, so that no wave sits in a full memory-instruction queue while
-  // its MFMAs wait behind it.
-  auto slice = [&](auto cur_c, auto bs_c, auto reads_c, const char* rst, int rsl, bool issue, int islot, bool itail) {
+  // (which spans SL slices; -1 = outside the loop): with ISSUE, the LPW global loads of a newly requested stage (ring
+  // slot islot) are spread evenly over the body's MFMAs, one at a time, so that no wave sits in a full
+  // memory-instruction queue while its MFMAs wait behind it.
+  auto slice = [&](auto cur_c, auto bs_c, auto reads_c, int rslot, auto rsl_c, auto issue_c, auto tail_c, int islot) {
     constexpr int CUR = decltype(cur_c)::value, BS = decltype(bs_c)::value;
-    constexpr bool READS = decltype(reads_c)::value;
+    constexpr bool READS = decltype(reads_c)::value, ISSUE = decltype(issue_c)::value;
     constexpr int GAPS = N_MFMA > 2 ? N_MFMA - 2 : 1;
     constexpr int RPG = (N_READS + GAPS - 1) / GAPS;
     static_for<0, N_MFMA>([&](auto m_c) {
@@ -249,67 +284,88 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       constexpr int MTI = M / Cfg::NT, NTI = M % Cfg::NT;
       acc[MTI][NTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[CUR][NTI], af[CUR][MTI], acc[MTI][NTI], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (BS >= 0) {
+      if constexpr (BS >= 0 && ISSUE) {
         constexpr int G = BS * N_MFMA + M;  // MFMA index inside the loop body
         static_for<0, LPW>([&](auto l_c) {
           constexpr int L = decltype(l_c)::value;
           if constexpr (G == ((2 * L + 1) * SL * N_MFMA) / (2 * LPW)) {
-            if (issue) issue_load(islot, l_c, itail);
+            issue_load(islot, l_c, tail_c);
             __builtin_amdgcn_sched_barrier(0);
           }
         });
       }
       if constexpr (READS) {
         static_for<M * RPG, ((M + 1) * RPG < N_READS ? (M + 1) * RPG : N_READS)>([&](auto r_c) {
-          read_frag(rst, rsl, std::integral_constant<int, CUR ^ 1>{}, r_c);
+          read_frag(rslot, rsl_c, integral_constant<int, CUR ^ 1>{}, r_c);
         });
         __builtin_amdgcn_sched_barrier(0);
       }
     });
   };
-  using std::integral_constant;
-  typedef integral_constant<bool, true> yes;
-  typedef integral_constant<bool, false> no;
 
-  // K loop: BK per step, ring of NS LDS stages, stage s lives in slot s % NS.  The loop body starts at
+  // K loop: BK per step, ring of NS LDS stages, stage s lives in slot s % NS.  A loop body starts at
   // the barrier:
   //   wait + barrier : stage s+1 has landed for every wave; nobody reads stage s from LDS any more
   //                    (the fragments of its last slice are already in registers)
   //   body slice 0   : multiply the last slice of stage s, read (stage s+1, slice 0)
   //   body slice j>0 : multiply slice j-1 of stage s+1, read (stage s+1, slice j)
   //   throughout     : request stage s+NS into the slot stage s just left, one load at a time
-  // The last NS bodies request nothing and wait for all outstanding loads instead.
+  // The last NS bodies request nothing and wait for all outstanding loads instead; the body that requests a short
+  // last stage is a copy of its own.
   const int nk = (K + Cfg::BK - 1) / Cfg::BK;
-  const int n_pre = nk < NS ? nk : NS;
-  for (int s = 0; s < n_pre; s++) issue_stage(s, k_tail != 0 && s == nk - 1);
+  static_for<0, NS>([&](auto s_c) {
+    constexpr int S = decltype(s_c)::value;
+    if (S < nk) {
+      if (k_tail != 0 && S == nk - 1) issue_stage(S, yes{}); else issue_stage(S, no{});
+    }
+  });
   if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
   __syncthreads();
-  static_for<0, N_READS>([&](auto r_c) { read_frag(smem, 0, integral_constant<int, 0>{}, r_c); });
+  static_for<0, N_READS>([&](auto r_c) { read_frag(0, integral_constant<int, 0>{}, integral_constant<int, 0>{}, r_c); });
   static_for<0, SL - 1>([&](auto sl_c) {
     constexpr int S = decltype(sl_c)::value;
-    slice(integral_constant<int, S & 1>{}, integral_constant<int, -1>{}, yes{}, smem, S + 1, false, 0, false);
+    slice(integral_constant<int, S & 1>{}, integral_constant<int, -1>{}, yes{}, 0, integral_constant<int, S + 1>{}, no{}, no{}, 0);
   });
 
-  int slot = 0;  // s % NS
-  for (int s = 0; s + 1 < nk; s++) {
+  // body of K step s (ring slot `slot` = s % NS): MORE = a further stage (s + NS) is requested, TAIL = it is the short one
+  auto body = [&](int s, int slot, auto more_c, auto tail_c) {
+    constexpr bool MORE = decltype(more_c)::value;
     const int nslot = slot + 1 == NS ? 0 : slot + 1;
-    const char* nst = smem + nslot * Cfg::STAGE_BYTES;
-    const bool more = s + NS < nk;  // a further stage remains to be requested
-    const bool itail = k_tail != 0 && s + NS == nk - 1;  // ... and it is the short one
-    const bool new_chunk = KW::ENABLED && more && kw.starts(s + NS);
+    const bool new_chunk = KW::ENABLED && MORE && kw.starts(s + NS);
     if (new_chunk) kw.wait(s + NS);
     // stage s+1 must have landed; while requests continue, the NS-2 younger stages may stay in flight
-    if (more) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+    if constexpr (MORE) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
     __syncthreads();
     if (new_chunk) kw.acquire();
-    slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nst, 0, more, slot, itail);
+    slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, 0>{}, yes{}, nslot, integral_constant<int, 0>{}, more_c, tail_c, slot);
     static_for<0, SL - 1>([&](auto sl_c) {
       constexpr int S = decltype(sl_c)::value;
-      slice(integral_constant<int, S & 1>{}, integral_constant<int, S + 1>{}, yes{}, nst, S + 1, more, slot, itail);
+      slice(integral_constant<int, S & 1>{}, integral_constant<int, S + 1>{}, yes{}, nslot, integral_constant<int, S + 1>{}, more_c, tail_c, slot);
     });
-    slot = nslot;
+    if constexpr (MORE) {
+      a_base += Cfg::BK * 2;
+      b_base += b_step;
+    }
+  };
+  int s = 0;
+  const int n_main = nk - NS - (k_tail != 0 ? 1 : 0);   // K steps that request a whole further stage
+  for (; s + NS <= n_main; s += NS)
+    static_for<0, NS>([&](auto u_c) { body(s + decltype(u_c)::value, decltype(u_c)::value, yes{}, no{}); });
+  int slot = 0;                                          // s is a multiple of NS here
+  for (; s < n_main; s++) {
+    body(s, slot, yes{}, no{});
+    slot = slot + 1 == NS ? 0 : slot + 1;
   }
-  slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, smem, 0, false, 0, false);
+  if (k_tail != 0 && nk - NS - 1 >= 0) {                 // s == nk - NS - 1: this step requests the short last stage
+    body(s, slot, yes{}, yes{});
+    slot = slot + 1 == NS ? 0 : slot + 1;
+    s++;
+  }
+  for (; s + 1 < nk; s++) {
+    body(s, slot, no{}, no{});
+    slot = slot + 1 == NS ? 0 : slot + 1;
+  }
+  slice(integral_constant<int, (SL - 1) & 1>{}, integral_constant<int, -1>{}, no{}, 0, integral_constant<int, 0>{}, no{}, no{}, 0);
   __syncthreads();  // all operand reads of this tile are complete: LDS is free for the epilogue
 
   // ---- epilogue.  Accumulator register e of lane l holds C[row = l%32][col = (e/4)*8 + (l/32)*4 + e%4] of its 32x32

@@ -480,6 +480,8 @@ static int resolve_moe(const tl_ctx* ctx, int op, int T, int H, int I, int E, in
   if ((T / R) % c.channels_per_rank) return fail(TL_ERR_UNSUPPORTED_SHAPE, "channels per rank %d must divide T/R=%d", c.channels_per_rank, T / R);
   if (R * c.channels_per_rank > 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "at most 64 AllGather channels (R*C=%d)", R * c.channels_per_rank);
   if (H % 64 || I % 64) return fail(TL_ERR_UNSUPPORTED_SHAPE, "H=%d and I=%d must be multiples of 64", H, I);
+  // the grouped GEMM addresses a gathered token row as a 32-bit byte offset from the start of the token buffer
+  if ((long)T * H * 2 >= (1L << 32)) return fail(TL_ERR_UNSUPPORTED_SHAPE, "the gathered token buffer (T*H = %ld elements) must stay below 4 GiB", (long)T * H);
   memset(r, 0, sizeof *r);
   const int N = (op == TL_OP_MOE_AG_GATHER_GEMM) ? I : H;
   int v = -1;
