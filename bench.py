@@ -65,6 +65,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
 
             def fn(st=st):
                 st["epoch"] += 1
+                cs.wait_stream(ms)      # one call at a time per workspace
                 ms.wait_stream(cs)
                 call(st)
             t[name], _ = timed(fn, steps, warmup)
@@ -126,6 +127,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
 
         def fn(st=st, part=part):
             st["epoch"] += 1
+            cs.wait_stream(ms)
             ms.wait_stream(cs)
             mlp_call(st, (part,))
         r[f"{part}_fused_ms"] = round(timed(fn, steps, warmup)[0], 4)
@@ -316,6 +318,7 @@ def shape_table(torch, tl, dev, timed, cs, ms, mode, steps, warmup, over_ag=None
 
             def fn(st=st):
                 st["epoch"] += 1
+                cs.wait_stream(ms)      # one call at a time per workspace
                 ms.wait_stream(cs)
                 call(st)
             t[name] = timed(fn, steps, warmup)[0]
@@ -557,7 +560,8 @@ def main():
 
         def __call__(self):
             self.epoch += 1
-            ms.wait_stream(cs)          # the producer of this call may not run ahead into the previous call's GEMM
+            cs.wait_stream(ms)          # one call at a time per workspace: the previous call's communication side has finished
+            ms.wait_stream(cs)          # ... and the producer of this call may not run ahead into the previous call's GEMM
             if self.op == tl.TL_OP_AG_GEMM:
                 tl.tl_ag_gemm(self.ctx, shards, gathered, b2, c2, M, N, K, self.flags, self.epoch, self.wsp, self.ws_bytes, cs, ms)
             else:
@@ -635,11 +639,16 @@ def main():
         t_fused, _ = timed(fused, args.steps, args.warmup)
         for o in (fused, alone, comm):
             tl.tl_check_status(o.ctx, o.wsp)
+        mhz = {}
+        for key, o in (("fused", fused), ("compute_alone", alone)):     # shader clock of the last launch's first workgroup
+            cyc, ticks = tl.tl_read_clocks(o.ctx, o.wsp)
+            mhz[key] = round(cyc / max(ticks, 1) * 100.0, 0)
         fl = flop2 if op == tl.TL_OP_AG_GEMM else flop3
         res[name] = {"fused_ms": round(t_fused, 4), "compute_alone_ms": round(t_alone, 4), "comm_alone_ms": round(t_comm, 4),
                      "tflops": round(fl / t_fused / 1e9, 1), "frac_of_peak": round(fl / t_fused / 1e9 / PEAK_BF16_TFLOPS, 4),
                      "compute_alone_tflops": round(fl / t_alone / 1e9, 1),
                      "overlap_efficiency": round(max(t_alone, t_comm) / t_fused, 4),
+                     "shader_mhz_fused": mhz["fused"], "shader_mhz_compute_alone": mhz["compute_alone"],
                      "compute_alone_fresh_input_ms": round(t_cold, 4),
                      "overlap_efficiency_fresh_input": round(max(t_cold, t_comm) / t_fused, 4),
                      "paper_overlap_ratio": round((t_alone + t_comm - t_fused) / t_comm, 4),
@@ -656,6 +665,27 @@ def main():
     for o in ops_.values():
         tl.tl_check_status(o.ctx, o.wsp)
     tflops = (flop2 + flop3) / ms_step / 1e9
+
+    # ---------------- what the matrix cores alone sustain on this data: MFMA-only register loop, operands drawn like the
+    # GEMM's (activations N(0,1), weights N(0,0.02)); the clock the chip grants depends on the operand values
+    n_thr = torch.cuda.get_device_properties(0).multi_processor_count * 512
+    opnd = torch.cat([torch.randn((n_thr, 32), device=dev, dtype=torch.float32), torch.randn((n_thr, 16), device=dev, dtype=torch.float32) * 0.02],
+                     dim=1).to(torch.bfloat16).contiguous()
+    sink = torch.zeros(n_thr, dtype=torch.float32, device=dev)
+    clk = torch.zeros(2, dtype=torch.int64, device=dev)
+    pctx = ops_["ag_gemm"].ctx
+    probe_iters, probe_ms, probe_flop = 20000, [], 0.0
+    for i in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(cs)
+        probe_flop = tl.tl_mfma_peak_probe(pctx, opnd, opnd.numel() * 2, probe_iters, sink, clk, cs)
+        e1.record(cs)
+        torch.cuda.synchronize()
+        probe_ms.append(e0.elapsed_time(e1))
+    mfma_only_tflops = probe_flop / (sum(probe_ms[2:]) / 3.0) / 1e9
+    pc = clk.cpu().tolist()
+    mfma_only_mhz = round(pc[0] / max(pc[1], 1) * 100.0, 0)
+    del opnd, sink
 
     # dominant kernel = the fused GEMM kernels (AG+GEMM and GEMM+RS have the same flop count); the
     # average launch duration is the fused time measured above on the stream the kernel runs on
@@ -674,7 +704,14 @@ def main():
         "ops": res,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": HBM_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)"},
+                     "traffic_source": "constant from the FETCH_SIZE / WRITE_SIZE counter runs in profiles/bench_ag_gemm_gemm_rs_mlp5_tp8.md, "
+                                       "not measured by this run",
+                     "kernel": "ag_gemm_kernel / gemm_rs_kernel (4.81e11 flop per launch each)",
+                     "mfma_only_tflops": round(mfma_only_tflops, 1), "mfma_only_shader_mhz": mfma_only_mhz,
+                     "frac_of_sustained": round(achieved / mfma_only_tflops, 4),
+                     "shader_mhz": {k: {"fused": v["shader_mhz_fused"], "compute_alone": v["shader_mhz_compute_alone"]} for k, v in res.items()},
+                     "note": "mfma_only_tflops = MFMA-only register loop (tl_mfma_peak_probe, 8 waves per compute unit) on operands drawn like the "
+                             "GEMM's: what the matrix cores sustain at the clock the chip grants for this data; frac is against the datasheet peak"},
         "host_wall_ms_per_step": round(wall_step, 4),
     }
     if not args.no_extras and mode != tl.TL_COMM_STREAM:

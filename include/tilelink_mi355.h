@@ -140,6 +140,23 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims /*host*/
  * tl_ag_gemm_static on the context's device. */
 int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
 
+/* Measurement aid: the rate the matrix cores alone sustain on given operand data (an MFMA-only register loop, one
+ * workgroup of 8 waves per compute unit; no LDS, no loads inside the loop).  Enqueues one kernel on `stream`.
+ *   operands  dev, bf16 values drawn as the GEMM inputs are (num_compute_units * 512 * 48 of them, 16-byte aligned);
+ *             operand_bytes = their size, checked.   iters = loop iterations of 8 matrix instructions per wave.
+ *   sink      dev float[num_compute_units * 512] (written; keeps the loop alive)
+ *   clocks    dev long long[2] (written): shader cycles and 100 MHz ticks the first workgroup's loop took
+ *   flop      host, optional: the matrix work of the launch, so that flop / measured time = the sustained rate. */
+int tl_mfma_peak_probe(tl_ctx* ctx, const void* operands /*dev*/, size_t operand_bytes, int iters, float* sink /*dev*/,
+                       long long* clocks /*dev*/, void* stream, double* flop /*host*/);
+
+/* Measurement aid.  Synchronous: after a tl_ag_gemm-family or tl_gemm_rs-family call has completed, out[0] = shader-clock
+ * cycles and out[1] = ticks of the 100 MHz wall clock during which the call's first compute workgroup was resident
+ * (kept in bytes 32..47 of the workspace): out[0] / out[1] x 100 is the shader clock in MHz the tile kernel ran at.  On
+ * this chip that clock depends on the operand data, so it belongs beside every throughput figure.  workspace = NULL: the
+ * static scratch of tl_ag_gemm_static. */
+int tl_read_clocks(tl_ctx* ctx, void* workspace /*dev*/, long long* out /*host, 2 values*/);
+
 /*
  * AllGather + GEMM (paper: "Tile-Centric Mapping", AllGather pull mode + GEMM; tensor-parallel
  * FFN first half).  C[M,N] = concat_rows(a_shards[0..R-1])[M,K] . B[K,N], fp32 accumulation,

@@ -54,6 +54,8 @@ _lib.tl_ctx_create_host.argtypes = [ctypes.POINTER(tl_config), _i, ctypes.POINTE
 _lib.tl_ctx_destroy.argtypes = [_vp]
 _lib.tl_query_workspace.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
 _lib.tl_check_status.argtypes = [_vp, _vp]
+_lib.tl_read_clocks.argtypes = [_vp, _vp, ctypes.POINTER(ctypes.c_longlong)]
+_lib.tl_mfma_peak_probe.argtypes = [_vp, _vp, _sz, _i, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
 _lib.tl_resolve.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i)]
 _lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i), _sz, ctypes.POINTER(_sz)]
 _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
@@ -142,6 +144,20 @@ def tl_query_workspace(ctx, op, dims):
 
 def tl_check_status(ctx, workspace):
     _check(_lib.tl_check_status(ctx, _ptr(workspace)))
+
+
+def tl_read_clocks(ctx, workspace):
+    """(shader cycles, 100 MHz ticks) of the last call's first compute workgroup; cycles / ticks * 100 = MHz."""
+    out = (ctypes.c_longlong * 2)()
+    _check(_lib.tl_read_clocks(ctx, _ptr(workspace), out))
+    return int(out[0]), int(out[1])
+
+
+def tl_mfma_peak_probe(ctx, operands, operand_bytes, iters, sink, clocks, stream=None):
+    """Enqueues the MFMA-only loop; returns the matrix work of the launch in flop."""
+    flop = ctypes.c_double()
+    _check(_lib.tl_mfma_peak_probe(ctx, _ptr(operands), operand_bytes, iters, _ptr(sink), _ptr(clocks), _stream(stream), ctypes.byref(flop)))
+    return flop.value
 
 
 def tl_resolve(ctx, op, dims):

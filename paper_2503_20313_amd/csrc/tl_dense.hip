@@ -66,6 +66,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
   __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   const int M_per_channel = p.prod.rows_per_channel;
+  const ClockSample cs0 = clock_sample_begin(w);
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
     int tile = sched_tile(p.sched, pos);
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
@@ -92,6 +93,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) ag_gemm_kernel(const AgGemmPara
       gemm_tile<Cfg>(p.prod.gathered + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, p.N, out, rows, cols, p.K, smem);
     }
   }
+  clock_sample_end(cs0, w, p.prod.ctl.status);
 }
 
 // Producer as a kernel of its own (small register/LDS footprint, so it can share compute units
@@ -119,6 +121,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
   __builtin_amdgcn_s_setprio(TL_COMPUTE_WAVE_PRIO);  // matrix waves go first when they share a SIMD with communication waves
   const int w = blockIdx.x - p.n_comm;
   const RsSide& rs = p.rs;
+  const ClockSample cs0 = clock_sample_begin(w);
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
     int tile = sched_tile(p.sched, pos);
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
@@ -160,6 +163,43 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
         }
       }
     }
+  }
+  clock_sample_end(cs0, w, rs.ctl.status);
+}
+
+// Achievable-peak probe: nothing but matrix instructions on register operands -- every compute unit runs one workgroup
+// of 8 waves (two per SIMD, as in the tile kernels), each wave `iters` times the 8 MFMAs of one k-slice of its 128x64
+// wave tile (4 + 2 operand fragments loaded once from `operands`, 8 accumulators).  What this loop reaches on a given
+// operand distribution is what the matrix cores sustain at the clock the chip grants for that data; the first
+// workgroup leaves its cycle and wall-clock counts in `clocks`.
+__global__ void __launch_bounds__(512) mfma_peak_kernel(const u32x4* __restrict__ operands, float* __restrict__ sink, int iters, long long* clocks) {
+  const size_t t = (size_t)blockIdx.x * 512 + threadIdx.x;
+  u32x4 fa[4], fb[2];
+#pragma unroll
+  for (int j = 0; j < 4; j++) fa[j] = operands[t * 6 + j];
+#pragma unroll
+  for (int j = 0; j < 2; j++) fb[j] = operands[t * 6 + 4 + j];
+  floatx16 c[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) c[j][e] = 0.f;
+  const long long c0 = clock64();
+  const unsigned long long w0 = wall_clock64();
+  for (int i = 0; i < iters; i++) {
+#pragma unroll
+    for (int m = 0; m < 8; m++)
+      c[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[m & 1]), __builtin_bit_cast(bf16x8, fa[m >> 1]), c[m], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; j++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) sum += c[j][e];
+  sink[t] = sum;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    clocks[0] = clock64() - c0;
+    clocks[1] = (long long)(wall_clock64() - w0);
   }
 }
 
@@ -504,6 +544,27 @@ int tl_query_workspace(const tl_ctx* ctx, int op, const long long* dims, size_t*
     return TL_OK;
   }
   return fail(TL_ERR_INVALID_ARG, "unknown operator %d", op);
+}
+
+int tl_mfma_peak_probe(tl_ctx* ctx, const void* operands, size_t operand_bytes, int iters, float* sink, long long* clocks, void* stream,
+                       double* flop) {
+  if (int e = check_op_ctx(ctx)) return e;
+  if (!operands || !sink || !clocks || iters <= 0) return fail(TL_ERR_INVALID_ARG, "tl_mfma_peak_probe: null pointer or non-positive iteration count");
+  const size_t need = (size_t)ctx->num_cus * 512 * 6 * 16;
+  if (operand_bytes < need) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_mfma_peak_probe: %zu operand bytes given, %zu needed", operand_bytes, need);
+  if (!aligned16(operands)) return fail(TL_ERR_INVALID_ARG, "tl_mfma_peak_probe: operands must be 16-byte aligned");
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(ctx->num_cus), dim3(512), 0, (hipStream_t)stream, (const u32x4*)operands, sink, iters, clocks);
+  TL_HIP(hipGetLastError());
+  if (flop) *flop = (double)ctx->num_cus * 8.0 * iters * 8.0 * 32768.0;   // workgroups x waves x iterations x MFMAs x (2 x 32 x 32 x 16)
+  return TL_OK;
+}
+
+int tl_read_clocks(tl_ctx* ctx, void* workspace, long long* out) {
+  if (int e = check_op_ctx(ctx)) return e;
+  if (!workspace && ctx->device < kMaxDevices) workspace = g_static[ctx->device].ptr;
+  if (!workspace || !out) return fail(TL_ERR_INVALID_ARG, "workspace or out is null");
+  TL_HIP(hipMemcpy(out, (const char*)workspace + 32, 2 * sizeof(long long), hipMemcpyDeviceToHost));
+  return TL_OK;
 }
 
 int tl_check_status(tl_ctx* ctx, void* workspace) {

@@ -119,6 +119,26 @@ __device__ __forceinline__ void wave_tile_wait(const unsigned* flag, unsigned ta
 }
 
 // ---------------------------------------------------------------------------------------
+// Clock sample of a launch: the first compute workgroup reads the shader-clock cycle counter and the 100 MHz wall clock
+// when it starts and when it has finished its last tile, and leaves both differences in bytes 32..47 of the workspace
+// (cycles, ticks): cycles / ticks x 100 = the shader clock in MHz the launch ran at, which on this chip depends on the
+// operand data (measurement, read with tl_read_clocks).
+// ---------------------------------------------------------------------------------------
+struct ClockSample { long long cycles; unsigned long long ticks; };
+__device__ __forceinline__ ClockSample clock_sample_begin(int compute_wg) {
+  ClockSample c = {0, 0};
+  if (compute_wg == 0) { c.cycles = clock64(); c.ticks = wall_clock64(); }
+  return c;
+}
+__device__ __forceinline__ void clock_sample_end(const ClockSample& c0, int compute_wg, int* status_word) {
+  if (compute_wg == 0 && threadIdx.x == 0) {
+    long long* o = (long long*)status_word + 4;
+    o[0] = clock64() - c0.cycles;
+    o[1] = (long long)(wall_clock64() - c0.ticks);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Single-lane atomics without a divergent branch.  A loop whose body holds workgroup barriers
 // must stay uniform for the compiler as well as at run time: with an `if (tid == 0)` around an
 // atomic inside such a loop, the control-flow structurizer is free to rotate the divergent part
