@@ -461,7 +461,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream"])
+    ap.add_argument("--comm-mode", default="side", choices=["waves", "side", "stream", "copy_engine"],
+                    help="resource binding of the communication side; copy_engine (a DMA engine moves the AllGather's shards) applies to AG+GEMM, "
+                         "GEMM+RS then uses the side kernel")
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--ag-comm-tile-m", type=int, default=0, help="rows of an AllGather producer tile (default: the library's choice)")
@@ -507,7 +509,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
         return
-    mode = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM}[args.comm_mode]
+    mode = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM, "copy_engine": tl.TL_COMM_COPY_ENGINE}[args.comm_mode]
+    STREAMED = (tl.TL_COMM_STREAM, tl.TL_COMM_COPY_ENGINE)
 
     def up(bits):
         return torch.from_numpy(bits.view(np.int16)).to(dev)
@@ -543,12 +546,14 @@ def main():
             tm, tn = (int(v) for v in tile.split("x"))
             fields = dict(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
                           comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
-                          ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
-                          link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode != tl.TL_COMM_STREAM else 0,
+                          ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode not in STREAMED else 0,
+                          link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode not in STREAMED else 0,
                           comm_workgroups=args.comm_workgroups, xcd_swizzle=1,
                           tile_order=tl.TL_ORDER_ARRIVAL if op == tl.TL_OP_AG_GEMM and args.ag_order == "arrival" else tl.TL_ORDER_OWN_FIRST,
                           spin_timeout_us=10_000_000, comm_alone=comm_alone, rs_direct_push=0 if args.no_direct_push else args.direct_push_mode)
             fields.update(over)
+            if op == tl.TL_OP_GEMM_RS and fields["comm_mode"] == tl.TL_COMM_COPY_ENGINE:
+                fields["comm_mode"] = tl.TL_COMM_SIDE_KERNEL      # the reduction needs compute units
             self.ctx = tl.tl_ctx_create(**fields)
             self.op, self.dims = op, dims
             self.ws_bytes, n_flags = tl.tl_query_workspace(self.ctx, op, dims)
@@ -606,7 +611,7 @@ def main():
 
     if args.shape_table:
         del shards, gathered, a_full, b2, c2, a3, b3, a3_src, partial, recv, push, out3
-        table = shape_table(torch, tl, dev, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL, min(args.steps, 20), 3,
+        table = shape_table(torch, tl, dev, timed, cs, ms, mode if mode not in STREAMED else tl.TL_COMM_SIDE_KERNEL, min(args.steps, 20), 3,
                             over_ag=dict(ag_k_chunks=args.ag_k_chunks, comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups,
                                          tile_m=int((args.ag_tile or "0x0").split("x")[0]), tile_n=int((args.ag_tile or "0x0").split("x")[1])),
                             over_rs=dict(comm_tile_m=args.rs_comm_tile_m, comm_workgroups=args.comm_workgroups), only=args.shape_filter)
@@ -714,7 +719,7 @@ def main():
                              "GEMM's: what the matrix cores sustain at the clock the chip grants for this data; frac is against the datasheet peak"},
         "host_wall_ms_per_step": round(wall_step, 4),
     }
-    if not args.no_extras and mode != tl.TL_COMM_STREAM:
+    if not args.no_extras and mode not in STREAMED:
         # AG+GEMM with the shards arriving over simulated xGMI links (153 GB/s per source rank, all side by side), arrival
         # tile order.  (Four K chunks per channel are 2 % faster still, but need the producer kernel to run beside the
         # GEMM, which a profiler that serialises kernels does not allow.)
@@ -729,7 +734,7 @@ def main():
                                     "overlap_efficiency": round(max(res["ag_gemm"]["compute_alone_ms"], t_cl) / t_fl, 4),
                                     "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 1}
     if not args.no_extras:
-        out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode != tl.TL_COMM_STREAM else tl.TL_COMM_SIDE_KERNEL,
+        out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode not in STREAMED else tl.TL_COMM_SIDE_KERNEL,
                                args.steps, args.warmup, 0 if args.no_direct_push else 1, args.comm_workgroups)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops

@@ -109,6 +109,36 @@ __global__ void notify_kernel(unsigned* flags, int count, unsigned inc) {
   if (i < count) tile_notify(flags + i, inc);
 }
 
+// producer_tile_notify of one finished GEMM tile: one add per reduce tile it overlaps -- and, for a reduce tile of another
+// rank's segment that this tile alone fills, the announcement to its owner (peer_tile_notify) right with it.  The tile's
+// rows were stored written-through to device scope (PushRows), so "released" means no more than: every wave has seen its
+// stores complete and the workgroup has met at a barrier since; the caller guarantees both (gemm_tile's hook, or an
+// explicit wait after the last tile).  Deferring the notification into the next tile's prologue hides that wait behind
+// the latency of the next tile's first loads: a release fence at device scope right after the epilogue cost 4-5 us per tile.
+struct TileNotify {
+  const RsSide* rs;
+  bool have;          // false: nothing pending
+  int row_lo, col_lo, rows, cols;
+  __device__ __forceinline__ bool pending() const { return have; }
+  __device__ __forceinline__ void run() const {
+    const RsSide& r = *rs;
+    const int cm_lo = row_lo / r.Tm_r, cm_hi = (row_lo + rows - 1) / r.Tm_r;
+    const int cn_lo = col_lo / r.Tn_r, cn_hi = (col_lo + cols - 1) / r.Tn_r;
+    const int ncols = cn_hi - cn_lo + 1, cnt = (cm_hi - cm_lo + 1) * ncols;
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+      const int cm = cm_lo + i / ncols, cn = cn_lo + i % ncols;
+      __hip_atomic_fetch_add(r.ready + cm * r.ncn + cn, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int r_lo = cm * r.Tm_r, c_lo = cn * r.Tn_r;
+      const int r_n = min(r.Tm_r, r.M - r_lo), c_n = min(r.Tn_r, r.N - c_lo);
+      if (producer_notifies_peer(r, r_lo, r_n, c_lo, c_n)) {
+        const int dest = r_lo / r.seg_rows;
+        const int local = (cm - dest * (r.seg_rows / r.Tm_r)) * r.ncn + cn;
+        __hip_atomic_fetch_add(r.pushed + dest * r.tiles_per_seg + local, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+};
+
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -122,6 +152,10 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
   const int w = blockIdx.x - p.n_comm;
   const RsSide& rs = p.rs;
   const ClockSample cs0 = clock_sample_begin(w);
+  // the 224-wide tile has no register left for the state a deferred notification carries from tile to tile
+  constexpr bool DEFER = Cfg::BN != 224;
+  bool have = false;            // the previous tile of this workgroup awaits its notification
+  int p_row = 0, p_col = 0, p_rows = 0, p_cols = 0;
   for (int pos = w; pos < p.sched.n_tiles; pos += p.sched.G) {
     int tile = sched_tile(p.sched, pos);
     int bm = tile / p.sched.nbn, bn = tile - bm * p.sched.nbn;
@@ -142,27 +176,24 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
       }
       __syncthreads();
     }
-    gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRows{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
-    if (p.do_notify) {
-      // producer_tile_notify: one release-add per reduce tile this GEMM tile overlaps
-      __syncthreads();
-      int cm_lo = row_lo / rs.Tm_r, cm_hi = (row_lo + rows - 1) / rs.Tm_r;
-      int cn_lo = col_lo / rs.Tn_r, cn_hi = (col_lo + cols - 1) / rs.Tn_r;
-      int ncols = cn_hi - cn_lo + 1, cnt = (cm_hi - cm_lo + 1) * ncols;
-      for (int i = tid; i < cnt; i += Cfg::NTHREADS) {
-        const int cm = cm_lo + i / ncols, cn = cn_lo + i % ncols;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // one release, then relaxed adds
-        __hip_atomic_fetch_add(rs.ready + cm * rs.ncn + cn, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // a reduce tile of another rank's segment that this tile alone fills: tell its owner right away
-        const int r_lo = cm * rs.Tm_r, c_lo = cn * rs.Tn_r;
-        const int r_n = min(rs.Tm_r, rs.M - r_lo), c_n = min(rs.Tn_r, rs.N - c_lo);
-        if (producer_notifies_peer(rs, r_lo, r_n, c_lo, c_n)) {
-          const int dest = r_lo / rs.seg_rows;
-          const int local = (cm - dest * (rs.seg_rows / rs.Tm_r)) * rs.ncn + cn;
-          __hip_atomic_fetch_add(rs.pushed + dest * rs.tiles_per_seg + local, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    if constexpr (DEFER) {
+      // producer_tile_notify of the PREVIOUS tile happens inside this tile's prologue, once its stores are known complete
+      gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRowsT<true>{&rs, row_lo, col_lo}, rows, cols, p.K, smem, NoKWait{},
+                     TileNotify{&rs, have, p_row, p_col, p_rows, p_cols});
+      if (p.do_notify) { have = true; p_row = row_lo; p_col = col_lo; p_rows = rows; p_cols = cols; }
+    } else {
+      gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRowsT<false>{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
+      if (p.do_notify) {
+        __syncthreads();                                      // every wave's stores are complete ...
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and written back to where every die sees them
+        TileNotify{&rs, true, row_lo, col_lo, rows, cols}.run();
       }
     }
+  }
+  if (have) {   // the last tile: nothing follows that could hide the wait for its stores
+    wait_vmcnt<0>();
+    __syncthreads();
+    TileNotify{&rs, true, p_row, p_col, p_rows, p_cols}.run();
   }
   clock_sample_end(cs0, w, rs.ctl.status);
 }

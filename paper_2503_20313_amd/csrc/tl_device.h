@@ -118,6 +118,13 @@ __device__ __forceinline__ void wave_tile_wait(const unsigned* flag, unsigned ta
   }
 }
 
+// 16-byte global store written through to device scope (sc1): once the wave's memory counter says it is complete it is
+// visible to every die, so a producer that stores its tile this way can notify after a plain wait for its own stores,
+// without the L2 write-back a release fence at device scope performs.
+__device__ __forceinline__ void store16_device_scope(void* p, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // ---------------------------------------------------------------------------------------
 // Clock sample of a launch: the first compute workgroup reads the shader-clock cycle counter and the 100 MHz wall clock
 // when it starts and when it has finished its last tile, and leaves both differences in bytes 32..47 of the workspace

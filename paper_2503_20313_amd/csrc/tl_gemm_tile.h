@@ -109,6 +109,16 @@ struct NoKWait {
   __device__ __forceinline__ void acquire() const {}
 };
 
+// Hook of gemm_tile for work that has to wait until this workgroup's earlier global stores are complete (the deferred
+// producer_tile_notify of the previous tile): when pending() holds, the prologue waits for ALL outstanding vector memory
+// operations of every wave instead of for the first stage only -- the stores of the previous tile's epilogue were issued
+// before this tile's loads and have long been on their way -- and run() is called by every thread right after the
+// workgroup barrier that follows.
+struct NoHook {
+  __device__ __forceinline__ bool pending() const { return false; }
+  __device__ __forceinline__ void run() const {}
+};
+
 // Output of a GEMM whose B holds a gate and an up projection side by side, 32 columns of the one, then the same 32
 // features of the other (so that the two values of a feature sit in the same lane, in neighbouring 32x32 accumulator
 // blocks): the tile stores act(gate) * up, half as many columns as it computes (the activation between the two halves
@@ -146,10 +156,10 @@ struct GatedRows {
 // whole tile) + (an immediate), and the direct-to-LDS loads as (a scalar base that advances per K step) + (a lane
 // offset fixed for the whole tile).  The loop body is left with no vector-ALU instruction besides the matrix ones:
 // measured on this chip, a plain vector instruction does not overlap a matrix instruction of the same SIMD, it delays it.
-template <class Cfg, class Out, class KW = NoKWait>
+template <class Cfg, class Out, class KW = NoKWait, class Hook = NoHook>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda, const int* __restrict__ a_rows, int a_div,
                                           const bf16_t* __restrict__ b, long ldb, const Out& out, int rows, int cols, int K,
-                                          char* smem, const KW& kw = KW{}) {
+                                          char* smem, const KW& kw = KW{}, const Hook& hook = Hook{}) {
   constexpr int NS = Cfg::NS, SL = Cfg::SL, LPW = Cfg::LPW;
   constexpr int A_REGION = NS * Cfg::A_BYTES;   // the B stages start here
   const int tid = threadIdx.x, lane = tid & 63;
@@ -319,8 +329,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       if (k_tail != 0 && S == nk - 1) issue_stage(S, yes{}); else issue_stage(S, no{});
     }
   });
-  if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
+  const bool hooked = hook.pending();
+  if (nk >= NS && !hooked) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
   __syncthreads();
+  if (hooked) hook.run();
   static_for<0, N_READS>([&](auto r_c) { read_frag(0, integral_constant<int, 0>{}, integral_constant<int, 0>{}, r_c); });
   static_for<0, SL - 1>([&](auto sl_c) {
     constexpr int S = decltype(sl_c)::value;
@@ -417,7 +429,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
       out.store(grow, col, *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16));
     }
   }
-  __syncthreads();  // the next tile's loads overwrite the staging regions
+  // the next tile's loads overwrite the staging regions: all LDS reads must be done; the global stores need not be
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 }  // namespace tl

@@ -119,7 +119,10 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
 
 // Where the rows of a [M,N] partial result go (output functor of the matrix tile): row g of the own segment to
 // partial[g,:], and with direct push row g of segment q to peer_push[q][g - q*seg_rows,:]; else all rows to partial.
-struct PushRows {
+// WT: the rows are stored written-through to device scope, so that the tile's notification can follow a plain wait for
+// the stores (TileNotify); else ordinary stores, and the notification needs a release fence at device scope.
+template <bool WT>
+struct PushRowsT {
   static constexpr bool SCALED = false, GATED = false;
   const RsSide* rs;
   int row_lo, col_lo;
@@ -129,14 +132,15 @@ struct PushRows {
     if (!rs->direct || dest == rs->rank) return rs->partial + (long)g * rs->N + col_lo;
     return rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo;
   }
-  // 8 values of tile row r at tile column col.  Mode 2, own segment: besides the bf16 partial, out = bf16(sum over
+  // 8 values of tile row r at tile column col, written through to device scope (the tile's notification follows a plain
+  // wait for these stores, see TileNotify).  Mode 2, own segment: besides the bf16 partial, out = bf16(sum over
   // ranks in rank order, fp32) with the R-1 peer values of the same place loaded together (the caller has done the
   // peer_tile_wait): the same arithmetic as the consumer's sum, so both paths give identical bits.
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const {
     const int g = row_lo + r;
     const int dest = g / rs->seg_rows;
     if (!rs->direct || dest == rs->rank) {
-      *(u32x4*)(rs->partial + (long)g * rs->N + col_lo + col) = v;
+      put(rs->partial + (long)g * rs->N + col_lo + col, v);
       if (rs->direct == 2) {
         const long off = (long)(g - dest * rs->seg_rows) * rs->N + col_lo + col;
         u32x4 pv[kMaxWorld];
@@ -150,8 +154,11 @@ struct PushRows {
         *(u32x4*)(rs->out + off) = pack_bf16x8(s);
       }
     } else {
-      *(u32x4*)(rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo + col) = v;
+      put(rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo + col, v);
     }
+  }
+  __device__ __forceinline__ void put(bf16_t* p, u32x4 v) const {
+    if constexpr (WT) store16_device_scope(p, v); else *(u32x4*)p = v;
   }
 };
 
