@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) gemm_rs_kernel(const GemmRsPara
                      TileNotify{&rs, have, p_row, p_col, p_rows, p_cols});
       if (p.do_notify) { have = true; p_row = row_lo; p_col = col_lo; p_rows = rows; p_cols = cols; }
     } else {
-      gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRowsT<false>{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
+      gemm_tile<Cfg>(p.a + (long)row_lo * p.K, p.K, nullptr, 1, p.b + col_lo, rs.N, PushRowsT<false, false>{&rs, row_lo, col_lo}, rows, cols, p.K, smem);
       if (p.do_notify) {
         __syncthreads();                                      // every wave's stores are complete ...
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and written back to where every die sees them

@@ -124,6 +124,10 @@ __device__ __forceinline__ void wave_tile_wait(const unsigned* flag, unsigned ta
 __device__ __forceinline__ void store16_device_scope(void* p, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
+// ... with the address as a scalar base (the same for every lane) plus a 32-bit lane offset
+__device__ __forceinline__ void store16_device_scope(const void* base, unsigned lane_off, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, %2 sc1" ::"v"(lane_off), "v"(v), "s"(base) : "memory");
+}
 
 // ---------------------------------------------------------------------------------------
 // Clock sample of a launch: the first compute workgroup reads the shader-clock cycle counter and the 100 MHz wall clock

@@ -96,6 +96,7 @@ struct DenseRows {
   long ldc;
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
   // 8 consecutive bf16 of tile row r starting at tile column col (col % 8 == 0)
+  __device__ __forceinline__ void group(int /*r0*/) const {}
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(c + (long)r * ldc + col) = v; }
 };
 
@@ -131,6 +132,7 @@ struct GatedRows {
   long ldc;
   int act;
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const { return c + (long)r * ldc; }
+  __device__ __forceinline__ void group(int /*r0*/) const {}
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(c + (long)r * ldc + col) = v; }
   __device__ __forceinline__ float apply(float g, float u) const {
     if (act == ACT_SILU_MUL) return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;  // g * sigmoid(g) * u
@@ -143,7 +145,10 @@ struct GatedRows {
 // within 4 GiB of `a`); `b` points at row 0 of B at the tile's first column; both are the same for every lane.
 // `out.row(r, scale)` gives the address of the tile's first
 // column in output row r (and a per-row factor applied in fp32 before rounding if Out::SCALED);
-// `out.store(r, col, v)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce).
+// `out.store(r, col, v, r0)` stores 8 rounded values of row r (a functor may do more with them, e.g. reduce); r0 is the
+// first of the consecutive rows that the same store instruction covers (no lane's row is below it), the same for every lane, so that a
+// functor whose destination depends on the row can decide per instruction instead of per lane.  gemm_tile works on a copy
+// of the functor, which may therefore keep state from one store to the next.
 // With Out::GATED the tile's columns come in pairs of 32 (gate, up): out.apply(gate, up) is stored, at half the column.
 // rows/cols = valid extent of the tile (ragged edges): loads are clamped to valid memory, stores are
 // masked.  K % 8 == 0 (rows of A start on 16-byte boundaries); a last K step shorter than BK is filled up with zeros:
@@ -420,13 +425,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ a, long lda
   constexpr int EP_ITERS = Cfg::WTM * EP_CPR / 64;
   static_assert((Cfg::WTM * EP_CPR) % 64 == 0, "the epilogue hands out 16-byte chunks 64 at a time");
   const int out_cols = Out::GATED ? cols / 2 : cols;
+  Out o = out;
 #pragma unroll 4
   for (int i = 0; i < EP_ITERS; i++) {
     const int idx = i * 64 + lane;
     const int row = idx / EP_CPR, q = idx - row * EP_CPR;
     const int grow = wm * Cfg::WTM + row, col = wn * OUT_WTN + q * 8;
+    o.group(wm * Cfg::WTM + (i * 64) / EP_CPR);
     if (grow < rows && col < out_cols) {  // cols % 8 == 0: a chunk is all in or all out
-      out.store(grow, col, *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16));
+      o.store(grow, col, *(const u32x4*)(ep + row * Cfg::EP_PITCH + q * 16));
     }
   }
   // the next tile's loads overwrite the staging regions: all LDS reads must be done; the global stores need not be

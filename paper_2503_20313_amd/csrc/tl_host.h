@@ -130,6 +130,7 @@ inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void
   p->Tm_r = Tm_r; p->Tn_r = Tn_r; p->ncm = M / Tm_r; p->ncn = N / Tn_r;
   p->direct = cfg.rs_direct_push == 2 ? 2 : (cfg.rs_direct_push ? 1 : 0);
   p->seg_rows = M / R;
+  p->fast_rows = (long)(M / R) * N * 2 < (1L << 32) ? 1 : 0;
   p->tiles_per_seg = (p->seg_rows / Tm_r) * p->ncn;
   p->rs_first_block = 0;
   p->do_wait = 1;

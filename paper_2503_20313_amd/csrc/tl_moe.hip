@@ -322,6 +322,7 @@ struct ScatterRows {
     scale = w[rid];
     return scatter + (long)rid * ld;
   }
+  __device__ __forceinline__ void group(int /*r0*/) const {}
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(scatter + (long)rows[r] * ld + col) = v; }
 };
 

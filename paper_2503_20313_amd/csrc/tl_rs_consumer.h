@@ -18,6 +18,7 @@ struct RsSide {
   int do_wait;                      // wait for the producer stage's notifications
   int direct;                       // 1: the producer stage stored the other segments' rows into peer_push itself;
                                     // 2: it also reduced the own segment in its epilogue (the consumer only forwards)
+  int fast_rows;                    // a segment of the partial result spans less than 4 GiB: 32-bit offsets inside it
   int ring;                         // ring ReduceScatter: peer_recv[q] = the next rank's running sum of segment q,
                                     // peer_push[q] = the previous rank's landing zone for this rank's running sum of it
   unsigned epoch;
@@ -121,23 +122,53 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
 // partial[g,:], and with direct push row g of segment q to peer_push[q][g - q*seg_rows,:]; else all rows to partial.
 // WT: the rows are stored written-through to device scope, so that the tile's notification can follow a plain wait for
 // the stores (TileNotify); else ordinary stores, and the notification needs a release fence at device scope.
-template <bool WT>
+//
+// The destination depends on the row's segment.  One store instruction of the tile's epilogue covers a few consecutive
+// rows, and the functor remembers the segment [seg_lo, seg_hi) of the last group's first row with the base address of its
+// destination: a group that lies in that segment is stored as (scalar base) + (32-bit lane offset) with no per-lane
+// segment arithmetic; only lanes of a group that straddles a segment boundary take the per-lane path.
+// FAST = false: always the per-lane path (for a tile shape that has no register left for the remembered segment).
+template <bool WT, bool FAST = true>
 struct PushRowsT {
   static constexpr bool SCALED = false, GATED = false;
   const RsSide* rs;
   int row_lo, col_lo;
+  int seg_lo = 0, seg_hi = 0;       // global rows of the remembered segment (empty: nothing remembered yet)
+  const bf16_t* seg_base = nullptr; // address of row seg_lo, column col_lo, of that segment's destination
   __device__ __forceinline__ bf16_t* row(int r, float& scale) const {
     const int g = row_lo + r;
     const int dest = g / rs->seg_rows;
     if (!rs->direct || dest == rs->rank) return rs->partial + (long)g * rs->N + col_lo;
     return rs->peer_push[dest] + (long)(g - dest * rs->seg_rows) * rs->N + col_lo;
   }
-  // 8 values of tile row r at tile column col, written through to device scope (the tile's notification follows a plain
-  // wait for these stores, see TileNotify).  Mode 2, own segment: besides the bf16 partial, out = bf16(sum over
-  // ranks in rank order, fp32) with the R-1 peer values of the same place loaded together (the caller has done the
-  // peer_tile_wait): the same arithmetic as the consumer's sum, so both paths give identical bits.
+  // r0 = first row of the next instruction's group of rows; every lane calls this, in uniform control flow
+  __device__ __forceinline__ void group(int r0) {
+    if (!FAST || rs->direct == 2 || !rs->fast_rows) return;
+    const int g0 = __builtin_amdgcn_readfirstlane(row_lo + r0);
+    if (g0 < seg_lo || g0 >= seg_hi) {   // uniform: a new segment starts (once or twice per tile)
+      const int dest = __builtin_amdgcn_readfirstlane(g0 / rs->seg_rows);
+      seg_lo = dest * rs->seg_rows;
+      seg_hi = seg_lo + rs->seg_rows;
+      const bf16_t* b = (!rs->direct || dest == rs->rank) ? rs->partial + (long)seg_lo * rs->N + col_lo : rs->peer_push[dest] + col_lo;
+      seg_base = (const bf16_t*)uniform64((unsigned long long)b);
+    }
+  }
+  // 8 values of tile row r at tile column col
   __device__ __forceinline__ void store(int r, int col, u32x4 v) const {
     const int g = row_lo + r;
+    if (FAST && rs->direct != 2 && rs->fast_rows) {
+      if (g < seg_hi) {
+        const unsigned off = ((unsigned)(g - seg_lo) * (unsigned)rs->N + (unsigned)col) * 2u;
+        if constexpr (WT) store16_device_scope(seg_base, off, v); else *(u32x4*)((char*)seg_base + off) = v;
+        return;
+      }
+    }
+    store_lane(g, col, v);
+  }
+  // Per-lane path.  Mode 2, own segment: besides the bf16 partial, out = bf16(sum over ranks in rank order, fp32) with
+  // the R-1 peer values of the same place loaded together (the caller has done the peer_tile_wait): the same arithmetic
+  // as the consumer's sum, so both paths give identical bits.
+  __device__ __forceinline__ void store_lane(int g, int col, u32x4 v) const {
     const int dest = g / rs->seg_rows;
     if (!rs->direct || dest == rs->rank) {
       put(rs->partial + (long)g * rs->N + col_lo + col, v);
