@@ -114,8 +114,9 @@ __device__ __forceinline__ void produce_tile(const AgProducer& p, int i, int tid
     bf16_t* d = p.gathered + (long)row_lo * p.ld + (long)tn * p.Tn_p;
     copy_tile<DEPTH>(s, p.ld, d, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
   }
-  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
-  if (wave == 0) wave_tile_notify(p.flags + (p.k_chunks > 1 ? channel * p.k_chunks + tn : channel));
+  wait_all_vmem();  // this wave's written-through stores are complete ...
+  __syncthreads();  // ... and so are every other wave's: the tile is where every die sees it
+  if (wave == 0) lane0_add(p.flags + (p.k_chunks > 1 ? channel * p.k_chunks + tn : channel), 1u);
 }
 
 // Push mode (paper: "Data Primitives", push mode): ticket j of the push range is producer tile j % (tiles per shard) of the local shard,
@@ -130,9 +131,10 @@ __device__ __forceinline__ void push_tile(const AgProducer& p, int j, int tid, i
   const int tm = t / p.n_ptn, tn = t - tm * p.n_ptn;
   const long off = (long)tm * p.Tm_p * p.ld + (long)tn * p.Tn_p;
   copy_tile<DEPTH>(p.shards[p.rank] + off, p.ld, p.peer_slots[q] + off, p.ld, p.Tm_p, p.Tn_p, tid, nthreads);
-  __syncthreads();  // every lane's stores have been acknowledged (waitcnt precedes the barrier)
+  wait_all_vmem();
+  __syncthreads();  // every wave's written-through stores are complete
   const int cpr = p.rows_per_rank / p.rows_per_channel;
-  if (wave == 0) wave_tile_notify(p.pushed + q * cpr + (tm * p.Tm_p) / p.rows_per_channel);
+  if (wave == 0) lane0_add(p.pushed + q * cpr + (tm * p.Tm_p) / p.rows_per_channel, 1u);
 }
 
 // A claimed ticket of either kind.

@@ -122,11 +122,13 @@ __device__ __forceinline__ void wave_tile_wait(const unsigned* flag, unsigned ta
 // visible to every die, so a producer that stores its tile this way can notify after a plain wait for its own stores,
 // without the L2 write-back a release fence at device scope performs.
 __device__ __forceinline__ void store16_device_scope(void* p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  // the wait states behind it: a vector instruction may not overwrite the data registers of a store of more than 8 bytes
+  // right after it, and the compiler does not look inside this statement
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 // ... with the address as a scalar base (the same for every lane) plus a 32-bit lane offset
 __device__ __forceinline__ void store16_device_scope(const void* base, unsigned lane_off, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, %2 sc1" ::"v"(lane_off), "v"(v), "s"(base) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, %2 sc1\n\ts_nop 1" ::"v"(lane_off), "v"(v), "s"(base) : "memory");
 }
 
 // ---------------------------------------------------------------------------------------
@@ -206,6 +208,15 @@ __device__ __forceinline__ void lane0_add(unsigned* ptr, unsigned v) {
 __device__ __forceinline__ void wave_tile_notify(unsigned* flag, unsigned inc = 1u) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   lane0_add(flag, inc);
+}
+
+// The tile movers below store written-through to device scope (sc1), so their data is where every die sees it as soon
+// as the storing wave's memory counter says the stores are complete: a mover's notification is then
+//   every wave: wait_all_vmem();  workgroup barrier;  one wave or lane: a relaxed add on the flag
+// with no release fence, i.e. without the write-back of the die's L2 that such a fence performs (and waits for).
+__device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void notify_relaxed(unsigned* flag, unsigned inc = 1u) {
+  __hip_atomic_fetch_add(flag, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // A 64-bit value every lane holds alike, as a wave-uniform value for the compiler too.
@@ -389,11 +400,11 @@ __device__ __forceinline__ void copy_tile(const bf16_t* __restrict__ src, long s
       if (c >= cpr) { c -= cpr; r++; }
     }
 #pragma unroll
-    for (int u = 0; u < 4; u++) *(u32x4*)(db + doff[u]) = v[u];
+    for (int u = 0; u < 4; u++) store16_device_scope(db + doff[u], v[u]);
   }
   for (; i < total; i += nthreads) {
-    *(u32x4*)(db + ((unsigned)r * dld + (unsigned)c * 16u)) =
-        __builtin_nontemporal_load((const u32x4*)(sb + ((unsigned)r * sld + (unsigned)c * 16u)));
+    store16_device_scope(db + ((unsigned)r * dld + (unsigned)c * 16u),
+                         __builtin_nontemporal_load((const u32x4*)(sb + ((unsigned)r * sld + (unsigned)c * 16u))));
     r += dr; c += dc;
     if (c >= cpr) { c -= cpr; r++; }
   }
@@ -489,7 +500,7 @@ __device__ __forceinline__ void sum_tile(SrcFn src, int n_src, bf16_t* dst, long
     const unsigned so = (unsigned)r * sld + (unsigned)c * 16u;
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int q = 0; q < n_src; q++) acc_bf16x8(s, __builtin_nontemporal_load((const u32x4*)((const char*)src(q) + so)));
-    *(u32x4*)(db + ((unsigned)r * dld + (unsigned)c * 16u)) = pack_bf16x8(s);
+    store16_device_scope(db + ((unsigned)r * dld + (unsigned)c * 16u), pack_bf16x8(s));
     r += dr; c += dc;
     if (c >= cpr) { c -= cpr; r++; }
   }

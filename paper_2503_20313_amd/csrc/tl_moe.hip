@@ -367,9 +367,9 @@ __device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int
     bf16_t* dst = (!p.rs.direct || dest == p.rs.rank) ? p.rs.partial + (long)t_lo * p.H + col_lo
                                                       : p.rs.peer_push[dest] + (long)(t_lo - dest * p.rs.seg_rows) * p.H + col_lo;
     sum_tile<2, 2>([&](int j) { return src0 + (long)j * p.H; }, p.topk, dst, (long)p.topk * p.H, p.H, p.Tt, cols, tid, nthreads);
-    __syncthreads();
+    wait_all_vmem();
+    __syncthreads();   // every wave's written-through stores are complete: relaxed adds announce the tile
     if (tid == 0) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // one release, then relaxed adds
       __hip_atomic_fetch_add(p.rs.ready + tb * p.rs.ncn + bn, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (producer_notifies_peer(p.rs, t_lo, p.Tt, col_lo, cols))   // final where it is: the owner hears of it at once
         __hip_atomic_fetch_add(p.rs.pushed + dest * p.rs.tiles_per_seg + (tb - dest * (p.rs.seg_rows / p.Tt)) * p.rs.ncn + bn, 1u,

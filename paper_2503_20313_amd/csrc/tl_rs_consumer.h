@@ -81,8 +81,9 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
         sum_tile<2, 2>([&](int j) { return j == 0 ? own : inc; }, 2, dst, p.N, p.N, rows, cols, tid, nthreads);
       }
       if (dest != p.rank) {
-        __syncthreads();
-        if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);                         // peer_tile_notify
+        wait_all_vmem();
+        __syncthreads();   // every wave's written-through stores are complete
+        if (tid == 0) notify_relaxed(p.pushed + dest * p.tiles_per_seg + local);                      // peer_tile_notify
       }
       continue;
     }
@@ -111,8 +112,9 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
       // tile_push_data to the owner's landing zone (unless the producer stage has put the rows there itself), then
       // peer_tile_notify
       if (!p.direct) copy_tile(mine, p.N, p.peer_push[dest] + (long)seg_row * p.N + col_lo, p.N, rows, cols, tid, nthreads);
-      __syncthreads();
-      if (tid == 0) tile_notify(p.pushed + dest * p.tiles_per_seg + local);
+      wait_all_vmem();
+      __syncthreads();   // every wave's written-through stores are complete (with direct push: the producer's already were)
+      if (tid == 0) notify_relaxed(p.pushed + dest * p.tiles_per_seg + local);
     }
   }
 }
