@@ -311,7 +311,8 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_ag_gather_gemm_kernel(const
 //   stage B (top-k reduce tiles): waits for Tt*topk rows, partial[t,:] = sum_j scatter[t*topk+j,:], notifies the RS tile
 //   stage C (RS tiles): the shared ReduceScatter consumer on `partial`
 // ======================================================================================
-struct ScatterRows {
+template <bool WT>
+struct ScatterRowsT {
   static constexpr bool SCALED = true, GATED = false;
   bf16_t* scatter;        // [T*topk, H] at the tile's first column
   long ld;
@@ -323,8 +324,13 @@ struct ScatterRows {
     return scatter + (long)rid * ld;
   }
   __device__ __forceinline__ void group(int /*r0*/) const {}
-  __device__ __forceinline__ void store(int r, int col, u32x4 v) const { *(u32x4*)(scatter + (long)rows[r] * ld + col) = v; }
+  // WT: written through to device scope, so that the tile's notification (RowsNotify) can follow a plain wait for these
+  // stores; else ordinary stores, and the notification needs a release fence at device scope
+  __device__ __forceinline__ void store(int r, int col, u32x4 v) const {
+    if constexpr (WT) store16_device_scope(scatter + (long)rows[r] * ld + col, v); else *(u32x4*)(scatter + (long)rows[r] * ld + col) = v;
+  }
 };
+typedef ScatterRowsT<true> ScatterRows;
 
 struct MoeP2Params {
   const bf16_t* x2;         // [T*topk, I] sorted row order
@@ -378,12 +384,38 @@ __device__ void topk_reduce(const MoeP2Params& p, int wg, int n_wg, int tid, int
   }
 }
 
+// producer_tile_notify of one finished stage-A tile, with counts: the tile's rows are token-ascending, so every token
+// block receives one run of them, and the first row of a run adds the run's length to the counter of (token block,
+// column block).  Runs are found inside each wave of 64 rows with one ballot (a run that crosses a wave boundary is
+// announced in two parts).  The tile's rows were stored written-through to device scope, so nothing but "every wave has
+// seen its stores complete, and a workgroup barrier since" has to precede these relaxed adds: gemm_tile's hook provides
+// that inside the NEXT tile's prologue, where the wait hides behind the latency of the first loads.
+struct RowsNotify {
+  const int* sorted_rows;   // sorted_row + f_lo of the tile
+  unsigned* counters;       // rows_ready + column block
+  int have, rows, topk, Tt, nbn;
+  __device__ __forceinline__ bool pending() const { return have != 0; }
+  __device__ __forceinline__ void run() const {
+    const int r = threadIdx.x, lane = r & 63;
+    const bool valid = r < rows;
+    const int tb = valid ? (sorted_rows[r] / topk) / Tt : -1;
+    const int prev = __shfl_up(tb, 1);
+    const bool start = valid && (lane == 0 || prev != tb);
+    const unsigned long long starts = __builtin_amdgcn_ballot_w64(start), valids = __builtin_amdgcn_ballot_w64(valid);
+    if (start) {
+      const unsigned long long later = lane == 63 ? 0ull : starts & ~((2ull << lane) - 1ull);
+      const int end = later ? __builtin_ctzll(later) : __builtin_popcountll(valids);   // valid lanes are the low ones
+      __hip_atomic_fetch_add(counters + (long)tb * nbn, (unsigned)(end - lane), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+};
+
 // A row tile of at most 64 rows in the small tile shape with the deeper ring (see part 1).  Kept out of line: inlined
 // beside the 256x256 loop it would raise the kernel's register count above what leaves room for the reduce kernel's
 // waves on the same SIMDs.
 __device__ __attribute__((noinline)) void moe_small_scatter_tile(const bf16_t* a, long lda, const bf16_t* b, long ldb, ScatterRows out, int rows,
-                                                                 int cols, int K, char* smem) {
-  gemm_tile<Cfg64x256>(a, lda, nullptr, 1, b, ldb, out, rows, cols, K, smem);
+                                                                 int cols, int K, char* smem, RowsNotify pend) {
+  gemm_tile<Cfg64x256>(a, lda, nullptr, 1, b, ldb, out, rows, cols, K, smem, NoKWait{}, pend);
 }
 
 template <class Cfg>
@@ -409,6 +441,8 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
   sc.first_block = 0;
   sc.swizzle = p.swizzle;
   sc.group_m = 1;
+  constexpr bool DEFER = Cfg::BN != 224;
+  int have = 0, p_f_lo = 0, p_bn = 0, p_rows = 0;   // the previous tile of this workgroup awaits its notification
   for (int pos = w; pos < sc.n_tiles; pos += sc.G) {
     // groups of column blocks slowest: those columns of every token are complete early
     int bm, bn;
@@ -419,34 +453,30 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
     const int rows = f_hi - f_lo, cols = min(Cfg::BN, p.H - col_lo);
     bool small = false;
     if constexpr (Cfg::BM == 256 && Cfg::BN == 256) small = rows <= Cfg64x256::BM;
+    // producer_tile_notify of the PREVIOUS tile happens inside this tile's prologue (RowsNotify); the 224-wide tile has
+    // no register left for the state that carries from tile to tile and notifies right after its own stores
+    const RowsNotify pend{p.sorted_row + p_f_lo, p.rows_ready + p_bn, DEFER ? have : 0, p_rows, p.topk, p.Tt, p.nbn};
     if (small)
       moe_small_scatter_tile(p.x2 + (long)f_lo * p.I, p.I, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
-                             ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
+                             ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem, pend);
+    else if constexpr (DEFER)
+      gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
+                     ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem, NoKWait{}, pend);
     else
       gemm_tile<Cfg>(p.x2 + (long)f_lo * p.I, p.I, nullptr, 1, p.w2 + (long)e * p.I * p.H + col_lo, p.H,
-                     ScatterRows{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
-    if (p.do_notify) {
-      // producer_tile_notify with a count: the rows of this tile are token-ascending, so each token block receives
-      // one run of them; the first row of a run adds the run's length to the block's counter.  The token block of
-      // every row goes through LDS (free once the tile is stored) so that finding the runs costs no global loads;
-      // one wave issues a single device-scope release for the whole tile, then relaxed adds.
-      __syncthreads();  // every wave's stores of the tile have completed
-      int* s_tb = (int*)smem;
-      for (int r = tid; r < rows; r += Cfg::NTHREADS) s_tb[r] = (p.sorted_row[f_lo + r] / p.topk) / p.Tt;
-      __syncthreads();
-      if (__builtin_amdgcn_readfirstlane(tid >> 6) == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        for (int r = tid; r < rows; r += 64) {
-          int tb = s_tb[r];
-          if (r == 0 || s_tb[r - 1] != tb) {
-            int n = 1;
-            while (r + n < rows && s_tb[r + n] == tb) n++;
-            __hip_atomic_fetch_add(p.rows_ready + tb * p.nbn + bn, (unsigned)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-        }
-      }
-      __syncthreads();  // the next tile's loads overwrite s_tb
+                     ScatterRowsT<false>{p.scatter + col_lo, p.H, p.sorted_row + f_lo, p.topk_w}, rows, cols, p.I, smem);
+    if constexpr (DEFER) {
+      if (p.do_notify) { have = 1; p_f_lo = f_lo; p_bn = bn; p_rows = rows; }
+    } else if (p.do_notify) {
+      __syncthreads();                                      // every wave's stores are complete ...
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // ... and written back to where every die sees them
+      RowsNotify{p.sorted_row + f_lo, p.rows_ready + bn, 1, rows, p.topk, p.Tt, p.nbn}.run();
     }
+  }
+  if (have) {   // the last tile: nothing follows that could hide the wait for its stores
+    wait_vmcnt<0>();
+    __syncthreads();
+    RowsNotify{p.sorted_row + p_f_lo, p.rows_ready + p_bn, 1, p_rows, p.topk, p.Tt, p.nbn}.run();
   }
 }
 
