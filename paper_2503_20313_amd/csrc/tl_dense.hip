@@ -250,7 +250,8 @@ int launch_peers_arrive(const RsSide& rs, hipStream_t s) {
 }
 
 __global__ void __launch_bounds__(256) rs_consumer_kernel(const RsSide p) {
-  rs_consumer(p, blockIdx.x, gridDim.x, threadIdx.x, 256);
+  __shared__ int s_item;
+  rs_consumer(p, blockIdx.x, gridDim.x, threadIdx.x, 256, &s_item);
 }
 
 // ======================================================================================
@@ -820,6 +821,7 @@ static int gemm_rs_impl(const char* name, bool ring, tl_ctx* ctx, const void* a,
         if (int e = launch_gemm_rs(r.variant, p, r.G, cs)) return e;
       if (p.rs.direct != 2)
         if (int e = peers_arrive(ms)) return e;
+      use_rs_queue(&p.rs, workspace, epoch);   // (the GEMM kernel above was given its parameters by value before this)
       hipLaunchKernelGGL(rs_consumer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.rs);
       TL_HIP(hipGetLastError());
       return TL_OK;

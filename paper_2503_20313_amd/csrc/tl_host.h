@@ -139,6 +139,11 @@ inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void
   p->arrived = flags + (size_t)p->ncm * p->ncn;
   p->pushed = p->arrived + (size_t)R * p->tiles_per_seg;
   p->ctl = make_ctl(ctx, workspace);
+  // own-segment reduce tiles are handed out in row slices of about 32 rows; no item queue unless the caller sets one up
+  p->slices = Tm_r >= 64 ? (Tm_r / 32 < 8 ? Tm_r / 32 : 8) : 1;
+  p->queue = nullptr;
+  p->queue_end = 0;
+  p->others_done = 0;
   // reduce tiles whose edges do not fall on 128-byte lines share cache lines with their neighbours
   bool aligned = N % 64 == 0 && Tn_r % 64 == 0 && aligned128(partial);
   for (int q = 0; q < R; q++)
@@ -147,6 +152,15 @@ inline void fill_rs_side(const tl_ctx* ctx, RsSide* p, void* partial, const void
 }
 
 int launch_peers_arrive(const RsSide& rs, hipStream_t s);
+
+// The reduce side as a kernel of its own takes its work items from a queue (word 1 of the workspace, which grows by the
+// items of every call: zeroed with the flags, one call at a time).  Call once p->ring is final.
+inline void use_rs_queue(RsSide* p, void* workspace, unsigned epoch) {
+  // with direct push a reduce tile of another segment that lies inside one producer tile is announced by its producer
+  p->others_done = (p->direct && !p->ring && p->do_wait && p->tile_m % p->Tm_r == 0 && p->tile_n % p->Tn_r == 0 && p->N % p->Tn_r == 0) ? 1 : 0;
+  p->queue = (unsigned*)workspace + 1;
+  p->queue_end = epoch * (unsigned)rs_item_count(*p);
+}
 
 inline int check_ctx(const tl_ctx* ctx) {
   if (!ctx) return fail(TL_ERR_INVALID_ARG, "context is null");

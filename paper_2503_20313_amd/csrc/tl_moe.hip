@@ -481,9 +481,12 @@ __global__ void __launch_bounds__(Cfg::NTHREADS) moe_gemm_scatter_kernel(const M
 }
 
 // stages B and C as a kernel of their own (side-kernel binding)
+// The top-k reduce workgroups join stage C when their own tiles are done: stage C hands its items out through a queue,
+// and what becomes ready last (the last column group, at the very end) then spreads over all of them.
 __global__ void __launch_bounds__(256) moe_reduce_kernel(const MoeP2Params p) {
+  __shared__ int s_item;
   if ((int)blockIdx.x < p.n_topk) topk_reduce(p, blockIdx.x, p.n_topk, threadIdx.x, 256);
-  else rs_consumer(p.rs, blockIdx.x - p.n_topk, p.n_rs, threadIdx.x, 256);
+  rs_consumer(p.rs, blockIdx.x, gridDim.x, threadIdx.x, 256, &s_item);
 }
 
 __global__ void __launch_bounds__(256) moe_ag_producer_kernel(const AgProducer p) {
@@ -775,6 +778,7 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
         if (int e = launch(r.G)) return e;
       if (int e = launch_peers_arrive(p.rs, ms)) return e;
       p.n_topk = n_topk; p.n_rs = n_rs;
+      use_rs_queue(&p.rs, workspace, epoch);   // (stage A above was given its parameters by value before this)
       hipLaunchKernelGGL(moe_reduce_kernel, dim3(n_topk + n_rs), dim3(256), 0, ms, p);
       TL_HIP(hipGetLastError());
       return TL_OK;

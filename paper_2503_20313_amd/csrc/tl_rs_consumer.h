@@ -25,6 +25,12 @@ struct RsSide {
   unsigned* ready;                  // [ncm*ncn]
   unsigned* arrived;                // [R*tiles_per_seg]
   unsigned* pushed;                 // [R*tiles_per_seg]
+  int slices;                       // >= 1: a reduce tile of the own segment is handed out in this many row slices
+  int others_done;                  // 1: every reduce tile of another segment is announced by its producer (direct push, each
+                                    // reduce tile inside one producer tile): the reduce side has items of the own segment only
+  unsigned* queue;                  // head of the work-item queue of the reduce side (word 1 of the workspace: it grows by the
+                                    // call's number of items), or null: items are dealt out by workgroup index
+  unsigned queue_end;               // epoch * items per call
   WaitCtl ctl;
 };
 
@@ -43,18 +49,81 @@ __device__ __forceinline__ bool producer_notifies_peer(const RsSide& p, int row_
 // peer's rows, sum in fp32 in rank order, store bf16.  Other segments: push to the owner's
 // landing zone and notify it.
 // ======================================================================================
-__device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthreads) {
+// Work items of the reduce side.  A reduce tile of the own segment is the heavy kind -- R sources of tile size read by
+// one workgroup, which is bound by the bytes it keeps in flight -- and needs no notification afterwards: each of its
+// p.slices row slices is an item, so that the tiles that become ready last (in MoE part 2: a whole column group at the
+// very end) spread over all workgroups of the reduce side.  Every tile of another segment is one item, unless its
+// producer announces it itself (others_done).  The items of the own segment come first if the visiting order starts with
+// it, else last; inside each kind the visiting order holds, which is the order in which the tiles become ready.  The ring
+// form has one item per tile in visiting order.
+__host__ __device__ inline int rs_item_count(const RsSide& p) {
+  const int n_rt = p.ncm * p.ncn, own = (p.seg_rows / p.Tm_r) * p.ncn;
+  if (p.ring) return n_rt;
+  return own * p.slices + (p.others_done ? 0 : n_rt - own);
+}
+
+// With a queue the items go to whoever asks next; workgroups that had other work first (stage B of MoE part 2) join when
+// they are done.  s_item: an int in LDS for handing the claimed item to the workgroup.
+__device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthreads, int* s_item = nullptr) {
   const int n_rt = p.ncm * p.ncn;
   const int cm_per_seg = p.seg_rows / p.Tm_r;
-  for (int i = wg; i < n_rt; i += n_wg) {
-    int cmi = i / p.ncn, cn = i - cmi * p.ncn;
-    int cm = cmi + p.rs_first_block;
-    if (cm >= p.ncm) cm -= p.ncm;
+  const int S = p.ring ? 1 : p.slices;
+  const int n_items = rs_item_count(p);
+  const int n_own = p.ring ? 0 : cm_per_seg * p.ncn * S, n_oth = n_items - n_own;
+  const int own_lo = p.rank * cm_per_seg;                                   // first row block of the own segment
+  int own_rel = own_lo - p.rs_first_block;                                  // ... and its place in the visiting order
+  if (own_rel < 0) own_rel += p.ncm;
+  const bool own_first = own_rel == 0;
+  const bool queued = p.queue != nullptr && s_item != nullptr;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (int it = wg;; it += n_wg) {
+    if (queued) {
+      if (wave == 0) {
+        const unsigned t = lane0_fetch_add(p.queue, 1u);
+        const unsigned idx = t - (p.queue_end - (unsigned)n_items);
+        if (idx >= (unsigned)n_items) lane0_add(p.queue, 0xffffffffu);   // past the end (or not this epoch's counter): give it back
+        *s_item = idx < (unsigned)n_items ? (int)idx : -1;
+      }
+      __syncthreads();
+      it = __builtin_amdgcn_readfirstlane(*s_item);
+      __syncthreads();
+      if (it < 0) break;
+    } else if (it >= n_items) break;
+    int cm, cn, slice = 0;
+    if (p.ring) {
+      const int cmi = it / p.ncn;
+      cn = it - cmi * p.ncn;
+      cm = cmi + p.rs_first_block;
+      if (cm >= p.ncm) cm -= p.ncm;
+    } else {
+      const bool own = own_first ? it < n_own : it >= n_oth;
+      if (own) {
+        const int j = own_first ? it : it - n_oth;
+        const int tl_ = j / S;
+        slice = j - tl_ * S;
+        cm = own_lo + tl_ / p.ncn;
+        cn = tl_ % p.ncn;
+      } else {
+        const int j = own_first ? it - n_own : it;
+        const int k = j / p.ncn;                       // k-th row block of another segment in visiting order
+        cn = j - k * p.ncn;
+        cm = p.rs_first_block + (k < own_rel ? k : k + cm_per_seg);
+        if (cm >= p.ncm) cm -= p.ncm;
+      }
+    }
     const int t = cm * p.ncn + cn;
-    const int row_lo = cm * p.Tm_r, col_lo = cn * p.Tn_r;
-    const int rows = min(p.Tm_r, p.M - row_lo), cols = min(p.Tn_r, p.N - col_lo);
-    const int dest = row_lo / p.seg_rows;                       // owner of these rows in the scattered output
+    const int tile_row_lo = cm * p.Tm_r, col_lo = cn * p.Tn_r;
+    const int tile_rows = min(p.Tm_r, p.M - tile_row_lo), cols = min(p.Tn_r, p.N - col_lo);
+    const int dest = tile_row_lo / p.seg_rows;                  // owner of these rows in the scattered output
     const int local = (cm - dest * cm_per_seg) * p.ncn + cn;    // reduce-tile index inside its segment
+    // the rows of this item: a slice of an own-segment tile, else the whole tile
+    int row_lo = tile_row_lo, rows = tile_rows;
+    if (S > 1 && dest == p.rank) {
+      const int per = (tile_rows + S - 1) / S;
+      row_lo = tile_row_lo + slice * per;
+      rows = min(per, tile_row_lo + tile_rows - row_lo);
+      if (rows <= 0) continue;
+    }
     const int seg_row = row_lo - dest * p.seg_rows;
     if (p.ring) {
       // Ring order (paper: kernel design, GEMM + ring ReduceScatter): the running sum of segment q travels from rank
@@ -64,7 +133,7 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
       const int start = p.rank + 1 == p.R ? 0 : p.rank + 1;
       if (tid == 0) {
         if (p.do_wait) {
-          unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
+          unsigned n_m = (unsigned)((tile_row_lo + tile_rows - 1) / p.tile_m - tile_row_lo / p.tile_m + 1);
           unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
           tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);                                    // consumer_tile_wait
         }
@@ -88,19 +157,18 @@ __device__ void rs_consumer(const RsSide& p, int wg, int n_wg, int tid, int nthr
       continue;
     }
     if (p.direct == 2 && dest == p.rank) continue;  // reduced by the producer stage's epilogue
-    if (producer_notifies_peer(p, row_lo, rows, col_lo, cols)) continue;
+    if (producer_notifies_peer(p, tile_row_lo, tile_rows, col_lo, cols)) continue;
+    // the waits of one item side by side, one lane each: lane 0 consumer_tile_wait (all GEMM tiles that overlap this
+    // reduce tile have stored their part), lane 1 + q peer_tile_wait for peer q's contribution to a tile of the own segment
     if (tid == 0) {
       if (p.do_wait) {
-        // consumer_tile_wait: all GEMM tiles that overlap this reduce tile have stored their part
-        unsigned n_m = (unsigned)((row_lo + rows - 1) / p.tile_m - row_lo / p.tile_m + 1);
+        unsigned n_m = (unsigned)((tile_row_lo + tile_rows - 1) / p.tile_m - tile_row_lo / p.tile_m + 1);
         unsigned n_n = (unsigned)((col_lo + cols - 1) / p.tile_n - col_lo / p.tile_n + 1);
         tile_wait(p.ready + t, p.epoch * n_m * n_n, p.ctl, t);
       }
-      if (dest == p.rank) {
-        // peer_tile_wait: every peer's contribution to this tile has landed
-        for (int q = 0; q < p.R; q++)
-          if (q != p.rank) tile_wait(p.arrived + q * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + q * p.tiles_per_seg + local);
-      }
+    } else if (tid <= p.R && dest == p.rank) {
+      const int q = tid - 1;
+      if (q != p.rank) tile_wait(p.arrived + q * p.tiles_per_seg + local, p.epoch, p.ctl, n_rt + q * p.tiles_per_seg + local);
     }
     __syncthreads();
     const bf16_t* mine = p.partial + (long)row_lo * p.N + col_lo;
