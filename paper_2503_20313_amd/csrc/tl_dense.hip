@@ -370,7 +370,8 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, b
   }
   // in-kernel communication workgroups each take a compute unit's worth of LDS and registers; as a kernel of
   // their own they are small and share compute units with the GEMM, so many more of them pay off
-  int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : 128);
+  // (the reduce side as a kernel of its own: one workgroup per compute unit, each is bound by the bytes it keeps in flight)
+  int n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : (op == TL_OP_GEMM_RS ? 256 : 128));
   r->n_comm = (c.comm_mode == TL_COMM_NONE) ? 0 : n_comm;
   // ---- communication tiles
   if (op == TL_OP_AG_GEMM) {
