@@ -364,7 +364,7 @@ def shape_table(torch, tl, dev, timed, cs, ms, mode, steps, warmup, over_ag=None
             tl.tl_ag_gemm(st["ctx"], shards, st["g"], b, c, S, N, H, st["flags"], st["epoch"], st["wsp"], st["ws"], cs, ms)
         row = {"ag_gemm": dict(run3(ag_make, ag_call, 2.0 * S * N * H), M=S, N=N, K=H)}
         del shards, full, b, c
-        K = N - N % 64
+        K = N                                            # the real K of the share (a multiple of 8; the tile zero-fills the tail of its last K step)
         a, b, partial = rnd((S, K)), rnd((K, H), 0.02), zeros((S, H))
         recv = [0] + [rnd((S // R, H), K ** 0.5 * 0.02) for _ in range(1, R)]
         push = [0] + [zeros((S // R, H)) for _ in range(1, R)]

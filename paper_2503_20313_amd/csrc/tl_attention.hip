@@ -52,6 +52,13 @@ __device__ __forceinline__ void both_halves(float v, float& lo, float& hi) {
 // v_max_f32 on the raw registers; fmaxf() on them would first canonicalise each operand with an instruction of its own.
 __device__ __forceinline__ float raw_max(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
 
+// max(m, a, b) in one instruction on raw matrix-instruction results (finite or -inf)
+__device__ __forceinline__ float raw_max3(float m, float a, float b) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(a), "v"(b));
+  return r;
+}
+
 __device__ __forceinline__ float halves_max(float v) {
   float lo, hi;
   both_halves(v, lo, hi);
@@ -108,26 +115,30 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   constexpr int LPW = 16 / NW;                                    // loads per wave and tile
   const int wg_q_hi = min(q0 + kBQ, p.S_loc) - 1;                 // last valid local query row of the workgroup
   const int n_kv = p.causal ? (g0 + wg_q_hi) / kBKV + 1 : (p.S + kBKV - 1) / kBKV;
+  // The global address of a load is a scalar base (the block's first row of this head, the same for every lane) plus a
+  // lane offset that is fixed for the whole kernel: no vector arithmetic per block.  Every block is whole (the rows per
+  // channel, and so S, are multiples of the block).
   const char* kbase = (const char*)(p.kprod.gathered + (long)head * kD);
   const char* vbase = (const char*)(p.vprod.gathered + (long)head * kD);
-  int ld_row[LPW], ld_kc[LPW], ld_vc[LPW];
+  unsigned ld_koff[LPW], ld_voff[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; i++) {
     int j = wave + i * NW;
     int row = j * 4 + (lane >> 4), pc = lane & 15;
-    ld_row[i] = row;
-    ld_kc[i] = (pc ^ (row & 15)) * 16;
-    ld_vc[i] = (pc ^ ((row & 3) << 2)) * 16;
+    ld_koff[i] = (unsigned)row * (unsigned)(ldq * 2) + (unsigned)((pc ^ (row & 15)) * 16);
+    ld_voff[i] = (unsigned)row * (unsigned)(ldq * 2) + (unsigned)((pc ^ ((row & 3) << 2)) * 16);
   }
+  const unsigned smem_u = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem);
   auto issue_block = [&](int blk, int stage) __attribute__((always_inline)) {
-    char* sk = smem + stage * 2 * kKvTileBytes;
-    char* sv = sk + kKvTileBytes;
+    const long blk_off = (long)__builtin_amdgcn_readfirstlane(blk) * (kBKV * ldq * 2);
+    const char* kb = (const char*)uniform64((unsigned long long)(kbase + blk_off));
+    const char* vb = (const char*)uniform64((unsigned long long)(vbase + blk_off));
+    const unsigned sk = smem_u + (unsigned)__builtin_amdgcn_readfirstlane(stage) * (2 * kKvTileBytes), sv = sk + kKvTileBytes;
 #pragma unroll
     for (int i = 0; i < LPW; i++) {
-      int j = wave + i * NW;
-      long row = min(blk * kBKV + ld_row[i], p.S - 1);
-      lds_load16(kbase + row * ldq * 2 + ld_kc[i], sk + j * 1024);
-      lds_load16(vbase + row * ldq * 2 + ld_vc[i], sv + j * 1024);
+      const int j = wave + i * NW;
+      lds_load16_sbase(kb, ld_koff[i], sk + j * 1024);
+      lds_load16_sbase(vb, ld_voff[i], sv + j * 1024);
     }
   };
   // consumer_tile_wait on the K and V flags of the channel block `blk` starts, if it starts one
@@ -185,7 +196,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   auto block_max = [&](const floatx16 (&sc)[2]) __attribute__((always_inline)) -> float {
     float m = -1e30f;
 #pragma unroll
-    for (int e = 0; e < 16; e += 2) m = fmaxf(m, fmaxf(raw_max(sc[0][e], sc[1][e]), raw_max(sc[0][e + 1], sc[1][e + 1])));
+    for (int e = 0; e < 16; e++) m = raw_max3(m, sc[0][e], sc[1][e]);
     return halves_max(m);
   };
   float m_blk[QT];   // block_max of the block the next iteration works on, computed one iteration early
@@ -282,7 +293,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
           for (int uu = 0; uu < QT; uu++) {
             float m = q == 0 ? -1e30f : m_part[uu];
 #pragma unroll
-            for (int e = q * 4; e < q * 4 + 4; e += 2) m = fmaxf(m, fmaxf(raw_max(n[uu][0][e], n[uu][1][e]), raw_max(n[uu][0][e + 1], n[uu][1][e + 1])));
+            for (int e = q * 4; e < q * 4 + 4; e++) m = raw_max3(m, n[uu][0][e], n[uu][1][e]);
             m_part[uu] = m;
           }
         }
