@@ -478,6 +478,9 @@ def main():
                     help="GEMM+RS: store every partial row locally and let the communication side copy the other ranks' rows "
                          "(default: the GEMM epilogue stores them straight into the peers' landing zones)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="launch nothing but fused steps (clock settling included) and report their times: the run to put under "
+                         "rocprofv3 --kernel-trace --stats, whose per-kernel averages then are those of the fused launches alone")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (MoE halves, sequence-parallel attention); they are outside the timed step")
     ap.add_argument("--shape-table", action="store_true",
@@ -622,7 +625,8 @@ def main():
     ops_ = {}
     # the chip needs some hundred milliseconds of load to settle its clocks: without this the first per-operator
     # timings below (not the timed steps, which come last) read up to 15 % slow
-    pre = [Op(tl.TL_OP_AG_GEMM, [M, N, K], tl.TL_COMM_NONE), Op(tl.TL_OP_GEMM_RS, [M3, N3, K3], tl.TL_COMM_NONE)]
+    pre_mode = mode if args.fused_only else tl.TL_COMM_NONE
+    pre = [Op(tl.TL_OP_AG_GEMM, [M, N, K], pre_mode), Op(tl.TL_OP_GEMM_RS, [M3, N3, K3], pre_mode)]
     gathered.copy_(torch.cat(shards))
     for _ in range(300):
         pre[0]()
@@ -631,7 +635,18 @@ def main():
     for o in pre:
         tl.tl_ctx_destroy(o.ctx)
     for name, op, dims in (("ag_gemm", tl.TL_OP_AG_GEMM, [M, N, K]), ("gemm_rs", tl.TL_OP_GEMM_RS, [M3, N3, K3])):
-        fused, alone, comm = Op(op, dims, mode), Op(op, dims, tl.TL_COMM_NONE), Op(op, dims, mode, comm_alone=1)
+        fused = Op(op, dims, mode)
+        if args.fused_only:
+            t_fused, _ = timed(fused, args.steps, args.warmup)
+            tl.tl_check_status(fused.ctx, fused.wsp)
+            cyc, ticks = tl.tl_read_clocks(fused.ctx, fused.wsp)
+            res[name] = {"fused_ms": round(t_fused, 4), "tflops": round((flop2 if op == tl.TL_OP_AG_GEMM else flop3) / t_fused / 1e9, 1),
+                         "shader_mhz_fused": round(cyc / max(ticks, 1) * 100.0, 0), "shader_mhz_compute_alone": None,
+                         "tile": f"{fused.info['tile_m']}x{fused.info['tile_n']}", "compute_workgroups": fused.info["compute_workgroups"],
+                         "comm_workgroups": fused.info["comm_workgroups"]}
+            ops_[name] = fused
+            continue
+        alone, comm = Op(op, dims, tl.TL_COMM_NONE), Op(op, dims, mode, comm_alone=1)
         if op == tl.TL_OP_AG_GEMM:
             fused()                      # leaves the gathered buffer complete for the compute-alone variant
             torch.cuda.synchronize()
@@ -673,6 +688,15 @@ def main():
 
     # ---------------- what the matrix cores alone sustain on this data: MFMA-only register loop, operands drawn like the
     # GEMM's (activations N(0,1), weights N(0,0.02)); the clock the chip grants depends on the operand values
+    if args.fused_only:
+        dom_ms = 0.5 * (res["ag_gemm"]["fused_ms"] + res["gemm_rs"]["fused_ms"])
+        print(json.dumps({"metric": "TFLOP/s + overlap efficiency, AG+GEMM & GEMM+RS at TP=8 share, 1 MI355X", "value": round(tflops, 1),
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+                          "higher_is_better": True, "dtype": "bf16", "data": "synthetic", "fused_only": True, "ops": res,
+                          "roofline": {"bound": "mfma", "achieved": round(flop2 / dom_ms / 1e9, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": round(flop2 / dom_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                                       "kernel_ms": round(dom_ms, 4)}}))
+        return
     n_thr = torch.cuda.get_device_properties(0).multi_processor_count * 512
     opnd = torch.cat([torch.randn((n_thr, 32), device=dev, dtype=torch.float32), torch.randn((n_thr, 16), device=dev, dtype=torch.float32) * 0.02],
                      dim=1).to(torch.bfloat16).contiguous()

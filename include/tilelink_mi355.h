@@ -254,6 +254,10 @@ int tl_ag_gemm_push(tl_ctx* ctx, const void* const* a_shards /*host array of R d
  *   segment q: peer_push[q]).  A reduce tile of another segment that one GEMM tile fills alone is then announced to its
  *   owner by that GEMM tile (its pushed counter moves together with its ready counter); reduce tiles that several GEMM
  *   tiles share are announced by the reduce side once all of them have stored their part.
+ *   workspace  dev, tl_query_workspace bytes: word 0 = status word, word 1 = head of the reduce side's work queue when the
+ *              reduce side is a kernel of its own (TL_COMM_SIDE_KERNEL, TL_COMM_STREAM): it grows by the number of work
+ *              items per call, so the caller zeroes the workspace together with the flags (once, or when `epoch`
+ *              restarts at 1), keeps `epoch` counting call by call, and runs one call at a time per workspace.
  *   Requirements: R | M, reduce tile Tm_r | M/R and Tn_r | N, K % 8 == 0, N % 8 == 0.
  */
 int tl_gemm_rs(tl_ctx* ctx, const void* a, const void* b, void* partial, const void* const* peer_recv /*host array of dev*/,
@@ -346,6 +350,7 @@ int tl_moe_ag_gather_gemm_act_mul(tl_ctx* ctx, const void* const* x_shards /*hos
  *   flags dev unsigned[info[3] of tl_moe_query]: row counters | reduce-tile ready | peer arrived | pushed
  *   With tl_config.rs_direct_push stage B stores the token blocks of another rank's segment straight into peer_push[]
  *   (and those of the own segment into `partial`) and announces them to their owner itself; stage C reduces the own segment.
+ *   workspace as for tl_gemm_rs (word 1 = the work queue of stage C in TL_COMM_SIDE_KERNEL mode: zeroed with the flags).
  *   Requirements: those of tl_moe_route, H % tile_n == 0, tokens per reduce tile | T/R.  comm_mode: NONE (stage A only),
  *   WAVES or SIDE_KERNEL.
  */

@@ -483,7 +483,7 @@ using namespace tl;
 extern "C" {
 
 const char* tl_last_error(void) { return g_err; }
-const char* tl_version(void) { return "tilelink_mi355 0.1 (gfx950)"; }
+const char* tl_version(void) { return "tilelink_mi355 0.2 (gfx950)"; }
 
 static int check_config(const tl_config* cfg) {
   if (cfg->world_size < 1 || cfg->world_size > kMaxWorld) return fail(TL_ERR_INVALID_ARG, "world_size %d outside [1,%d]", cfg->world_size, kMaxWorld);
