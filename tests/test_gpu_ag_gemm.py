@@ -177,6 +177,18 @@ def test_arrival_order_and_paced_links(mode, order, kc):
         assert flags.tolist() == [2 * info["expected_per_channel"]] * (4 * 2 * info["k_chunks"])
 
 
+@pytest.mark.parametrize("mode,order", [("side", tl.TL_ORDER_OWN_FIRST), ("side", tl.TL_ORDER_ARRIVAL), ("waves", tl.TL_ORDER_ARRIVAL)])
+def test_late_producer_new_data_every_call(mode, order):
+    """The producer is late on purpose (10 GB/s per link: a 1 MiB shard takes 105 us, the GEMM tiles of the remote rows
+    are resident and waiting long before their rows arrive) and every call brings new shard contents into the same
+    buffers: a tile that read any byte of the gathered matrix before its channel's flag would see the previous call's
+    data and miss the oracle's result for this call's."""
+    w = wl.ag_gemm_inputs(2048, 456, 1024, 4, config_id=19)
+    hs, g, c, flags, info = run_ag_gemm(w, 1, 2, MODES[mode], epochs=3, tile_m=256, tile_n=256, tile_order=order, link_gbps=10, comm_workgroups=8)
+    check(w, hs, g, c, f"late producer, {mode}, order {order}")
+    assert flags.tolist() == [3 * info["expected_per_channel"]] * (4 * 2 * info["k_chunks"])
+
+
 def test_paced_links_take_the_time_of_the_link():
     """Producers alone, 8 ranks, shards of 4 MiB at 50 GB/s per link: the gather may not finish before 4 MiB / 50 GB/s
     = 84 us have passed (all links run side by side), and does not take several times that either (warm calls)."""
