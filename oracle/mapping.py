@@ -99,17 +99,29 @@ def logical_order(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, gro
     return order
 
 
-def xcd_positions(n_tiles: int, G: int):
+def xcd_positions(n_tiles: int, G: int, busy_first: bool = False):
     """position -> logical index.  Inside each full round of G positions the
     workgroups that share a die (w % 8) are given a contiguous run of G/8
     logical tiles, so tiles that run side by side on one die share operands.
     A ragged last round gets the same treatment if its length is a multiple of
-    8, else it is left in order.  With G not a multiple of 8 nothing moves."""
+    8, else it is left in order.  With G not a multiple of 8 nothing moves.
+
+    `busy_first` (tile order is a free choice of the design space; this one is
+    for consumers whose first tiles wait for data that arrives in logical
+    order): if the last round is a partial one of `tail` positions (a multiple
+    of 8, more than one round in all), the workgroups w < tail are the ones
+    with a tile more than the others, so in round 0 they take the logical
+    tiles [0, tail) -- the earliest data -- and the workgroups with a tile
+    less take [tail, G); both sets again as one contiguous run per die."""
     pos = []
+    tail = n_tiles % G
     for p in range(n_tiles):
         rnd, w = divmod(p, G)
         span = min(G, n_tiles - rnd * G)
-        if G % XCDS == 0 and span % XCDS == 0:
+        if busy_first and G % XCDS == 0 and rnd == 0 and n_tiles > G and tail and tail % XCDS == 0:
+            die, i, tb = w % XCDS, w // XCDS, tail // XCDS
+            pos.append(die * tb + i if i < tb else tail + die * ((G - tail) // XCDS) + (i - tb))
+        elif G % XCDS == 0 and span % XCDS == 0:
             per_die = span // XCDS
             pos.append(rnd * G + (w % XCDS) * per_die + w // XCDS)
         else:
@@ -117,20 +129,23 @@ def xcd_positions(n_tiles: int, G: int):
     return pos
 
 
-def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool, group_m: int = 1, arrival: bool = False):
+def tile_schedule(nbm: int, nbn: int, R: int, first_rank: int, rotate: bool, G: int, swizzle: bool, group_m: int = 1, arrival: bool = False,
+                  busy_first: bool = False):
     """Output-tile id at every schedule position."""
     logical = logical_order(nbm, nbn, R, first_rank, rotate, group_m, arrival)
     n = nbm * nbn
-    pos = xcd_positions(n, G) if swizzle else list(range(n))
+    pos = xcd_positions(n, G, busy_first) if swizzle else list(range(n))
     return [logical[pos[p]] for p in range(n)]
 
 
 def ag_gemm_schedule_records(M, N, K, R, C, rank, Tm_c, Tn_c, G, rotate=True, swizzle=True, group_m=1, arrival=False):
     """One 8-int record per schedule position:
-    (tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0)."""
+    (tile_id, bm, bn, row_lo, row_hi, chan_lo, chan_hi, 0).  The consumer of an
+    AllGather waits for rows that arrive in logical order, so its die swizzle
+    is the `busy_first` one."""
     nbm, nbn = ceil_div(M, Tm_c), ceil_div(N, Tn_c)
     recs = []
-    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle, group_m, arrival):
+    for t in tile_schedule(nbm, nbn, R, rank, rotate, G, swizzle, group_m, arrival, busy_first=True):
         bm, bn, lo, hi, clo, chi = consumer_tile(t, M, N, R, C, Tm_c, Tn_c)
         recs.append((t, bm, bn, lo, hi, clo, chi, 0))
     return recs

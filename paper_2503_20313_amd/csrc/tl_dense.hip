@@ -442,7 +442,7 @@ int resolve_dense(const tl_ctx* ctx, int op, int M, int N, int K, Resolved* r, b
   return TL_OK;
 }
 
-static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
+static Sched make_sched(const tl_ctx* ctx, const Resolved& r, int op) {
   Sched s;
   s.nbm = r.nbm;
   s.nbn = r.nbn;
@@ -452,6 +452,7 @@ static Sched make_sched(const tl_ctx* ctx, const Resolved& r) {
   s.swizzle = ctx->cfg.xcd_swizzle;
   s.group_m = r.group_m;
   s.arrival_bpr = r.arrival_bpr;
+  s.busy_first = op == TL_OP_AG_GEMM ? 1 : 0;   // the AllGather's consumer: its first tiles wait for rows that arrive in logical order
   return s;
 }
 
@@ -656,7 +657,7 @@ static int ag_gemm_impl(tl_ctx* ctx, const void* const* a_shards, void* a_gather
   p.c = (bf16_t*)c;
   p.M = M; p.N = N; p.K = K;
   p.act = act;
-  p.sched = make_sched(ctx, r);
+  p.sched = make_sched(ctx, r, TL_OP_AG_GEMM);
   hipStream_t cs = (hipStream_t)compute_stream, ms = (hipStream_t)comm_stream;
 
   const bool alone = cfg.comm_alone != 0;  // communication side only (timing)
@@ -783,7 +784,7 @@ static int gemm_rs_impl(const char* name, bool ring, tl_ctx* ctx, const void* a,
     first_rank = no_recv;
     if (cfg.tile_order != TL_ORDER_NATURAL && r.nbm % R == 0) r.first_block = first_rank * (r.nbm / R);
   }
-  p.sched = make_sched(ctx, r);
+  p.sched = make_sched(ctx, r, TL_OP_GEMM_RS);
   fill_rs_side(ctx, &p.rs, partial, peer_recv, peer_push, out, M, N, r.tile_m, r.tile_n, r.Tm_p, r.Tn_p, flags, epoch, workspace);
   if (cfg.tile_order != TL_ORDER_NATURAL) p.rs.rs_first_block = first_rank * (r.rows_per_rank / r.Tm_p);
   if (ring) {
@@ -855,7 +856,7 @@ int tl_dump_schedule(const tl_ctx* ctx, int op, const long long* dims, int* out,
   Resolved r;
   if (int e = resolve_dense(ctx, op, M, N, K, &r)) return e;
   const tl_config& cfg = ctx->cfg;
-  Sched s = make_sched(ctx, r);
+  Sched s = make_sched(ctx, r, op);
   size_t need = (op == TL_OP_AG_GEMM) ? (size_t)r.n_tiles * 8 : (size_t)r.n_tiles * 9 + (size_t)r.n_ptm * r.n_ptn * 9;
   *n = need;
   if (!out || cap < need) return fail(TL_ERR_WORKSPACE_TOO_SMALL, "tl_dump_schedule: %zu ints needed, capacity %zu", need, cap);

@@ -241,6 +241,7 @@ struct Sched {
   int group_m;      // >= 1
   int arrival_bpr = 0;  // 0, or the row blocks per rank: after the bpr blocks from first_block on (the local shard's), block j
                     // of each further rank along the ring comes before block j+1 of any
+  int busy_first = 0;   // round 0: the workgroups that also have a tile in the partial last round take the first logical tiles
 };
 
 // Die swizzle alone: the logical index of schedule position p.
@@ -248,6 +249,15 @@ __host__ __device__ inline int sched_logical(const Sched& s, int p) {
   int l = p;
   if (s.swizzle && s.G % kXcds == 0) {
     int rnd = p / s.G, w = p - rnd * s.G;
+    if (s.busy_first && rnd == 0 && s.n_tiles > s.G) {
+      // A consumer whose first tiles wait for data that arrives in logical order: the workgroups w < tail run one tile
+      // more than the others, so they get the earliest tiles [0, tail) and the others [tail, G), a run per die each.
+      const int tail = s.n_tiles % s.G;
+      if (tail && tail % kXcds == 0) {
+        const int die = w % kXcds, i = w / kXcds, tb = tail / kXcds;
+        return i < tb ? die * tb + i : tail + die * ((s.G - tail) / kXcds) + (i - tb);
+      }
+    }
     int span = s.n_tiles - rnd * s.G;
     if (span > s.G) span = s.G;
     if (span % kXcds == 0) l = rnd * s.G + (w % kXcds) * (span / kXcds) + w / kXcds;

@@ -92,6 +92,28 @@ def test_swizzle_gives_each_die_a_contiguous_run():
             assert got == list(range(rnd * G + die * 32, rnd * G + die * 32 + 32))
 
 
+def test_busy_first_swizzle_gives_the_early_tiles_to_the_workgroups_with_a_tile_more():
+    """448 tiles on 256 workgroups: workgroups 0..191 run two tiles.  In round 0 they get logical tiles 0..191 (die d the run
+    24d..24d+23), the others 192..255 (die d the run 192+8d..192+8d+7); the second round is the plain swizzle; the whole
+    thing is a permutation; with a whole number of rounds, or one round, nothing changes."""
+    G, n = 256, 448
+    pos = mp.xcd_positions(n, G, busy_first=True)
+    assert sorted(pos) == list(range(n))
+    for die in range(8):
+        busy = sorted(pos[w] for w in range(192) if w % 8 == die)
+        rest = sorted(pos[w] for w in range(192, 256) if w % 8 == die)
+        assert busy == list(range(24 * die, 24 * die + 24)) and rest == list(range(192 + 8 * die, 192 + 8 * die + 8))
+        second = sorted(pos[256 + w] for w in range(192) if w % 8 == die)
+        assert second == list(range(256 + 24 * die, 256 + 24 * die + 24))
+    assert pos[0] == 0 and pos[8] == 1 and pos[1] == 24 and pos[192] == 192 and pos[193] == 200   # hand values
+    assert pos[256:] == mp.xcd_positions(n, G)[256:]
+    for n2 in (512, 256, 200, 452):   # whole rounds, one round, less than a round, tail not a multiple of 8
+        assert mp.xcd_positions(n2, G, busy_first=True) == mp.xcd_positions(n2, G)
+    # three and a half rounds: only round 0 moves
+    p3, q3 = mp.xcd_positions(896, 256, busy_first=True), mp.xcd_positions(896, 256)
+    assert p3[256:] == q3[256:] and sorted(p3[:256]) == list(range(256)) and max(p3[w] for w in range(128)) == 127
+
+
 def test_ag_gemm_schedule_records_cover_every_tile():
     recs = mp.ag_gemm_schedule_records(8192, 3584, 8192, 8, 4, 3, 256, 224, 256)
     assert len(recs) == 512 and sorted(r[0] for r in recs) == list(range(512))
