@@ -57,8 +57,8 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     res = {}
     R = 8
 
-    def triple(make, call, flop, extra=None):
-        t = {}
+    def triple(make, call, flop, extra=None, clocks=False):
+        t, mhz = {}, {}
         for name, m, alone in (("compute_alone_ms", tl.TL_COMM_NONE, 0), ("comm_alone_ms", mode, 1), ("fused_ms", mode, 0)):
             st = make(m, alone)
             st["epoch"] = 0
@@ -69,6 +69,9 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
                 ms.wait_stream(cs)
                 call(st)
             t[name], _ = timed(fn, steps, warmup)
+            if clocks and not alone:     # shader clock of the last launch's first workgroup
+                cyc, ticks = tl.tl_read_clocks(st["ctx"], st["wsp"])
+                mhz["shader_mhz_" + name[:-3]] = round(cyc / max(ticks, 1) * 100.0, 0)
             for ctx_, wsp_ in [(st["ctx"], st["wsp"])] + st.get("also", []):
                 tl.tl_check_status(ctx_, wsp_)
                 tl.tl_ctx_destroy(ctx_)
@@ -77,6 +80,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
         r["compute_alone_tflops"] = round(flop / t["compute_alone_ms"] / 1e9, 1)
         r["frac_of_peak"] = round(flop / t["fused_ms"] / 1e9 / PEAK_BF16_TFLOPS, 4)
         r["overlap_efficiency"] = round(max(t["compute_alone_ms"], t["comm_alone_ms"]) / t["fused_ms"], 4)
+        r.update(mhz)
         if extra:
             r.update(extra)
         return r
@@ -285,7 +289,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     flop_attn = 4.0 * D * Hd * float((g + 1).sum())     # QK^T and PV over the keys a causal query sees
     res["sp_ag_attention"] = triple(at_make, at_call, flop_attn,
                                     {"workload": f"S={S} heads={Hd} head_dim={D} causal, TP=8 share, rank {rank} (keys 0..{S - 1})",
-                                     "flop_count": "4*D*heads*sum_i(position_i+1): masked pairs are not counted"})
+                                     "flop_count": "4*D*heads*sum_i(position_i+1): masked pairs are not counted"}, clocks=True)
     return res
 
 

@@ -150,7 +150,7 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
 int tl_mfma_peak_probe(tl_ctx* ctx, const void* operands /*dev*/, size_t operand_bytes, int iters, float* sink /*dev*/,
                        long long* clocks /*dev*/, void* stream, double* flop /*host*/);
 
-/* Measurement aid.  Synchronous: after a tl_ag_gemm-family or tl_gemm_rs-family call has completed, out[0] = shader-clock
+/* Measurement aid.  Synchronous: after a tl_ag_gemm-family, tl_gemm_rs-family or tl_sp_ag_attention call has completed, out[0] = shader-clock
  * cycles and out[1] = ticks of the 100 MHz wall clock during which the call's first compute workgroup was resident
  * (kept in bytes 32..47 of the workspace): out[0] / out[1] x 100 is the shader clock in MHz the tile kernel ran at.  On
  * this chip that clock depends on the operand data, so it belongs beside every throughput figure.  workspace = NULL: the
@@ -373,7 +373,8 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
  *   k_gathered / v_gathered dev [S, heads, head_dim] bf16 (written);  o dev [S/R, heads, head_dim] bf16 (written)
  *   flags dev unsigned[2*R*C]: K channels, then V channels; channel c covers positions [c*S/(R*C), (c+1)*S/(R*C)).
  *   Zeroed once by the caller; after call number `epoch` (1, 2, ...) a gathered channel holds epoch * info[4] of tl_attn_query.
- *   workspace dev, 256 bytes, zeroed once (word 0 status, words 1 and 2 the K and V producer queues).
+ *   workspace dev, 256 bytes, zeroed once (word 0 status, words 1 and 2 the K and V producer queues, bytes 32..47 the clock
+ *             sample tl_read_clocks returns).
  *   Requirements: head_dim == 128, R | S, S/(R*C) % 64 == 0, R*C <= 64, 16-byte aligned pointers.
  *   comm_mode: NONE (k_gathered / v_gathered are taken as complete), WAVES or SIDE_KERNEL.
  * Returns TL_OK or a negative error; waits are bounded as in tl_ag_gemm (tl_check_status).

@@ -84,6 +84,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
   // workgroup -> (head, query block): the query blocks of a head run on one die (workgroup w runs on die w % 8) so
   // that they share the head's K/V in that die's L2; heavy (late, for causal) query blocks first
   const int wid = blockIdx.x - p.n_comm;
+  const ClockSample cs0 = clock_sample_begin(wid);   // workgroup 0 has the heaviest query block: it runs for the whole kernel
   int head, qb;
   if (p.heads % kXcds == 0) {
     const int hpx = p.heads / kXcds, die = wid % kXcds, slot = wid / kXcds;
@@ -370,6 +371,7 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
         }
     }
   }
+  clock_sample_end(cs0, wid, p.kprod.ctl.status);
 }
 
 constexpr int kAttnQT = TL_ATTN_QT, kAttnThreads = 512 / kAttnQT;
