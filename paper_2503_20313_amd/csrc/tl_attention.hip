@@ -308,13 +308,10 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
             constexpr int g = y / (8 * QT), uu = (y / 8) % QT, i = y % 8;
             const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(c[uu][g >> 1][(g & 1) * 8 + i], p.scale_log2e, mc[uu]));
             pf[uu][g][i] = (bf16_t)pv;
-            // the row sum takes the probabilities as the matrix instruction will see them (rounded to bf16), two per
-            // instruction: one dot product with (1, 1) instead of two additions
-            if constexpr (i & 1) {
-              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-              const bf16x2 pr = {pf[uu][g][i - 1], pf[uu][g][i]}, ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-              psum[uu] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[uu], false);
-            }
+            // the row sum takes the unrounded probabilities, one plain addition each.  (A dot product of the packed pair with
+            // (1, 1) is one instruction for two values, but v_dot2c_f32_bf16 runs in the matrix pipeline: measured, each one
+            // holds up the matrix instructions for 16 cycles, whereas additions issue beside them.)
+            psum[uu] += pv;
           }
         });
         __builtin_amdgcn_sched_barrier(0);
