@@ -57,7 +57,7 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     res = {}
     R = 8
 
-    def triple(make, call, flop, extra=None, clocks=False):
+    def triple(make, call, flop, extra=None, clocks=False, mode=mode):
         t, mhz = {}, {}
         for name, m, alone in (("compute_alone_ms", tl.TL_COMM_NONE, 0), ("comm_alone_ms", mode, 1), ("fused_ms", mode, 0)):
             st = make(m, alone)
@@ -290,6 +290,11 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     res["sp_ag_attention"] = triple(at_make, at_call, flop_attn,
                                     {"workload": f"S={S} heads={Hd} head_dim={D} causal, TP=8 share, rank {rank} (keys 0..{S - 1})",
                                      "flop_count": "4*D*heads*sum_i(position_i+1): masked pairs are not counted"}, clocks=True)
+    # the same with K and V gathered by the copy engines (the binding of the paper's AG-KV + attention kernel): on one GPU
+    # copying onto itself the engines move ~0.37 TB/s, so this measures the binding, not what links would deliver
+    res["sp_ag_attention_copy_engine"] = triple(at_make, at_call, flop_attn,
+                                                {"workload": f"as sp_ag_attention, K/V shards copied by hipMemcpyAsync(..., hipMemcpyDeviceToDeviceNoCU) "
+                                                             f"on the communication stream + a notify kernel per shard"}, mode=tl.TL_COMM_COPY_ENGINE)
     return res
 
 

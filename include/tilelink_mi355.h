@@ -376,7 +376,12 @@ int tl_moe_gemm_scatter_rs(tl_ctx* ctx, const void* x2, const void* w2, const in
  *   workspace dev, 256 bytes, zeroed once (word 0 status, words 1 and 2 the K and V producer queues, bytes 32..47 the clock
  *             sample tl_read_clocks returns).
  *   Requirements: head_dim == 128, R | S, S/(R*C) % 64 == 0, R*C <= 64, 16-byte aligned pointers.
- *   comm_mode: NONE (k_gathered / v_gathered are taken as complete), WAVES or SIDE_KERNEL.
+ *   comm_mode: NONE (k_gathered / v_gathered are taken as complete), WAVES, SIDE_KERNEL, or COPY_ENGINE: every needed
+ *   shard of K, then of V, is copied on comm_stream by the runtime's copy engines (rank_copy_data: a copy kind that keeps
+ *   the compute units out of it), each copy followed by a small kernel that raises the shard's C channel flags by one
+ *   (rank_notify; info[4] of tl_attn_query is 1 in this mode) -- the binding of the paper's AG KV + self-attention
+ *   kernel.  link_gbps must be 0 with it.  (The plain stream binding of tl_ag_gemm is not offered: the runtime's copy
+ *   kernels could not become resident beside attention workgroups that hold every compute unit while waiting for them.)
  * Returns TL_OK or a negative error; waits are bounded as in tl_ag_gemm (tl_check_status).
  */
 int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards /*host array of dev*/,

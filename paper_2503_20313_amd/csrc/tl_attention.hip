@@ -147,6 +147,15 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
     if (!p.do_wait) return;
     int row = blk * kBKV;
     if (row % p.rows_per_channel != 0) return;
+    if (p.do_wait == 2) {   // flags raised after copies of the runtime (no producer queue to help with): plain wait
+      const int ch = row / p.rows_per_channel;
+      if (tid == 0) {
+        tile_wait(p.kprod.flags + ch, p.kprod.wait_target, p.kprod.ctl, ch);
+        tile_wait(p.vprod.flags + ch, p.vprod.wait_target, p.vprod.ctl, p.n_channels + ch);
+      }
+      __syncthreads();
+      return;
+    }
     unsigned long long m = 1ull << (row / p.rows_per_channel);
     consumer_wait_or_produce(p.kprod, m, tid, NT, &s_ticket);
     consumer_wait_or_produce(p.vprod, m, tid, NT, &s_ticket);
@@ -373,6 +382,12 @@ __global__ void __launch_bounds__(512 / QT) sp_attention_kernel(const AttnParams
 
 constexpr int kAttnQT = TL_ATTN_QT, kAttnThreads = 512 / kAttnQT;
 
+// rank_notify for a shard copied by the runtime: raise `count` consecutive channel flags by one.
+__global__ void kv_notify_kernel(unsigned* flags, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) tile_notify(flags + i, 1u);
+}
+
 __global__ void __launch_bounds__(256) kv_producer_kernel(const AgProducer k, const AgProducer v) {
   __shared__ int s_ticket;
   if (blockIdx.x & 1) { ag_producer(v, threadIdx.x, 256, &s_ticket); ag_producer(k, threadIdx.x, 256, &s_ticket); }
@@ -406,9 +421,9 @@ static int resolve_attn(const tl_ctx* ctx, int S, int heads, int head_dim, int c
   r->Tm_p = Tm_p;
   r->shards_needed = causal ? c.rank + 1 : R;   // causal: keys after this rank's positions are never read
   r->n_ptm = r->shards_needed * (r->S_loc / Tm_p);
-  r->expected = r->rows_per_channel / Tm_p;
+  r->expected = c.comm_mode == TL_COMM_COPY_ENGINE ? 1 : r->rows_per_channel / Tm_p;   // one notification per channel after a shard's copy
   r->n_comm = c.comm_workgroups > 0 ? c.comm_workgroups : (c.comm_mode == TL_COMM_WAVES ? 16 : 128);
-  if (c.comm_mode == TL_COMM_NONE) r->n_comm = 0;
+  if (c.comm_mode == TL_COMM_NONE || c.comm_mode == TL_COMM_COPY_ENGINE) r->n_comm = 0;
   return TL_OK;
 }
 
@@ -444,8 +459,12 @@ int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, 
   for (int s = 0; s < R; s++)
     if (!k_shards[s] || !v_shards[s] || !aligned16(k_shards[s]) || !aligned16(v_shards[s]))
       return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: k_shards[%d] or v_shards[%d] is null or misaligned", s, s);
-  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL || cfg.comm_mode == TL_COMM_COPY_ENGINE)
-    return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: comm_mode must be NONE, WAVES or SIDE_KERNEL");
+  // (TL_COMM_STREAM is not offered: the runtime's copy kernels would have to become resident beside attention workgroups
+  // that hold every compute unit while they wait for exactly those copies)
+  if (cfg.comm_mode == TL_COMM_STREAM || cfg.comm_mode == TL_COMM_EXTERNAL)
+    return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: comm_mode must be NONE, WAVES, SIDE_KERNEL or COPY_ENGINE");
+  if (cfg.comm_mode == TL_COMM_COPY_ENGINE && cfg.link_gbps > 0)
+    return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: simulated links need the library's own producers (WAVES or SIDE_KERNEL)");
 
   AttnParams p;
   memset(&p, 0, sizeof p);
@@ -489,6 +508,22 @@ int tl_sp_ag_attention(tl_ctx* ctx, const void* q, const void* const* k_shards, 
       hipLaunchKernelGGL(kv_producer_kernel, dim3(r.n_comm), dim3(256), 0, ms, p.kprod, p.vprod);
       TL_HIP(hipGetLastError());
       return alone ? TL_OK : launch(n_wg);
+    case TL_COMM_COPY_ENGINE: {
+      // rank_copy_data + rank_notify per source rank on the communication stream, in the order the keys are consumed:
+      // the copy kind that keeps the compute units out of it (the runtime hands it to a copy engine), then a small
+      // kernel that raises the shard's K (or V) channel flags
+      p.n_comm = 0; p.do_wait = 2;
+      p.kprod.wait_target = p.vprod.wait_target = epoch;
+      const size_t shard_bytes = (size_t)r.S_loc * ld * sizeof(bf16_t);
+      for (int s = 0; s < r.shards_needed; s++) {
+        TL_HIP(hipMemcpyAsync((char*)k_gathered + (size_t)s * shard_bytes, k_shards[s], shard_bytes, hipMemcpyDeviceToDeviceNoCU, ms));
+        hipLaunchKernelGGL(kv_notify_kernel, dim3((r.C + 63) / 64), dim3(64), 0, ms, flags + s * r.C, r.C);
+        TL_HIP(hipMemcpyAsync((char*)v_gathered + (size_t)s * shard_bytes, v_shards[s], shard_bytes, hipMemcpyDeviceToDeviceNoCU, ms));
+        hipLaunchKernelGGL(kv_notify_kernel, dim3((r.C + 63) / 64), dim3(64), 0, ms, flags + RC + s * r.C, r.C);
+        TL_HIP(hipGetLastError());
+      }
+      return alone ? TL_OK : launch(n_wg);
+    }
   }
   return fail(TL_ERR_INVALID_ARG, "tl_sp_ag_attention: unknown comm_mode");
 }

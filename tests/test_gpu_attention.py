@@ -12,7 +12,7 @@ from oracle import ops
 from tests.gpu_util import assert_close_bf16, dev, down, make_ctx, poison, up
 
 pytestmark = pytest.mark.gpu
-MODES = {"none": tl.TL_COMM_NONE, "waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL}
+MODES = {"none": tl.TL_COMM_NONE, "waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "copy_engine": tl.TL_COMM_COPY_ENGINE}
 POISON = 0x7FC0
 
 
@@ -69,7 +69,7 @@ def check_gathered(w, res, rank, causal, C, epochs=1):
     assert np.array_equal(res["flags"], exp)
 
 
-@pytest.mark.parametrize("mode", ["none", "waves", "side"])
+@pytest.mark.parametrize("mode", ["none", "waves", "side", "copy_engine"])
 @pytest.mark.parametrize("causal", [True, False])
 def test_small(mode, causal):
     w = wl.sp_attention_inputs(512, 2, 128, 2, config_id=51)
@@ -125,7 +125,7 @@ def test_single_key_rows():
     assert np.array_equal(res["o"][0], w["v_shards"][0][0])
 
 
-@pytest.mark.parametrize("mode", ["waves", "side"])
+@pytest.mark.parametrize("mode", ["waves", "side", "copy_engine"])
 def test_epochs_reuse_flags(mode):
     w = wl.sp_attention_inputs(1024, 4, 128, 4, config_id=55)
     res = run_attention(w, 2, True, MODES[mode], C=2, epochs=3)
@@ -171,7 +171,7 @@ def test_invalid_arguments():
     tl.tl_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("rank,mode", [(7, "side"), (3, "waves"), (0, "side")])
+@pytest.mark.parametrize("rank,mode", [(7, "side"), (3, "waves"), (0, "side"), (7, "copy_engine")])
 def test_full_size_sampled(rank, mode):
     """Config 5 (S=32768, 32 heads, head_dim 128, TP=8, causal) in the launch configuration the bench uses.  The oracle
     computes EVERY head on rows of EVERY one of the 16 query blocks (a workgroup owns one head and 256 queries, a wave 32
