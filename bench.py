@@ -50,7 +50,7 @@ def cpu_baseline(np, ops, w2, w3, rank):
                       f"best of {passes} passes: {best:.1f} s ({time.time() - t_all:.1f} s in all)"}
 
 
-def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push, comm_wgs=0):
+def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direct_push, comm_wgs=0, copy_engine=False):
     """Secondary measurements, outside the timed step: the two MoE halves (configuration 4) and sequence-parallel
     attention (configuration 5, causal, the last rank = the one with the most keys), each fused, compute alone
     (communication off, gathered inputs complete) and communication alone."""
@@ -290,11 +290,14 @@ def extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode, steps, warmup, direc
     res["sp_ag_attention"] = triple(at_make, at_call, flop_attn,
                                     {"workload": f"S={S} heads={Hd} head_dim={D} causal, TP=8 share, rank {rank} (keys 0..{S - 1})",
                                      "flop_count": "4*D*heads*sum_i(position_i+1): masked pairs are not counted"}, clocks=True)
-    # the same with K and V gathered by the copy engines (the binding of the paper's AG-KV + attention kernel): on one GPU
-    # copying onto itself the engines move ~0.37 TB/s, so this measures the binding, not what links would deliver
-    res["sp_ag_attention_copy_engine"] = triple(at_make, at_call, flop_attn,
-                                                {"workload": f"as sp_ag_attention, K/V shards copied by hipMemcpyAsync(..., hipMemcpyDeviceToDeviceNoCU) "
-                                                             f"on the communication stream + a notify kernel per shard"}, mode=tl.TL_COMM_COPY_ENGINE)
+    # the same with K and V gathered by the copy engines (the binding of the paper's AG-KV + attention kernel; with
+    # --comm-mode copy_engine only: a profiler that serialises kernels would hold the notify kernels back behind the
+    # attention kernel that waits for them).  On one GPU copying onto itself the engines move ~0.5 TB/s, so this measures
+    # the binding, not what links would deliver
+    if copy_engine:
+        res["sp_ag_attention_copy_engine"] = triple(at_make, at_call, flop_attn,
+                                                    {"workload": "as sp_ag_attention, K/V shards copied by hipMemcpyAsync(..., hipMemcpyDeviceToDeviceNoCU) "
+                                                                 "on the communication stream + a notify kernel per shard"}, mode=tl.TL_COMM_COPY_ENGINE)
     return res
 
 
@@ -768,7 +771,8 @@ def main():
                                     "link_time_ms": round((M // R) * K * 2 / 153e9 * 1e3, 4), "tile_order": "arrival", "ag_k_chunks": 1}
     if not args.no_extras:
         out["extras"] = extras(torch, np, tl, wl, dev, up, timed, cs, ms, mode if mode not in STREAMED else tl.TL_COMM_SIDE_KERNEL,
-                               args.steps, args.warmup, 0 if args.no_direct_push else 1, args.comm_workgroups)
+                               args.steps, args.warmup, 0 if args.no_direct_push else 1, args.comm_workgroups,
+                               copy_engine=mode == tl.TL_COMM_COPY_ENGINE)
     if not args.no_cpu_baseline:
         from oracle import ops as oracle_ops
         out["cpu_baseline"] = cpu_baseline(np, oracle_ops, w2, w3, rank)
