@@ -342,7 +342,9 @@ def shape_table(torch, tl, dev, timed, cs, ms, mode, steps, warmup, over_ag=None
         return r
 
     def dense_ctx(m, alone, op, dims, C):
-        over = (over_ag if op == tl.TL_OP_AG_GEMM else over_rs) or {}
+        over = dict((over_ag if op == tl.TL_OP_AG_GEMM else over_rs) or {})
+        if callable(over.get("ag_k_chunks")):
+            over["ag_k_chunks"] = over["ag_k_chunks"](dims)
         ctx = tl.tl_ctx_create(world_size=R, rank=0, channels_per_rank=C, comm_mode=m, tile_order=tl.TL_ORDER_OWN_FIRST, xcd_swizzle=1,
                                spin_timeout_us=10_000_000, comm_alone=alone, rs_direct_push=1,
                                **{k: v for k, v in over.items() if m != tl.TL_COMM_NONE or k in ("tile_m", "tile_n")})
@@ -479,7 +481,9 @@ def main():
     ap.add_argument("--comm-workgroups", type=int, default=0)
     ap.add_argument("--channels", type=int, default=4)
     ap.add_argument("--ag-comm-tile-m", type=int, default=0, help="rows of an AllGather producer tile (default: the library's choice)")
-    ap.add_argument("--ag-k-chunks", type=int, default=1, help="chunks per AllGather channel along K, each with a flag of its own (1 = one flag per channel)")
+    ap.add_argument("--ag-k-chunks", type=int, default=0,
+                    help="chunks per AllGather channel along K, each with a flag of its own (1 = one flag per channel; 0 = this script's choice: "
+                         "4 where all tiles of the GEMM fit into one round of workgroups -- every tile then starts with a wait --, else 1)")
     ap.add_argument("--link-gbps", type=int, default=0, help="simulated link rate per source rank for the AllGather (0 = unthrottled local copy; xGMI: 153)")
     ap.add_argument("--ag-order", default="own_first", choices=["own_first", "arrival"], help="tile order of AG+GEMM")
     ap.add_argument("--ag-tile", default="", help="compute tile of AG+GEMM as MxN (default: the library's choice)")
@@ -555,13 +559,23 @@ def main():
     cs = torch.cuda.Stream()
     ms = torch.cuda.Stream()
 
+    def pick_k_chunks(asked, dims, workgroups=256):
+        """K chunks of the AllGather for a [M,N,K] GEMM: what was asked for, else 4 where one round of 256x256 tiles holds the
+        whole GEMM (every tile then waits for remote rows before it can start, and starting on the first quarter of K is
+        worth 6-10 %: the MLP-1..3 shares), else 1 (with more rounds chunks cost a few per cent)."""
+        if asked:
+            return asked
+        m, n, k = dims
+        one_round = -(-m // 256) * -(-n // 256) <= workgroups
+        return 4 if one_round and k % 256 == 0 and k // 256 >= 8 else 1
+
     class Op:
         def __init__(self, op, dims, comm_mode, comm_alone=0, **over):
             tile = (args.ag_tile if op == tl.TL_OP_AG_GEMM else args.rs_tile) or "0x0"
             tm, tn = (int(v) for v in tile.split("x"))
             fields = dict(world_size=R, rank=rank, channels_per_rank=args.channels, comm_mode=comm_mode, tile_m=tm, tile_n=tn,
                           comm_tile_m=args.ag_comm_tile_m if op == tl.TL_OP_AG_GEMM else 0,
-                          ag_k_chunks=args.ag_k_chunks if op == tl.TL_OP_AG_GEMM and comm_mode not in STREAMED else 0,
+                          ag_k_chunks=pick_k_chunks(args.ag_k_chunks, dims) if op == tl.TL_OP_AG_GEMM and comm_mode not in STREAMED else 0,
                           link_gbps=args.link_gbps if op == tl.TL_OP_AG_GEMM and comm_mode not in STREAMED else 0,
                           comm_workgroups=args.comm_workgroups, xcd_swizzle=1,
                           tile_order=tl.TL_ORDER_ARRIVAL if op == tl.TL_OP_AG_GEMM and args.ag_order == "arrival" else tl.TL_ORDER_OWN_FIRST,
@@ -627,7 +641,7 @@ def main():
     if args.shape_table:
         del shards, gathered, a_full, b2, c2, a3, b3, a3_src, partial, recv, push, out3
         table = shape_table(torch, tl, dev, timed, cs, ms, mode if mode not in STREAMED else tl.TL_COMM_SIDE_KERNEL, min(args.steps, 20), 3,
-                            over_ag=dict(ag_k_chunks=args.ag_k_chunks, comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups,
+                            over_ag=dict(ag_k_chunks=lambda dims: pick_k_chunks(args.ag_k_chunks, dims), comm_tile_m=args.ag_comm_tile_m, comm_workgroups=args.comm_workgroups,
                                          tile_m=int((args.ag_tile or "0x0").split("x")[0]), tile_n=int((args.ag_tile or "0x0").split("x")[1])),
                             over_rs=dict(comm_tile_m=args.rs_comm_tile_m, comm_workgroups=args.comm_workgroups), only=args.shape_filter)
         print(json.dumps({"shape_table": table, "data": "synthetic", "dtype": "bf16", "n_gpus": 1}))
@@ -739,7 +753,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "MLP-5 TP=8 share: AG+GEMM 8x[1024,8192]->[8192,8192]x[8192,3584] then GEMM+RS [8192,3584]x[3584,8192]->[1024,8192]",
                    "world_size": R, "rank": rank, "comm_mode": args.comm_mode, "channels_per_rank": args.channels,
-                   "rs_direct_push": 0 if args.no_direct_push else args.direct_push_mode, "ag_k_chunks": args.ag_k_chunks, "ag_order": args.ag_order, "link_gbps": args.link_gbps},
+                   "rs_direct_push": 0 if args.no_direct_push else args.direct_push_mode, "ag_k_chunks": ops_["ag_gemm"].info["k_chunks"], "ag_order": args.ag_order, "link_gbps": args.link_gbps},
         "overlap_efficiency": round(min(res["ag_gemm"]["overlap_efficiency"], res["gemm_rs"]["overlap_efficiency"]), 4),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "ops": res,
