@@ -27,17 +27,19 @@ def sample_columns(N, n, seed):
     return np.array(sorted(cols))
 
 
-@pytest.mark.parametrize("name,rank", [("MLP-1", 3), ("MLP-2", 6), ("MLP-4", 0), ("MLP-6", 7)])
-def test_ag_gemm_mlp_shares(name, rank):
+@pytest.mark.parametrize("name,rank,kc", [("MLP-1", 3, 4), ("MLP-2", 6, 4), ("MLP-3", 1, 4), ("MLP-4", 0, 1), ("MLP-6", 7, 1)])
+def test_ag_gemm_mlp_shares(name, rank, kc):
+    """kc = flags per AllGather channel along K as bench.py chooses them: four where one round of tiles holds the whole GEMM."""
     S, H, I = MLP[name]
     N = I // R                                       # 1376, 4608, 3696: the last two column tiles are ragged for 1376 and 3696
     w = wl.ag_gemm_inputs(S, N, H, R, config_id=60 + rank)
-    hs, g, c, flags, info = run_ag_gemm(w, rank, 4, tl.TL_COMM_SIDE_KERNEL, tile_order=tl.TL_ORDER_OWN_FIRST)
+    hs, g, c, flags, info = run_ag_gemm(w, rank, 4, tl.TL_COMM_SIDE_KERNEL, tile_order=tl.TL_ORDER_OWN_FIRST, ag_k_chunks=kc)
+    assert info["k_chunks"] == kc
     cols = sample_columns(N, 384, 600 + rank)
     a_ref, _, c_ref = ops.ag_gemm(hs, np.ascontiguousarray(w["b"][:, cols]))
     assert np.array_equal(g, a_ref)
     assert_close_bf16(c[:, cols], c_ref, f"AG+GEMM {name} share rank {rank} tile {info['tile_m']}x{info['tile_n']}")
-    assert flags.tolist() == [info["expected_per_channel"]] * (R * 4)
+    assert flags.tolist() == [info["expected_per_channel"]] * (R * 4 * kc)
 
 
 @pytest.mark.parametrize("name,rank,direct", [("MLP-1", 5, 1), ("MLP-2", 4, 1), ("MLP-3", 0, 0), ("MLP-6", 2, 1)])
