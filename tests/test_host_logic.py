@@ -106,3 +106,59 @@ def test_moe_and_attention_geometry_queries():
     a = tl.tl_attn_query(ctx, 32768, 32, 128, True)
     assert a["n_flags"] == 16 and a["shards_gathered"] == 8 and a["attention_workgroups"] == 16 * 32
     tl.tl_ctx_destroy(ctx)
+
+
+def test_schedules_match_the_mapping_oracle_on_seeded_random_shapes():
+    """200 seeded draws of (shape, world, channels, rank, tile, order, swizzle, group, grid size, compute units): every
+    AllGather + GEMM and GEMM + ReduceScatter schedule the library dumps is the mapping oracle's, record by record -- whole
+    and partial rounds, grids that are no multiple of the eight dies, ragged last tiles, every tile order."""
+    import numpy as np
+    rng = np.random.Generator(np.random.Philox(20313))
+    tiles = [(256, 256), (256, 224), (128, 128)]
+    checked = 0
+    for _ in range(200):
+        R = int(rng.choice([1, 2, 4, 8]))
+        C = int(rng.choice([1, 2, 4]))
+        tm, tn = tiles[int(rng.integers(len(tiles)))]
+        rows_per_channel = int(rng.choice([64, 128, 256, 512]))
+        M = R * C * rows_per_channel
+        N = int(rng.integers(1, 40)) * 64 + int(rng.choice([0, 8, 200]))
+        K = int(rng.integers(1, 64)) * 64
+        rank = int(rng.integers(R))
+        order = int(rng.choice([tl.TL_ORDER_NATURAL, tl.TL_ORDER_RING, tl.TL_ORDER_OWN_FIRST, tl.TL_ORDER_ARRIVAL]))
+        swz, gm = int(rng.integers(2)), int(rng.choice([0, 1, 2, 3, 8]))
+        cus = int(rng.choice([256, 64, 40, 304]))
+        G = int(rng.choice([0, 0, 24, 100]))
+        ctx = tl.tl_ctx_create_host(cus, world_size=R, rank=rank, channels_per_rank=C, comm_mode=tl.TL_COMM_SIDE_KERNEL, tile_order=order,
+                                    xcd_swizzle=swz, group_m=gm, tile_m=tm, tile_n=tn, compute_workgroups=G)
+        try:
+            info = tl.tl_resolve(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
+        except tl.TileLinkError:
+            tl.tl_ctx_destroy(ctx)
+            continue
+        got = tl.tl_dump_schedule(ctx, tl.TL_OP_AG_GEMM, [M, N, K])
+        want = omap.ag_gemm_schedule_records(M, N, K, R, C, rank, info["tile_m"], info["tile_n"], info["compute_workgroups"],
+                                             rotate=order != tl.TL_ORDER_NATURAL, swizzle=bool(swz), group_m=info["group_m"],
+                                             arrival=order == tl.TL_ORDER_ARRIVAL)
+        assert got == [v for rec in want for v in rec], (M, N, K, R, C, rank, tm, tn, order, swz, gm, cus, G)
+        checked += 1
+        if order != tl.TL_ORDER_ARRIVAL:
+            try:
+                info = tl.tl_resolve(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+            except tl.TileLinkError:
+                tl.tl_ctx_destroy(ctx)
+                continue
+            got = tl.tl_dump_schedule(ctx, tl.TL_OP_GEMM_RS, [M, N, K])
+            rot, own = order != tl.TL_ORDER_NATURAL, order == tl.TL_ORDER_OWN_FIRST
+            Tm_r, Tn_r = info["comm_tile_m"], info["comm_tile_n"]
+            gemm = omap.gemm_rs_schedule_records(M, N, K, R, rank, info["tile_m"], info["tile_n"], Tm_r, Tn_r, info["compute_workgroups"], rot,
+                                                 bool(swz), info["group_m"], own)
+            table = omap.rs_tile_table(M, N, R, rank, info["tile_m"], info["tile_n"], Tm_r, Tn_r)
+            want = [v for rec in gemm for v in rec]
+            for t in omap.rs_consumer_order(M, N, R, rank, Tm_r, Tn_r, rot, own):
+                cm, cn, rlo, rhi, clo, chi, dest, exp = table[t]
+                want += [t, cm, cn, rlo, rhi, clo, chi, dest, exp]
+            assert got == want, ("rs", M, N, K, R, C, rank, tm, tn, order, swz, gm, cus, G)
+            checked += 1
+        tl.tl_ctx_destroy(ctx)
+    assert checked >= 150
