@@ -497,6 +497,9 @@ def main():
     ap.add_argument("--fused-only", action="store_true",
                     help="launch nothing but fused steps (clock settling included) and report their times: the run to put under "
                          "rocprofv3 --kernel-trace --stats, whose per-kernel averages then are those of the fused launches alone")
+    ap.add_argument("--probes", action="store_true",
+                    help="run only the issue probe (tl_issue_probe): time per slot of one MFMA plus a few vector instructions, two waves per "
+                         "SIMD, zero operands (pinned clock), for every mode with and without the MFMA")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (MoE halves, sequence-parallel attention); they are outside the timed step")
     ap.add_argument("--shape-table", action="store_true",
@@ -527,6 +530,34 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
+        return
+    if args.probes:
+        ctx = tl.tl_ctx_create(world_size=1, rank=0, channels_per_rank=1)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.zeros(1 + cus * 512, dtype=torch.float32, device=dev)
+        clk = torch.zeros(2, dtype=torch.int64, device=dev)
+        st = torch.cuda.Stream()
+        names = {0: "nothing", 1: "6 v_fma_f32", 2: "2 v_exp_f32", 3: "v_cvt_pk_bf16_f32 + v_max3_f32", 4: "1 v_dot2c_f32_bf16"}
+        res = {}
+        for with_mfma in (1, 0):
+            for m, what in names.items():
+                if not with_mfma and m == 0:
+                    continue
+                times = []
+                for rep in range(4):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(st)
+                    slots = tl.tl_issue_probe(ctx, with_mfma, m, 20000, sink, clk, st)
+                    e1.record(st)
+                    torch.cuda.synchronize()
+                    times.append(e0.elapsed_time(e1))
+                cyc, ticks = clk.cpu().tolist()
+                ms_ = min(times[1:])
+                res[("mfma + " if with_mfma else "") + what] = {"ms": round(ms_, 4), "ns_per_slot_pair": round(ms_ * 1e6 / slots, 2),
+                                                                "shader_mhz": round(cyc / max(ticks, 1) * 100.0, 0)}
+        tl.tl_ctx_destroy(ctx)
+        print(json.dumps({"issue_probe": res, "note": "two waves per SIMD, 160000 slots per wave; ns_per_slot_pair = launch time / slots per wave = the "
+                                                      "time a SIMD spends on one slot of each of its two waves; one MFMA alone is 32 cycles"}))
         return
     mode = {"waves": tl.TL_COMM_WAVES, "side": tl.TL_COMM_SIDE_KERNEL, "stream": tl.TL_COMM_STREAM, "copy_engine": tl.TL_COMM_COPY_ENGINE}[args.comm_mode]
     STREAMED = (tl.TL_COMM_STREAM, tl.TL_COMM_COPY_ENGINE)

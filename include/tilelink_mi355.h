@@ -150,6 +150,16 @@ int tl_check_status(tl_ctx* ctx, void* workspace /*dev*/);
 int tl_mfma_peak_probe(tl_ctx* ctx, const void* operands /*dev*/, size_t operand_bytes, int iters, float* sink /*dev*/,
                        long long* clocks /*dev*/, void* stream, double* flop /*host*/);
 
+/* Measurement aid: what a SIMD issues beside a running matrix instruction.  Enqueues on `stream` a kernel of one 512-thread
+ * workgroup per compute unit (two waves per SIMD) whose waves run `iters` x 8 slots; a slot is one 32x32x16 bf16 matrix
+ * instruction (left out if with_mfma == 0) followed by the vector instructions of `mode`: 0 none, 1 six v_fma_f32, 2 two
+ * v_exp_f32, 3 v_cvt_pk_bf16_f32 + v_max3_f32, 4 one v_dot2c_f32_bf16.  All operands are zero, so the chip's power limit
+ * plays no part and the clock stays at its maximum: the caller times the launch (events on `stream`) and compares modes.
+ *   sink dev float[1 + num_compute_units * 512] (sink[0] is read, all are written); clocks dev long long[2] (cycles and
+ *   100 MHz ticks of the first workgroup); *slots (host, optional) = slots per wave.  No paper passage defines this. */
+int tl_issue_probe(tl_ctx* ctx, int with_mfma, int mode, int iters, float* sink /*dev*/, long long* clocks /*dev*/, void* stream,
+                   double* slots /*host*/);
+
 /* Measurement aid.  Synchronous: after a tl_ag_gemm-family, tl_gemm_rs-family or tl_sp_ag_attention call has completed, out[0] = shader-clock
  * cycles and out[1] = ticks of the 100 MHz wall clock during which the call's first compute workgroup was resident
  * (kept in bytes 32..47 of the workspace): out[0] / out[1] x 100 is the shader clock in MHz the tile kernel ran at.  On

@@ -56,6 +56,7 @@ _lib.tl_query_workspace.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), 
 _lib.tl_check_status.argtypes = [_vp, _vp]
 _lib.tl_read_clocks.argtypes = [_vp, _vp, ctypes.POINTER(ctypes.c_longlong)]
 _lib.tl_mfma_peak_probe.argtypes = [_vp, _vp, _sz, _i, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+_lib.tl_issue_probe.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
 _lib.tl_resolve.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i)]
 _lib.tl_dump_schedule.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_i), _sz, ctypes.POINTER(_sz)]
 _lib.tl_ag_gemm.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _vp, _u, _vp, _sz, _vp, _vp]
@@ -144,6 +145,13 @@ def tl_query_workspace(ctx, op, dims):
 
 def tl_check_status(ctx, workspace):
     _check(_lib.tl_check_status(ctx, _ptr(workspace)))
+
+
+def tl_issue_probe(ctx, with_mfma, mode, iters, sink, clocks, stream=None):
+    """Enqueues the issue probe (one MFMA per slot plus the vector instructions of `mode`); returns the slots per wave."""
+    slots = ctypes.c_double()
+    _check(_lib.tl_issue_probe(ctx, int(with_mfma), int(mode), int(iters), _ptr(sink), _ptr(clocks), _stream(stream), ctypes.byref(slots)))
+    return slots.value
 
 
 def tl_read_clocks(ctx, workspace):

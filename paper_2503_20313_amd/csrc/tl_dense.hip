@@ -234,6 +234,62 @@ __global__ void __launch_bounds__(512) mfma_peak_kernel(const u32x4* __restrict_
   }
 }
 
+// Issue probe: what a SIMD issues beside a running matrix instruction.  One slot = one 32x32x16 bf16 MFMA (two
+// accumulators in turn; MFMA = 0 leaves it out) followed by MODE's vector instructions, written out so that the compiler
+// neither merges nor moves them: 1 = six v_fma_f32, 2 = two v_exp_f32, 3 = v_cvt_pk_bf16_f32 + v_max3_f32,
+// 4 = one v_dot2c_f32_bf16, 0 = nothing.  All operands are zero: the chip draws little power, the clock stays at its
+// maximum, and time per slot compares across modes in cycles.  The first workgroup leaves its clock sample in `clocks`.
+template <int MFMA, int MODE>
+__global__ void __launch_bounds__(512) issue_probe_kernel(float* __restrict__ sink, int iters, long long* clocks) {
+  floatx16 c0, c1;
+#pragma unroll
+  for (int e = 0; e < 16; e++) { c0[e] = 0.f; c1[e] = 0.f; }
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; e++) { a[e] = (bf16_t)0.f; b[e] = (bf16_t)0.f; }
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) x[e] = 0.f;
+  float k1 = sink[0] * 0.f, k2 = 0.f, acc = 0.f;   // (a value the compiler cannot fold)
+  unsigned pk = 0;
+  const long long t0 = clock64();
+  const unsigned long long w0 = wall_clock64();
+  for (int i = 0; i < iters; i++) {
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+      if constexpr (MFMA != 0) {
+        if (s & 1) c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        else c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+      }
+      if constexpr (MODE == 1) {
+#pragma unroll
+        for (int v = 0; v < 6; v++) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[v]) : "v"(k1), "v"(k2));
+      } else if constexpr (MODE == 2) {
+        asm volatile("v_exp_f32 %0, %1" : "=v"(x[0]) : "v"(x[1]));
+        asm volatile("v_exp_f32 %0, %1" : "=v"(x[2]) : "v"(x[3]));
+      } else if constexpr (MODE == 3) {
+        asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(x[0]), "v"(x[1]));
+        asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(x[2]) : "v"(x[3]), "v"(k2));
+      } else if constexpr (MODE == 4) {
+        asm volatile("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "v"(pk), "v"(0x3f803f80u));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const long long t1 = clock64();
+  const unsigned long long w1 = wall_clock64();
+  float sum = acc + __uint_as_float(pk);
+#pragma unroll
+  for (int e = 0; e < 16; e++) sum += c0[e] + c1[e];
+#pragma unroll
+  for (int e = 0; e < 8; e++) sum += x[e];
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = sum;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    clocks[0] = t1 - t0;
+    clocks[1] = (long long)(w1 - w0);
+  }
+}
+
 // Simulated peers: peer q's push of every tile of this rank's segment "arrives".
 __global__ void peers_arrive_kernel(unsigned* arrived, int tiles_per_seg, int R, int rank) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -590,6 +646,24 @@ int tl_mfma_peak_probe(tl_ctx* ctx, const void* operands, size_t operand_bytes, 
   hipLaunchKernelGGL(mfma_peak_kernel, dim3(ctx->num_cus), dim3(512), 0, (hipStream_t)stream, (const u32x4*)operands, sink, iters, clocks);
   TL_HIP(hipGetLastError());
   if (flop) *flop = (double)ctx->num_cus * 8.0 * iters * 8.0 * 32768.0;   // workgroups x waves x iterations x MFMAs x (2 x 32 x 32 x 16)
+  return TL_OK;
+}
+
+int tl_issue_probe(tl_ctx* ctx, int with_mfma, int mode, int iters, float* sink, long long* clocks, void* stream, double* slots) {
+  if (int e = check_op_ctx(ctx)) return e;
+  if (!sink || !clocks || iters <= 0) return fail(TL_ERR_INVALID_ARG, "tl_issue_probe: null pointer or non-positive iteration count");
+  if (mode < 0 || mode > 4) return fail(TL_ERR_INVALID_ARG, "tl_issue_probe: mode %d outside [0,4]", mode);
+  const dim3 grid(ctx->num_cus), block(512);
+  hipStream_t st = (hipStream_t)stream;
+#define TL_PROBE(M, D) hipLaunchKernelGGL((issue_probe_kernel<M, D>), grid, block, 0, st, sink, iters, clocks)
+  if (with_mfma) {
+    switch (mode) { case 0: TL_PROBE(1, 0); break; case 1: TL_PROBE(1, 1); break; case 2: TL_PROBE(1, 2); break; case 3: TL_PROBE(1, 3); break; default: TL_PROBE(1, 4); }
+  } else {
+    switch (mode) { case 0: TL_PROBE(0, 0); break; case 1: TL_PROBE(0, 1); break; case 2: TL_PROBE(0, 2); break; case 3: TL_PROBE(0, 3); break; default: TL_PROBE(0, 4); }
+  }
+#undef TL_PROBE
+  TL_HIP(hipGetLastError());
+  if (slots) *slots = (double)iters * 8.0;   // slots per wave; every SIMD runs two waves
   return TL_OK;
 }
 
